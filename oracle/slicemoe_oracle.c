@@ -1,0 +1,351 @@
+/*
+ * CPU oracle for the SliceMoE layer forward pass.  TEST INFRASTRUCTURE ONLY.
+ *
+ * Plain, slow, fp64.  It follows the layer's definition (paper Section 3, Section 3.1,
+ * Eq. 1) slice by slice with no grouping, tiling or fusion; the grouped execution the
+ * paper describes in Section 3.4 only reorders independent per-slice work, so it reaches
+ * exactly this result.  Only tests, the smoke check and the benchmark's CPU-baseline leg
+ * may call this file; the product path never does, and the two share no code.
+ *
+ * Conventions (the paper is silent on some of these; they are the stated readings):
+ *   - slice n = t*S + s is the contiguous segment h[t, s*ds : (s+1)*ds]  (Section 3), so the
+ *     slice view of a row-major h[T, d] is simply x[Ns, ds] with Ns = T*S.
+ *   - Linear layers are y = x W + b with W stored [in, out] row-major; both router layers
+ *     and both expert layers have biases.
+ *   - router: g = ReLU(x Wr1 + br1) Wr2 + br2;  p = softmax(g) over all E experts
+ *     (temperature 1, Appendix B default), NOT renormalised over the selected k.
+ *   - top-k: selected on the logits (softmax is monotone) after rounding them to fp32,
+ *     the precision in which the GPU path takes the same decision; equal values go to the
+ *     lower expert index; slot 0 holds the largest.
+ *   - Eq. 1 weights the expert INPUT: expert e_j sees p_j * x; its bias is not scaled.
+ *   - expert: phi_e(v) = act(v W1[e] + b1[e]) W2[e] + b2[e], act = exact (erf) GELU.
+ *   - the k expert outputs of one slice are summed; the S slices are concatenated, which in
+ *     the slice view means out[n, :] sits at the same place as x[n, :].
+ *   - capacity (not in the paper; benchmark contract): within an expert, rows are ranked by
+ *     ascending slice id n; an assignment with rank >= C is dropped and contributes zero.
+ *   - flat assignment id a = n*k + j;  perm[row] = a;  inv[a] = row, or -1 if dropped.
+ *
+ * Pins (tests/test_oracle_*.py): brute-force stable sort for top-k and dispatch, count sum,
+ * bijection, E=1/k=1 dense-FFN reduction against library matmul+erf, S=1 token-level MoE,
+ * W2=0 and identity-activation closed forms, load-statistic closed forms.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORACLE_ACT_GELU 0
+#define ORACLE_ACT_IDENTITY 1 /* used only by closed-form pins */
+
+static double act_fn(double z, int act)
+{
+    if (act == ORACLE_ACT_IDENTITY) return z;
+    /* z * Phi(z), Phi(z) = (1 + erf(z/sqrt 2))/2 = erfc(-z/sqrt 2)/2 (the erfc form keeps
+     * full relative accuracy in the negative tail) */
+    return 0.5 * z * erfc(-z * 0.70710678118654752440);
+}
+
+/* Exposed so a test can pin it against closed forms and a library normal CDF. */
+double oracle_gelu(double z) { return act_fn(z, ORACLE_ACT_GELU); }
+
+/* Router logits of one slice (Section 3.1): g = ReLU(x Wr1 + br1) Wr2 + br2. */
+static void router_logits(const double *x, int ds, int Hr, int E,
+                          const double *Wr1, const double *br1,
+                          const double *Wr2, const double *br2,
+                          double *u /*[Hr] scratch*/, double *g /*[E]*/)
+{
+    for (int j = 0; j < Hr; ++j) u[j] = br1[j];
+    for (int i = 0; i < ds; ++i)
+        for (int j = 0; j < Hr; ++j) u[j] += x[i] * Wr1[(size_t)i * Hr + j];
+    for (int j = 0; j < Hr; ++j) u[j] = u[j] > 0.0 ? u[j] : 0.0;
+    for (int e = 0; e < E; ++e) g[e] = br2[e];
+    for (int j = 0; j < Hr; ++j)
+        for (int e = 0; e < E; ++e) g[e] += u[j] * Wr2[(size_t)j * E + e];
+}
+
+/*
+ * Routing of every slice (Section 3.1).
+ *   x[Ns, ds]  ->  idx[Ns, k] (int32), pk[Ns, k] (softmax probability of each selected
+ *   expert), optional logits[Ns, E] and margin[Ns] (= fp32 logit of the k-th selected
+ *   minus the largest unselected one; +inf when k == E).
+ * Returns 0, or -1 on bad arguments / allocation failure.
+ */
+int oracle_route(const double *x, int64_t Ns, int ds, int Hr, int E, int k,
+                 const double *Wr1, const double *br1, const double *Wr2, const double *br2,
+                 int32_t *idx, double *pk, double *logits, double *margin)
+{
+    if (!x || !idx || !pk || Ns < 0 || ds < 1 || Hr < 1 || E < 1 || k < 1 || k > E) return -1;
+    int fail = 0;
+#pragma omp parallel
+    {
+        double *u = (double *)malloc(sizeof(double) * (size_t)Hr);
+        double *g = (double *)malloc(sizeof(double) * (size_t)E);
+        double *p = (double *)malloc(sizeof(double) * (size_t)E);
+        float *gf = (float *)malloc(sizeof(float) * (size_t)E);
+        char *taken = (char *)malloc((size_t)E);
+        if (!u || !g || !p || !gf || !taken) {
+#pragma omp atomic write
+            fail = 1;
+        } else {
+#pragma omp for schedule(static)
+            for (int64_t n = 0; n < Ns; ++n) {
+                router_logits(x + n * ds, ds, Hr, E, Wr1, br1, Wr2, br2, u, g);
+                if (logits) memcpy(logits + n * E, g, sizeof(double) * (size_t)E);
+                /* softmax over all E experts */
+                double m = g[0];
+                for (int e = 1; e < E; ++e) m = g[e] > m ? g[e] : m;
+                double den = 0.0;
+                for (int e = 0; e < E; ++e) { p[e] = exp(g[e] - m); den += p[e]; }
+                for (int e = 0; e < E; ++e) p[e] /= den;
+                /* top-k: k rounds of "largest remaining fp32 logit, lowest index on ties" */
+                for (int e = 0; e < E; ++e) { gf[e] = (float)g[e]; taken[e] = 0; }
+                for (int j = 0; j < k; ++j) {
+                    int best = -1;
+                    for (int e = 0; e < E; ++e)
+                        if (!taken[e] && (best < 0 || gf[e] > gf[best])) best = e;
+                    taken[best] = 1;
+                    idx[n * k + j] = best;
+                    pk[n * k + j] = p[best];
+                }
+                if (margin) {
+                    int rest = -1;
+                    for (int e = 0; e < E; ++e)
+                        if (!taken[e] && (rest < 0 || gf[e] > gf[rest])) rest = e;
+                    margin[n] = rest < 0 ? INFINITY
+                                         : (double)gf[idx[n * k + k - 1]] - (double)gf[rest];
+                }
+            }
+        }
+        free(u); free(g); free(p); free(gf); free(taken);
+    }
+    return fail ? -1 : 0;
+}
+
+/*
+ * Dispatch: group assignments per expert in stable slice order, with optional capacity.
+ *   idx[Ns, k] -> counts_raw[E], counts[E] (= min(counts_raw, C)), offsets[E+1]
+ *   (exclusive scan of counts; offsets[E] = kept rows), perm[Ns*k] (first offsets[E]
+ *   entries valid, the rest set to -1), inv[Ns*k].
+ * capacity < 0 means dropless.  One serial pass in ascending n with per-expert counters.
+ */
+int oracle_dispatch(const int32_t *idx, int64_t Ns, int k, int E, int64_t capacity,
+                    int32_t *counts_raw, int32_t *counts, int32_t *offsets,
+                    int32_t *perm, int32_t *inv)
+{
+    if (!idx || !counts_raw || !counts || !offsets || !perm || !inv || E < 1 || k < 1) return -1;
+    int64_t Na = Ns * k;
+    for (int e = 0; e < E; ++e) counts_raw[e] = 0;
+    for (int64_t a = 0; a < Na; ++a) {
+        if (idx[a] < 0 || idx[a] >= E) return -1;
+        counts_raw[idx[a]]++;
+    }
+    offsets[0] = 0;
+    for (int e = 0; e < E; ++e) {
+        counts[e] = (capacity >= 0 && counts_raw[e] > capacity) ? (int32_t)capacity : counts_raw[e];
+        offsets[e + 1] = offsets[e] + counts[e];
+    }
+    int64_t *seen = (int64_t *)calloc((size_t)E, sizeof(int64_t));
+    if (!seen) return -1;
+    for (int64_t a = 0; a < Na; ++a) perm[a] = -1;
+    for (int64_t n = 0; n < Ns; ++n)
+        for (int j = 0; j < k; ++j) {
+            int64_t a = n * k + j;
+            int e = idx[a];
+            int64_t rank = seen[e]++;
+            if (capacity < 0 || rank < capacity) {
+                int64_t row = offsets[e] + rank;
+                perm[row] = (int32_t)a;
+                inv[a] = (int32_t)row;
+            } else {
+                inv[a] = -1;
+            }
+        }
+    free(seen);
+    return 0;
+}
+
+/* One expert on one weighted slice (Eq. 1 and the expert FFN of Section 3.1):
+ * y = act((p x) W1 + b1) W2 + b2. */
+static void expert_apply(const double *x, double p, int ds, int He,
+                         const double *W1, const double *b1, const double *W2, const double *b2,
+                         int act, double *z /*[He] scratch*/, double *y /*[ds]*/)
+{
+    for (int j = 0; j < He; ++j) z[j] = b1[j];
+    for (int i = 0; i < ds; ++i) {
+        double xi = p * x[i];
+        for (int j = 0; j < He; ++j) z[j] += xi * W1[(size_t)i * He + j];
+    }
+    for (int j = 0; j < He; ++j) z[j] = act_fn(z[j], act);
+    for (int i = 0; i < ds; ++i) y[i] = b2[i];
+    for (int j = 0; j < He; ++j)
+        for (int i = 0; i < ds; ++i) y[i] += z[j] * W2[(size_t)j * ds + i];
+}
+
+/*
+ * Expert stage on the stacked batch (Section 3.4 states the grouping; the values are those
+ * of Section 3.1): for each kept row r, a = perm[r], n = a / k, e = idx[a],
+ *   y[r, :] = phi_e(pk[a] * x[n, :]).
+ */
+int oracle_expert_rows(const double *x, int ds, int He, int k,
+                       const int32_t *idx, const double *pk, const int32_t *perm, int64_t n_rows,
+                       const double *W1, const double *b1, const double *W2, const double *b2,
+                       int act, double *y)
+{
+    if (!x || !idx || !pk || !perm || !y || n_rows < 0) return -1;
+    int fail = 0;
+#pragma omp parallel
+    {
+        double *z = (double *)malloc(sizeof(double) * (size_t)He);
+        if (!z) {
+#pragma omp atomic write
+            fail = 1;
+        } else {
+#pragma omp for schedule(static)
+            for (int64_t r = 0; r < n_rows; ++r) {
+                int64_t a = perm[r];
+                int64_t n = a / k;
+                int e = idx[a];
+                expert_apply(x + n * ds, pk[a], ds, He,
+                             W1 + (size_t)e * ds * He, b1 + (size_t)e * He,
+                             W2 + (size_t)e * He * ds, b2 + (size_t)e * ds, act, z, y + r * ds);
+            }
+        }
+        free(z);
+    }
+    return fail ? -1 : 0;
+}
+
+/*
+ * Combine (Section 3.1): out[n, :] = sum over the kept assignments j of slice n of
+ * y[inv[n*k + j], :]; a slice whose k assignments were all dropped yields zeros.
+ */
+int oracle_combine(const double *y, const int32_t *inv, int64_t Ns, int k, int ds, double *out)
+{
+    if (!y || !inv || !out) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < Ns; ++n) {
+        double *o = out + n * ds;
+        for (int i = 0; i < ds; ++i) o[i] = 0.0;
+        for (int j = 0; j < k; ++j) {
+            int64_t r = inv[n * k + j];
+            if (r < 0) continue;
+            for (int i = 0; i < ds; ++i) o[i] += y[r * ds + i];
+        }
+    }
+    return 0;
+}
+
+/*
+ * Expert + combine by the plain per-slice definition, given routing and the keep mask:
+ *   out[n, :] = sum_{j : inv[n*k+j] >= 0} phi_{idx[n,j]}(pk[n,j] * x[n, :]).
+ * `inv` may be NULL (nothing dropped).  Slices are independent, so this also serves
+ * sampled subsets: pass only the sampled rows of x / idx / pk / inv.
+ */
+int oracle_slices(const double *x, int64_t Ns, int ds, int He, int k,
+                  const int32_t *idx, const double *pk, const int32_t *inv,
+                  const double *W1, const double *b1, const double *W2, const double *b2,
+                  int act, double *out)
+{
+    if (!x || !idx || !pk || !out) return -1;
+    int fail = 0;
+#pragma omp parallel
+    {
+        double *z = (double *)malloc(sizeof(double) * (size_t)He);
+        double *y = (double *)malloc(sizeof(double) * (size_t)ds);
+        if (!z || !y) {
+#pragma omp atomic write
+            fail = 1;
+        } else {
+#pragma omp for schedule(static)
+            for (int64_t n = 0; n < Ns; ++n) {
+                double *o = out + n * ds;
+                for (int i = 0; i < ds; ++i) o[i] = 0.0;
+                for (int j = 0; j < k; ++j) {
+                    int64_t a = n * k + j;
+                    if (inv && inv[a] < 0) continue;
+                    int e = idx[a];
+                    expert_apply(x + n * ds, pk[a], ds, He,
+                                 W1 + (size_t)e * ds * He, b1 + (size_t)e * He,
+                                 W2 + (size_t)e * He * ds, b2 + (size_t)e * ds, act, z, y);
+                    for (int i = 0; i < ds; ++i) o[i] += y[i];
+                }
+            }
+        }
+        free(z); free(y);
+    }
+    return fail ? -1 : 0;
+}
+
+/*
+ * Whole layer: h[T, d] -> h'[T, d]  (route, dispatch, experts, combine).
+ * Optional outputs (may be NULL): idx[Ns,k], pk[Ns,k], margin[Ns], counts_raw[E],
+ * counts[E], offsets[E+1], perm[Ns*k], inv[Ns*k].
+ */
+int oracle_forward(const double *h, int64_t T, int d, int S, int Hr, int E, int k, int He,
+                   int64_t capacity,
+                   const double *Wr1, const double *br1, const double *Wr2, const double *br2,
+                   const double *W1, const double *b1, const double *W2, const double *b2,
+                   int act, double *h_out,
+                   int32_t *idx_o, double *pk_o, double *margin_o, int32_t *counts_raw_o,
+                   int32_t *counts_o, int32_t *offsets_o, int32_t *perm_o, int32_t *inv_o)
+{
+    if (!h || !h_out || T < 0 || S < 1 || d < 1 || d % S) return -1;
+    int ds = d / S;
+    int64_t Ns = T * S, Na = Ns * k;
+    int32_t *idx = (int32_t *)malloc(sizeof(int32_t) * (size_t)(Na + 1));
+    double *pk = (double *)malloc(sizeof(double) * (size_t)(Na + 1));
+    int32_t *perm = (int32_t *)malloc(sizeof(int32_t) * (size_t)(Na + 1));
+    int32_t *inv = (int32_t *)malloc(sizeof(int32_t) * (size_t)(Na + 1));
+    int32_t *cr = (int32_t *)malloc(sizeof(int32_t) * (size_t)E);
+    int32_t *cc = (int32_t *)malloc(sizeof(int32_t) * (size_t)E);
+    int32_t *off = (int32_t *)malloc(sizeof(int32_t) * (size_t)(E + 1));
+    int rc = -1;
+    if (idx && pk && perm && inv && cr && cc && off) {
+        rc = oracle_route(h, Ns, ds, Hr, E, k, Wr1, br1, Wr2, br2, idx, pk, NULL, margin_o);
+        if (!rc) rc = oracle_dispatch(idx, Ns, k, E, capacity, cr, cc, off, perm, inv);
+        if (!rc) rc = oracle_slices(h, Ns, ds, He, k, idx, pk, inv, W1, b1, W2, b2, act, h_out);
+        if (!rc) {
+            if (idx_o) memcpy(idx_o, idx, sizeof(int32_t) * (size_t)Na);
+            if (pk_o) memcpy(pk_o, pk, sizeof(double) * (size_t)Na);
+            if (perm_o) memcpy(perm_o, perm, sizeof(int32_t) * (size_t)Na);
+            if (inv_o) memcpy(inv_o, inv, sizeof(int32_t) * (size_t)Na);
+            if (counts_raw_o) memcpy(counts_raw_o, cr, sizeof(int32_t) * (size_t)E);
+            if (counts_o) memcpy(counts_o, cc, sizeof(int32_t) * (size_t)E);
+            if (offsets_o) memcpy(offsets_o, off, sizeof(int32_t) * (size_t)(E + 1));
+        }
+    }
+    free(idx); free(pk); free(perm); free(inv); free(cr); free(cc); free(off);
+    return rc;
+}
+
+/*
+ * Load statistics of per-expert counts.
+ *   cv_pop / cv_sample : std/mean with the population (1/E) and sample (1/(E-1)) variance;
+ *                        the capacity loss of Eq. 2 is alpha * cv^2 (population reading).
+ *   ele                : -sum_e load_e log load_e / log E with load_e = counts_e / sum
+ *                        (Section 4, Metrics); 0 log 0 = 0; defined as 1 when E == 1.
+ */
+int oracle_load_stats(const int32_t *counts, int E, double *cv_pop, double *cv_sample, double *ele)
+{
+    if (!counts || E < 1) return -1;
+    double sum = 0.0;
+    for (int e = 0; e < E; ++e) sum += counts[e];
+    double mean = sum / E, ss = 0.0, ent = 0.0;
+    for (int e = 0; e < E; ++e) {
+        double dlt = counts[e] - mean;
+        ss += dlt * dlt;
+        if (counts[e] > 0 && sum > 0) { double l = counts[e] / sum; ent -= l * log(l); }
+    }
+    if (cv_pop) *cv_pop = mean > 0 ? sqrt(ss / E) / mean : 0.0;
+    if (cv_sample) *cv_sample = (mean > 0 && E > 1) ? sqrt(ss / (E - 1)) / mean : 0.0;
+    if (ele) *ele = E > 1 ? ent / log((double)E) : 1.0;
+    return 0;
+}
+
+/* Number of OpenMP threads a parallel region of this library uses. */
+#ifdef _OPENMP
+#include <omp.h>
+int oracle_num_threads(void) { return omp_get_max_threads(); }
+#else
+int oracle_num_threads(void) { return 1; }
+#endif
