@@ -1,0 +1,200 @@
+/*
+ * slicemoe.h -- C ABI of the SliceMoE layer forward pass for AMD MI355X (gfx950).
+ *
+ * The layer (paper Section 3, Section 3.1, Eq. 1; execution strategy of Section 3.4):
+ * a token vector h in R^d is cut into S contiguous slices of width ds = d/S; a router MLP
+ * shared by all slices, Linear(ds -> Hr) -> ReLU -> Linear(Hr -> E), gives logits, softmax
+ * over the E experts gives p, the top-k experts of each slice are selected; expert e_j sees
+ * the weighted slice p_j * x (Eq. 1) and applies a two-layer GELU MLP ds -> He -> ds; the
+ * k outputs of a slice are summed and the S output slices concatenated into h' in R^d.
+ * Slices bound for one expert are grouped into one stacked batch per expert (Section 3.4).
+ *
+ * Conventions common to every entry point
+ *   - Every pointer is caller-allocated DEVICE memory unless it is the config / weights
+ *     struct itself (HOST).  The library never allocates, frees or keeps a pointer.
+ *   - Every call only enqueues kernels on `stream` and returns; there is no hidden
+ *     synchronisation and no device->host copy.  Same inputs give bit-identical outputs.
+ *   - Slice id n = t*S + s; because slices are contiguous, h[T, d] row-major IS the slice
+ *     matrix x[Ns = T*S, ds].  Assignment id a = n*k + j for the j-th selected expert.
+ *   - Linear layers are y = x W + b with W stored [in, out] row-major; expert tensors carry
+ *     the expert index on the leading axis.
+ *   - dtype is the storage type of h, h' and all weights (fp32 or bf16 bit patterns);
+ *     accumulation is always fp32.  topk_p and y are always fp32, indices are int32.
+ *   - Limits: 1 <= k <= min(E, 8), E <= 64, d % S == 0, T*S*k < 2^31.  The matrix-core
+ *     (MFMA) kernels need dtype = bf16, Hr = 256, ds in {64, 128}, He % 64 == 0; any
+ *     other shape runs on slower generic kernels unless SLICEMOE_FLAG_REQUIRE_MFMA is set.
+ *   - Errors are return codes; nothing aborts or throws across this boundary.
+ */
+#ifndef SLICEMOE_H
+#define SLICEMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SLICEMOE_OK = 0,
+    SLICEMOE_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, d % S != 0, k > E ...   */
+    SLICEMOE_ERR_UNSUPPORTED = 2, /* valid layer, but outside the limits listed above          */
+    SLICEMOE_ERR_WORKSPACE = 3,   /* workspace / packed buffer too small                       */
+    SLICEMOE_ERR_HIP = 4          /* a kernel launch reported an error (hipGetLastError)       */
+} slicemoe_status;
+
+typedef enum { SLICEMOE_F32 = 0, SLICEMOE_BF16 = 1 } slicemoe_dtype;
+
+/* flags */
+#define SLICEMOE_FLAG_FORCE_GENERIC 1u /* never use the MFMA kernels (debug / cross-check)      */
+#define SLICEMOE_FLAG_REQUIRE_MFMA 2u  /* return UNSUPPORTED instead of using generic kernels   */
+
+/* Same handle type as hipStream_t, spelled out so this header needs no HIP include. */
+struct ihipStream_t;
+typedef struct ihipStream_t *slicemoe_stream_t;
+
+typedef struct {
+    int32_t T;  /* tokens                                                                   */
+    int32_t d;  /* token width                                                              */
+    int32_t S;  /* slices per token (Section 3)                                             */
+    int32_t k;  /* experts per slice (Section 3.1)                                          */
+    int32_t E;  /* experts                                                                  */
+    int32_t Hr; /* router hidden width (256 in the paper, Section 3.1 / Appendix A)         */
+    int32_t He; /* expert hidden width                                                      */
+    float capacity_factor; /* <= 0: dropless.  > 0: per-expert row capacity
+                              C = ceil((double)capacity_factor * T*S*k / E); within an expert
+                              rows are ranked by ascending slice id and rank >= C is dropped
+                              (contributes zero to h').                                      */
+    int32_t dtype; /* slicemoe_dtype                                                        */
+    uint32_t flags;
+} slicemoe_config;
+
+/* Layer parameters, logical layout.  `packed` is optional (NULL allowed): the buffer
+ * written by slicemoe_pack_weights for the same config and tensors.  When it is NULL and a
+ * kernel wants the packed form, the call packs into its workspace first (slower). */
+typedef struct {
+    const void *Wr1; /* [ds, Hr]   router layer 1 */
+    const void *br1; /* [Hr]                      */
+    const void *Wr2; /* [Hr, E]    router layer 2 */
+    const void *br2; /* [E]                       */
+    const void *W1;  /* [E, ds, He] expert layer 1 */
+    const void *b1;  /* [E, He]                    */
+    const void *W2;  /* [E, He, ds] expert layer 2 */
+    const void *b2;  /* [E, ds]                    */
+    const void *packed;
+} slicemoe_weights;
+
+/* Byte offsets of the intermediates that slicemoe_forward leaves in its workspace. */
+typedef struct {
+    size_t topk_idx;   /* int32 [T*S, k]                                   */
+    size_t topk_p;     /* float [T*S, k]                                   */
+    size_t counts_raw; /* int32 [E]                                        */
+    size_t counts;     /* int32 [E]                                        */
+    size_t offsets;    /* int32 [E+1]                                      */
+    size_t perm;       /* int32 [T*S*k]                                    */
+    size_t inv;        /* int32 [T*S*k]                                    */
+    size_t y;          /* float [T*S*k, ds]                                */
+    size_t stats;      /* float [4], see slicemoe_load_stats               */
+    size_t scratch;    /* dispatch scratch                                 */
+    size_t packed;     /* on-the-fly packed weights                        */
+    size_t total;      /* == slicemoe_workspace_bytes                      */
+} slicemoe_workspace_layout;
+
+const char *slicemoe_status_string(slicemoe_status s);
+
+/* 1 if this config would run on the MFMA kernels, 0 if on the generic ones, -1 if invalid. */
+int slicemoe_uses_mfma(const slicemoe_config *cfg);
+
+/* Per-expert capacity C for this config, or -1 when dropless / invalid. */
+int64_t slicemoe_capacity(const slicemoe_config *cfg);
+
+/* Workspace sizes in bytes (0 on an invalid or unsupported config).  The forward workspace
+ * also satisfies slicemoe_dispatch.  Workspaces must be 256-byte aligned. */
+size_t slicemoe_workspace_bytes(const slicemoe_config *cfg);
+size_t slicemoe_dispatch_workspace_bytes(const slicemoe_config *cfg);
+slicemoe_status slicemoe_get_workspace_layout(const slicemoe_config *cfg, slicemoe_workspace_layout *out);
+
+/* One-time re-tiling of the weights into matrix-core fragment order (a weight-load step,
+ * like any layout transform done when a model is loaded; Section 3.4 leaves the kernel's
+ * internals open).  packed_bytes is 0 when the config runs on the generic kernels; then
+ * slicemoe_pack_weights is a no-op returning OK. */
+size_t slicemoe_packed_bytes(const slicemoe_config *cfg);
+slicemoe_status slicemoe_pack_weights(const slicemoe_config *cfg, const slicemoe_weights *w,
+                                      void *packed_out, size_t packed_bytes, slicemoe_stream_t stream);
+
+/*
+ * Router (Section 3.1): for every slice, logits g = ReLU(x Wr1 + br1) Wr2 + br2, p = softmax(g)
+ * over all E experts (temperature 1, not renormalised over the selected k), top-k on the fp32
+ * logits, equal logits resolved to the lower expert index, slot 0 = largest.
+ *   h        [T, d]    in
+ *   topk_idx [T*S, k]  out int32
+ *   topk_p   [T*S, k]  out float, p of each selected expert
+ *   workspace: needed only when w->packed is NULL on the MFMA path (>= slicemoe_workspace_bytes);
+ *              may be NULL otherwise.
+ */
+slicemoe_status slicemoe_route(const slicemoe_config *cfg, const void *h, const slicemoe_weights *w,
+                               int32_t *topk_idx, float *topk_p,
+                               void *workspace, size_t workspace_bytes, slicemoe_stream_t stream);
+
+/*
+ * Dispatch (the grouping of Section 3.4): stable counting sort of assignments by expert.
+ *   topk_idx   [T*S, k] in, values in [0, E) (out-of-range values are clamped, never faulted on)
+ *   counts_raw [E]      out: assignments per expert (the counts of Eq. 2)
+ *   counts     [E]      out: min(counts_raw, C)
+ *   offsets    [E+1]    out: exclusive scan of counts; offsets[E] = number of kept rows
+ *   perm       [T*S*k]  out: perm[row] = assignment id of stacked row `row` (rows of one expert
+ *                            are contiguous, in ascending slice order); entries at
+ *                            row >= offsets[E] are left untouched
+ *   inv        [T*S*k]  out: inv[a] = row of assignment a, or -1 if it was dropped
+ *   workspace  >= slicemoe_dispatch_workspace_bytes
+ */
+slicemoe_status slicemoe_dispatch(const slicemoe_config *cfg, const int32_t *topk_idx,
+                                  int32_t *counts_raw, int32_t *counts, int32_t *offsets,
+                                  int32_t *perm, int32_t *inv,
+                                  void *workspace, size_t workspace_bytes, slicemoe_stream_t stream);
+
+/*
+ * Expert FFN on the stacked batch (Eq. 1, Section 3.1 expert, Section 3.4 grouping): for every
+ * kept row r < offsets[E], with a = perm[r], n = a / k and e the expert whose range holds r,
+ *   y[r, :] = GELU((topk_p[a] * x[n, :]) W1[e] + b1[e]) W2[e] + b2[e]
+ * The gather of x and the Eq. 1 weighting are fused into the kernel (no stacked copy of the
+ * inputs is materialised); the He-wide hidden activations never leave the chip.
+ *   y [T*S*k, ds] out float; rows >= offsets[E] are left untouched.
+ * The MFMA kernel rounds the hidden activations to bf16 and uses the tanh form of GELU
+ * (|error| < 5e-4, below that rounding); the generic kernel uses erf.
+ */
+slicemoe_status slicemoe_expert_ffn(const slicemoe_config *cfg, const void *h, const float *topk_p,
+                                    const int32_t *offsets, const int32_t *perm,
+                                    const slicemoe_weights *w, float *y,
+                                    void *workspace, size_t workspace_bytes, slicemoe_stream_t stream);
+
+/*
+ * Combine (Section 3.1): h'[n, :] = sum over the kept assignments j of slice n of
+ * y[inv[n*k + j], :], summed in fp32 in ascending j, rounded once to the storage dtype and
+ * written at h_out[t, s*ds : (s+1)*ds].  A slice with all k assignments dropped gives zeros.
+ */
+slicemoe_status slicemoe_combine(const slicemoe_config *cfg, const float *y, const int32_t *inv,
+                                 void *h_out, slicemoe_stream_t stream);
+
+/*
+ * Load statistics of a routed batch, computed on device from the dispatch counts:
+ *   stats[0] = CV^2 of counts_raw with the population variance (= L_cap / alpha, Eq. 2)
+ *   stats[1] = ELE = -sum_e load_e log(load_e) / log(E), load_e = counts_raw[e] / sum (Section 4)
+ *   stats[2] = dropped fraction 1 - sum(counts) / sum(counts_raw)
+ *   stats[3] = CV^2 with the sample variance (E-1 in the denominator)
+ */
+slicemoe_status slicemoe_load_stats(const slicemoe_config *cfg, const int32_t *counts_raw,
+                                    const int32_t *counts, float *stats, slicemoe_stream_t stream);
+
+/*
+ * Whole layer: h[T, d] -> h_out[T, d] = route, dispatch, expert FFN, combine, load stats, all on
+ * `stream`.  Intermediates stay in `workspace` at the offsets of slicemoe_get_workspace_layout.
+ */
+slicemoe_status slicemoe_forward(const slicemoe_config *cfg, const void *h, const slicemoe_weights *w,
+                                 void *h_out, void *workspace, size_t workspace_bytes,
+                                 slicemoe_stream_t stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLICEMOE_H */

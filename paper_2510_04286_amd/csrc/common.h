@@ -1,0 +1,76 @@
+// Shared declarations of the SliceMoE HIP library: launch prototypes (host side) and small
+// device helpers.  gfx950 only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/slicemoe.h"
+
+namespace slicemoe {
+
+typedef unsigned short bf16_t;  // storage bit pattern of a bfloat16
+
+// ---- device helpers -------------------------------------------------------------------
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// round-to-nearest-even conversion (v_cvt_pk_bf16_f32 on gfx950)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f)
+{
+    __bf16 v = (__bf16)f;
+    return __builtin_bit_cast(bf16_t, v);
+}
+
+template <typename T> struct Storage;
+template <> struct Storage<float> {
+    static __device__ __forceinline__ float load(const float *p) { return *p; }
+    static __device__ __forceinline__ void store(float *p, float v) { *p = v; }
+};
+template <> struct Storage<bf16_t> {
+    static __device__ __forceinline__ float load(const bf16_t *p) { return bf16_to_f32(*p); }
+    static __device__ __forceinline__ void store(bf16_t *p, float v) { *p = f32_to_bf16(v); }
+};
+
+__host__ __device__ __forceinline__ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- packed-weight buffer layout (bf16 MFMA path) -------------------------------------
+// All offsets in bytes from the start of the packed buffer; every region 256-byte aligned.
+struct PackedLayout {
+    int ds, Hr, He, E, Epad;     // Epad = E rounded up to a multiple of 32
+    size_t r_w1, r_w2, r_b1, r_b2;  // router: Wr1 frags, Wr2 frags, br1 (f32), br2 (f32, Epad)
+    size_t experts;                 // start of expert 0
+    size_t e_w1, e_w2, e_b1, e_b2;  // offsets inside one expert block
+    size_t e_stride;                // bytes per expert
+    size_t total;
+};
+PackedLayout packed_layout(const slicemoe_config &cfg);
+
+// ---- dispatch geometry ----------------------------------------------------------------
+constexpr int kDispThreads = 256;
+constexpr int kDispItems = 16;
+constexpr int kDispChunk = kDispThreads * kDispItems;  // assignments per block
+
+// ---- kernel launchers (each only enqueues; returns hipGetLastError) --------------------
+hipError_t launch_route_generic(const slicemoe_config &c, const void *h, const slicemoe_weights &w,
+                                int32_t *idx, float *p, hipStream_t s);
+hipError_t launch_route_mfma(const slicemoe_config &c, const void *h, const void *packed,
+                             int32_t *idx, float *p, hipStream_t s);
+hipError_t launch_dispatch(const slicemoe_config &c, const int32_t *idx, int32_t *counts_raw,
+                           int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv,
+                           int32_t *block_counts, hipStream_t s);
+hipError_t launch_ffn_generic(const slicemoe_config &c, const void *h, const float *p,
+                              const int32_t *offsets, const int32_t *perm, const slicemoe_weights &w,
+                              float *y, hipStream_t s);
+hipError_t launch_ffn_mfma(const slicemoe_config &c, const void *h, const float *p,
+                           const int32_t *offsets, const int32_t *perm, const void *packed,
+                           float *y, hipStream_t s);
+hipError_t launch_combine(const slicemoe_config &c, const float *y, const int32_t *inv, void *h_out,
+                          hipStream_t s);
+hipError_t launch_load_stats(const slicemoe_config &c, const int32_t *counts_raw, const int32_t *counts,
+                             float *stats, hipStream_t s);
+hipError_t launch_pack(const slicemoe_config &c, const slicemoe_weights &w, void *packed, hipStream_t s);
+
+int num_compute_units();
+int max_lds_per_block();  // bytes of LDS one workgroup may use on the current device
+
+}  // namespace slicemoe

@@ -1,0 +1,211 @@
+// Dispatch stage: stable counting sort of slice->expert assignments (the grouping of paper
+// Section 3.4), with an optional per-expert capacity, plus the load statistics of Eq. 2 and
+// of the ELE metric (Section 4).
+//
+// Three kernels over chunks of kDispChunk consecutive assignment ids a = n*k + j:
+//   1. histogram   block_counts[b][e] = # assignments of chunk b bound for expert e
+//   2. scan        per expert, exclusive prefix over chunks (in place) -> rank of a chunk's first
+//                  assignment inside its expert; totals -> counts_raw, counts, offsets
+//   3. scatter     stable rank of every assignment inside its chunk, final row, perm / inv
+// Stability needs ranks in ascending a.  A block walks its chunk in rounds of 256 consecutive
+// ids; inside a wavefront the rank among equal experts comes from ballots (one per bit of the
+// expert id gives every lane the mask of lanes holding the same expert), across wavefronts and
+// rounds from a small LDS table scanned in (round, wavefront) order.
+#include "common.h"
+
+namespace slicemoe {
+
+__device__ __forceinline__ unsigned long long same_expert_mask(int e, bool valid, int nbits)
+{
+    unsigned long long m = __ballot(valid);
+    for (int b = 0; b < nbits; ++b) {
+        const bool bit = (e >> b) & 1;
+        const unsigned long long bal = __ballot(valid && bit);
+        m &= bit ? bal : ~bal;
+    }
+    return m;
+}
+
+__device__ __forceinline__ int clamp_expert(int e, int E) { return e < 0 ? 0 : (e >= E ? E - 1 : e); }
+
+__global__ __launch_bounds__(kDispThreads) void dispatch_hist_kernel(
+    const int32_t *__restrict__ idx, int Na, int E, int nbits, int32_t *__restrict__ block_counts)
+{
+    __shared__ int cnt[64];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    if (tid < 64) cnt[tid] = 0;
+    __syncthreads();
+    const int base = blockIdx.x * kDispChunk;
+    for (int i = 0; i < kDispItems; ++i) {
+        const int a = base + i * kDispThreads + tid;
+        const bool valid = a < Na;
+        const int e = valid ? clamp_expert(idx[a], E) : 0;
+        const unsigned long long m = same_expert_mask(e, valid, nbits);
+        const unsigned long long below = m & ((1ull << lane) - 1ull);
+        if (valid && below == 0) atomicAdd(&cnt[e], __popcll(m));
+    }
+    __syncthreads();
+    if (tid < E) block_counts[(size_t)blockIdx.x * E + tid] = cnt[tid];
+}
+
+// One block of 1024 threads.  Thread (seg, e) with e = tid % Epow2 sums a contiguous range of
+// chunks for expert e; the per-segment sums are scanned serially per expert (<= 1024/Epow2
+// segments), then each thread rewrites its range as exclusive prefixes.
+__global__ __launch_bounds__(1024) void dispatch_scan_kernel(
+    int32_t *__restrict__ block_counts, int nblocks, int E, int Epow2, long long capacity,
+    int32_t *__restrict__ counts_raw, int32_t *__restrict__ counts, int32_t *__restrict__ offsets)
+{
+    __shared__ int seg_sum[1024];
+    __shared__ int kept[64];
+    const int tid = threadIdx.x;
+    const int e = tid % Epow2;
+    const int seg = tid / Epow2;
+    const int nseg = 1024 / Epow2;
+    const int per = (nblocks + nseg - 1) / nseg;
+    const int b0 = seg * per;
+    const int b1 = min(nblocks, b0 + per);
+    int s = 0;
+    if (e < E)
+        for (int b = b0; b < b1; ++b) s += block_counts[(size_t)b * E + e];
+    seg_sum[tid] = s;
+    __syncthreads();
+    if (seg == 0 && e < E) {
+        int run = 0;
+        for (int g = 0; g < nseg; ++g) {
+            const int t = seg_sum[g * Epow2 + e];
+            seg_sum[g * Epow2 + e] = run;
+            run += t;
+        }
+        counts_raw[e] = run;
+        const int c = (capacity >= 0 && run > capacity) ? (int)capacity : run;
+        counts[e] = c;
+        kept[e] = c;
+    }
+    __syncthreads();
+    if (e < E) {
+        int run = seg_sum[tid];
+        for (int b = b0; b < b1; ++b) {
+            const size_t at = (size_t)b * E + e;
+            const int t = block_counts[at];
+            block_counts[at] = run;
+            run += t;
+        }
+    }
+    if (tid == 0) {
+        int run = 0;
+        for (int x = 0; x < E; ++x) {
+            offsets[x] = run;
+            run += kept[x];
+        }
+        offsets[E] = run;
+    }
+}
+
+__global__ __launch_bounds__(kDispThreads) void dispatch_scatter_kernel(
+    const int32_t *__restrict__ idx, int Na, int E, int nbits, long long capacity,
+    const int32_t *__restrict__ block_base, const int32_t *__restrict__ offsets,
+    int32_t *__restrict__ perm, int32_t *__restrict__ inv)
+{
+    constexpr int kWaves = kDispThreads / 64;
+    __shared__ int wcnt[kDispItems][kWaves][64];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    for (int i = tid; i < kDispItems * kWaves * 64; i += kDispThreads) (&wcnt[0][0][0])[i] = 0;
+    __syncthreads();
+
+    const int base = blockIdx.x * kDispChunk;
+    int ex[kDispItems];
+    int rk[kDispItems];
+#pragma unroll
+    for (int i = 0; i < kDispItems; ++i) {
+        const int a = base + i * kDispThreads + tid;
+        const bool valid = a < Na;
+        const int e = valid ? clamp_expert(idx[a], E) : 0;
+        const unsigned long long m = same_expert_mask(e, valid, nbits);
+        const int below = __popcll(m & ((1ull << lane) - 1ull));
+        ex[i] = valid ? e : -1;
+        rk[i] = below;
+        if (valid && below == 0) wcnt[i][wave][e] = __popcll(m);
+    }
+    __syncthreads();
+    if (tid < E) {
+        int run = block_base[(size_t)blockIdx.x * E + tid];
+        for (int i = 0; i < kDispItems; ++i)
+            for (int w = 0; w < kWaves; ++w) {
+                const int t = wcnt[i][w][tid];
+                wcnt[i][w][tid] = run;
+                run += t;
+            }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kDispItems; ++i) {
+        const int e = ex[i];
+        if (e < 0) continue;
+        const int a = base + i * kDispThreads + tid;
+        const int rank = wcnt[i][wave][e] + rk[i];
+        if (capacity < 0 || rank < capacity) {
+            const int row = offsets[e] + rank;
+            perm[row] = a;
+            inv[a] = row;
+        } else {
+            inv[a] = -1;
+        }
+    }
+}
+
+hipError_t launch_dispatch(const slicemoe_config &c, const int32_t *idx, int32_t *counts_raw,
+                           int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv,
+                           int32_t *block_counts, hipStream_t s)
+{
+    const long long Na = (long long)c.T * c.S * c.k;
+    const int nblocks = (int)((Na + kDispChunk - 1) / kDispChunk);
+    int nbits = 0;
+    while ((1 << nbits) < c.E) ++nbits;
+    const int Epow2 = 1 << nbits;
+    const long long cap = slicemoe_capacity(&c);
+    if (nblocks > 0) dispatch_hist_kernel<<<nblocks, kDispThreads, 0, s>>>(idx, (int)Na, c.E, nbits, block_counts);
+    dispatch_scan_kernel<<<1, 1024, 0, s>>>(block_counts, nblocks, c.E, Epow2, cap, counts_raw, counts,
+                                           offsets);
+    if (nblocks > 0)
+        dispatch_scatter_kernel<<<nblocks, kDispThreads, 0, s>>>(idx, (int)Na, c.E, nbits, cap, block_counts,
+                                                                offsets, perm, inv);
+    return hipGetLastError();
+}
+
+// ---- load statistics (Eq. 2 statistic, ELE of Section 4) --------------------------------
+__global__ void load_stats_kernel(const int32_t *__restrict__ counts_raw, const int32_t *__restrict__ counts,
+                                  int E, float *__restrict__ stats)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    double sum = 0.0, kept = 0.0;
+    for (int e = 0; e < E; ++e) {
+        sum += counts_raw[e];
+        kept += counts[e];
+    }
+    const double mean = sum / E;
+    double ss = 0.0, ent = 0.0;
+    for (int e = 0; e < E; ++e) {
+        const double dl = counts_raw[e] - mean;
+        ss += dl * dl;
+        if (counts_raw[e] > 0) {
+            const double l = counts_raw[e] / sum;
+            ent -= l * log(l);
+        }
+    }
+    stats[0] = mean > 0 ? (float)(ss / E / (mean * mean)) : 0.f;
+    stats[1] = E > 1 ? (float)(ent / log((double)E)) : 1.f;
+    stats[2] = sum > 0 ? (float)(1.0 - kept / sum) : 0.f;
+    stats[3] = (mean > 0 && E > 1) ? (float)(ss / (E - 1) / (mean * mean)) : 0.f;
+}
+
+hipError_t launch_load_stats(const slicemoe_config &c, const int32_t *counts_raw, const int32_t *counts,
+                             float *stats, hipStream_t s)
+{
+    load_stats_kernel<<<1, 64, 0, s>>>(counts_raw, counts, c.E, stats);
+    return hipGetLastError();
+}
+
+}  // namespace slicemoe

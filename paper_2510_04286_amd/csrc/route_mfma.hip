@@ -1,0 +1,206 @@
+// Fused slice router on the matrix cores (paper Section 3.1): per slice
+//   u = ReLU(x Wr1 + br1)  (Hr = 256),  g = u Wr2 + br2,  p = softmax(g),  top-k of g.
+// bf16 inputs, fp32 accumulation, logits good to fp32 rounding so that the selected experts
+// agree with a reference except on near-ties:
+//   GEMM1  bf16 x bf16 products are exact in fp32, accumulated in fp32 (bias preloaded into
+//          the accumulators).
+//   GEMM2  u stays fp32.  It is split exactly into three bf16 terms u = u0 + u1 + u2 (each the
+//          truncation of the running remainder: 8 + 8 + 8 significant bits), and the MFMA is
+//          issued once per term against the bf16 weights -- three exact-product passes instead
+//          of a slow fp32 matrix instruction.
+// Both GEMMs run transposed (see mfma.h): a lane owns one slice and, per 32-expert tile, 16 of
+// its logits; the other 16 sit in lane ^ 32.  Softmax and top-k therefore need only registers
+// and one cross-lane exchange per step.  A block keeps the whole router (<= 100 KiB packed) in
+// LDS and walks slice tiles of 32 per wavefront.
+#include "mfma.h"
+
+namespace slicemoe {
+
+constexpr int kRouteThreads = 256;
+constexpr int kRouteHr = 256;
+constexpr int kRouteHT = kRouteHr / 32;
+
+__device__ __forceinline__ uint32_t pack_hi16(float lo_elem, float hi_elem)
+{
+    // two bf16 truncations in one register: element 0 in the low half
+    return (__float_as_uint(lo_elem) >> 16) | (__float_as_uint(hi_elem) & 0xFFFF0000u);
+}
+
+template <int DS, int ET>
+__global__ __launch_bounds__(kRouteThreads) void route_mfma_kernel(
+    const bf16_t *__restrict__ x, long long Ns, int E, int k, const char *__restrict__ packed,
+    size_t off_w1, size_t off_w2, size_t off_b1, size_t off_b2, int32_t *__restrict__ idx,
+    float *__restrict__ pk)
+{
+    constexpr int KS = DS / 16;
+    constexpr int HT = kRouteHT;
+    extern __shared__ __align__(16) char lds[];
+    uint4 *w1s = (uint4 *)lds;                         // [HT][KS][64]
+    uint4 *w2s = w1s + HT * KS * 64;                   // [ET][HT][2][64]
+    float *b1s = (float *)(w2s + ET * HT * 2 * 64);    // [Hr]
+    float *b2s = b1s + kRouteHr;                       // [ET*32]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int j = lane & 31;
+    const int g = lane >> 5;
+
+    {
+        const uint4 *g1 = (const uint4 *)(packed + off_w1);
+        const uint4 *g2 = (const uint4 *)(packed + off_w2);
+        const float *gb1 = (const float *)(packed + off_b1);
+        const float *gb2 = (const float *)(packed + off_b2);
+        for (int i = tid; i < HT * KS * 64; i += kRouteThreads) w1s[i] = g1[i];
+        for (int i = tid; i < ET * HT * 2 * 64; i += kRouteThreads) w2s[i] = g2[i];
+        for (int i = tid; i < kRouteHr; i += kRouteThreads) b1s[i] = gb1[i];
+        for (int i = tid; i < ET * 32; i += kRouteThreads) b2s[i] = gb2[i];
+    }
+    __syncthreads();
+
+    const long long ntiles = (Ns + 31) / 32;
+    for (long long tile = (long long)blockIdx.x * 4 + wave; tile < ntiles; tile += (long long)gridDim.x * 4) {
+        const long long n = tile * 32 + j;
+        const bool valid = n < Ns;
+        bf16x8 xb[KS];
+        {
+            const uint4 *xp = (const uint4 *)(x + (valid ? n : 0) * DS);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (valid) v = xp[ks * 2 + g];
+                xb[ks] = __builtin_bit_cast(bf16x8, v);
+            }
+        }
+        f32x16 gacc[ET];
+#pragma unroll
+        for (int et = 0; et < ET; ++et)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) gacc[et][r] = 0.f;
+
+        for (int ht = 0; ht < HT; ++ht) {
+            // GEMM1 with the bias preloaded
+            f32x16 acc;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x4 b = *(const f32x4 *)(b1s + ht * 32 + 8 * q + 4 * g);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acc[4 * q + c] = b[c];
+            }
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                acc = mfma_bf16(__builtin_bit_cast(bf16x8, w1s[(ht * KS + ks) * 64 + lane]), xb[ks], acc);
+            // ReLU and the exact three-term bf16 split
+            uint32_t t0[8], t1[8], t2[8];
+#pragma unroll
+            for (int r = 0; r < 16; r += 2) {
+                float u[2], r1[2], r2[2];
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    u[c] = fmaxf(acc[r + c], 0.f);
+                    const float h0 = __uint_as_float(__float_as_uint(u[c]) & 0xFFFF0000u);
+                    r1[c] = u[c] - h0;
+                    const float h1 = __uint_as_float(__float_as_uint(r1[c]) & 0xFFFF0000u);
+                    r2[c] = r1[c] - h1;
+                }
+                t0[r >> 1] = pack_hi16(u[0], u[1]);
+                t1[r >> 1] = pack_hi16(r1[0], r1[1]);
+                t2[r >> 1] = pack_hi16(r2[0], r2[1]);
+            }
+            // GEMM2: three passes per K-step
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const bf16x8 u0 = __builtin_bit_cast(bf16x8, make_uint4(t0[4 * s], t0[4 * s + 1], t0[4 * s + 2], t0[4 * s + 3]));
+                const bf16x8 u1 = __builtin_bit_cast(bf16x8, make_uint4(t1[4 * s], t1[4 * s + 1], t1[4 * s + 2], t1[4 * s + 3]));
+                const bf16x8 u2 = __builtin_bit_cast(bf16x8, make_uint4(t2[4 * s], t2[4 * s + 1], t2[4 * s + 2], t2[4 * s + 3]));
+#pragma unroll
+                for (int et = 0; et < ET; ++et) {
+                    const bf16x8 a2 = __builtin_bit_cast(bf16x8, w2s[((et * HT + ht) * 2 + s) * 64 + lane]);
+                    gacc[et] = mfma_bf16(a2, u2, gacc[et]);
+                    gacc[et] = mfma_bf16(a2, u1, gacc[et]);
+                    gacc[et] = mfma_bf16(a2, u0, gacc[et]);
+                }
+            }
+        }
+
+        // ---- logits of this lane: expert 32*et + 8*(r/4) + 4*g + r%4, ascending in (et, r)
+        float v[ET * 16];
+#pragma unroll
+        for (int et = 0; et < ET; ++et)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int e = et * 32 + acc_feature(r, g);
+                const float val = gacc[et][r] + b2s[e];
+                v[et * 16 + r] = e < E ? val : -INFINITY;
+            }
+        float m = v[0];
+#pragma unroll
+        for (int i = 1; i < ET * 16; ++i) m = fmaxf(m, v[i]);
+        m = fmaxf(m, __shfl_xor(m, 32));
+        float den = 0.f;
+#pragma unroll
+        for (int i = 0; i < ET * 16; ++i) den += __expf(v[i] - m);
+        den += __shfl_xor(den, 32);
+        const float rden = 1.0f / den;
+
+        for (int jj = 0; jj < k; ++jj) {
+            float bv = v[0];
+            int be = acc_feature(0, g);
+#pragma unroll
+            for (int i = 1; i < ET * 16; ++i) {
+                const int e = (i >> 4) * 32 + acc_feature(i & 15, g);
+                if (v[i] > bv) {
+                    bv = v[i];
+                    be = e;
+                }
+            }
+            const float ov = __shfl_xor(bv, 32);
+            const int oe = __shfl_xor(be, 32);
+            if (ov > bv || (ov == bv && oe < be)) {
+                bv = ov;
+                be = oe;
+            }
+#pragma unroll
+            for (int i = 0; i < ET * 16; ++i) {
+                const int e = (i >> 4) * 32 + acc_feature(i & 15, g);
+                if (e == be) v[i] = -INFINITY;
+            }
+            if (valid && g == 0) {
+                idx[n * k + jj] = be;
+                pk[n * k + jj] = __expf(bv - m) * rden;
+            }
+        }
+    }
+}
+
+template <int DS, int ET>
+static hipError_t run_route(const slicemoe_config &c, const void *h, const void *packed, int32_t *idx, float *p,
+                            hipStream_t s)
+{
+    const PackedLayout L = packed_layout(c);
+    const long long Ns = (long long)c.T * c.S;
+    constexpr int KS = DS / 16;
+    const size_t lds = (size_t)(kRouteHT * KS * 64 + ET * kRouteHT * 2 * 64) * 16 + (kRouteHr + ET * 32) * 4;
+    const long long ntiles = (Ns + 31) / 32;
+    long long blocks = (ntiles + 3) / 4;
+    const long long cap = (long long)num_compute_units() * (lds <= 80 * 1024 ? 2 : 1);
+    if (blocks > cap) blocks = cap;
+    auto kern = route_mfma_kernel<DS, ET>;
+    hipError_t err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (err != hipSuccess) return err;
+    kern<<<(int)blocks, kRouteThreads, lds, s>>>((const bf16_t *)h, Ns, c.E, c.k, (const char *)packed, L.r_w1,
+                                                 L.r_w2, L.r_b1, L.r_b2, idx, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_route_mfma(const slicemoe_config &c, const void *h, const void *packed, int32_t *idx,
+                             float *p, hipStream_t s)
+{
+    if ((long long)c.T * c.S == 0) return hipSuccess;
+    const int ds = c.d / c.S;
+    const int et = (c.E + 31) / 32;
+    if (ds == 64) return et == 1 ? run_route<64, 1>(c, h, packed, idx, p, s) : run_route<64, 2>(c, h, packed, idx, p, s);
+    return et == 1 ? run_route<128, 1>(c, h, packed, idx, p, s) : run_route<128, 2>(c, h, packed, idx, p, s);
+}
+
+}  // namespace slicemoe

@@ -64,10 +64,10 @@ class SliceMoEShape:
         return self.T * self.S * self.k
 
     def capacity(self) -> int:
-        """Per-expert row capacity; -1 when dropless."""
+        """Per-expert row capacity C = ceil(float32(capacity_factor) * Na / E); -1 when dropless."""
         if self.capacity_factor <= 0:
             return -1
-        return int(math.ceil(self.capacity_factor * self.Na / self.E - 1e-9))
+        return int(math.ceil(float(np.float32(self.capacity_factor)) * self.Na / self.E))
 
     def scaled(self, T: int, name: str | None = None) -> "SliceMoEShape":
         """Same layer, fewer (or more) tokens."""

@@ -1,0 +1,83 @@
+"""Host-side checks of the C-ABI library: it loads, exports every declared symbol, and its
+argument validation and sizing logic behave as the header says.  No kernel is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2510_04286_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2510_04286_amd import build
+        build.build()
+    return binding
+
+
+def test_library_exports_every_declared_symbol(B):
+    header = open(os.path.join(ROOT, "include", "slicemoe.h")).read()
+    declared = set(re.findall(r"\b(slicemoe_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    L = B.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_struct_layouts_match_the_header(B):
+    assert ctypes.sizeof(B.slicemoe_config) == 40
+    assert ctypes.sizeof(B.slicemoe_weights) == 9 * ctypes.sizeof(ctypes.c_void_p)
+    assert ctypes.sizeof(B.slicemoe_workspace_layout) == 12 * ctypes.sizeof(ctypes.c_size_t)
+
+
+def test_status_strings(B):
+    assert B.slicemoe_status_string(0) == "ok"
+    assert "workspace" in B.slicemoe_status_string(B.SLICEMOE_ERR_WORKSPACE)
+    assert B.slicemoe_status_string(99) == "unknown status"
+
+
+def test_config_validation_and_kernel_choice(B):
+    ok = B.make_config(16384, 1024, 16, 2, 32, 256)
+    assert B.slicemoe_uses_mfma(ok) == 1
+    assert B.slicemoe_uses_mfma(B.make_config(512, 256, 4, 2, 8, 256, dtype="f32")) == 0
+    assert B.slicemoe_uses_mfma(B.make_config(64, 768, 8, 2, 16, 384)) == 0  # ds = 96: generic kernels
+    assert B.slicemoe_uses_mfma(B.make_config(64, 1024, 16, 2, 32, 256, flags=B.SLICEMOE_FLAG_FORCE_GENERIC)) == 0
+    for bad in [B.make_config(8, 100, 3, 2, 4, 16),      # d % S != 0
+                B.make_config(8, 64, 4, 5, 4, 16),       # k > E
+                B.make_config(-1, 64, 4, 2, 4, 16),
+                B.make_config(8, 64, 4, 0, 4, 16),
+                B.make_config(8, 64, 4, 2, 65, 16),      # E > 64
+                B.make_config(8, 64, 4, 9, 16, 16),      # k > 8
+                B.make_config(8, 768, 8, 2, 16, 384, flags=B.SLICEMOE_FLAG_REQUIRE_MFMA)]:
+        assert B.slicemoe_uses_mfma(bad) == -1
+        assert B.slicemoe_workspace_bytes(bad) == 0 and B.slicemoe_packed_bytes(bad) == 0
+    L = B.lib()
+    bad = B.make_config(8, 100, 3, 2, 4, 16)
+    assert L.slicemoe_forward(ctypes.byref(bad), None, None, None, None, 0, None) == B.SLICEMOE_ERR_INVALID_ARG
+    big = B.make_config(8, 64, 4, 2, 65, 16)
+    assert L.slicemoe_dispatch(ctypes.byref(big), None, None, None, None, None, None, None, 0, None) == B.SLICEMOE_ERR_UNSUPPORTED
+    # null pointers and short workspaces are reported before anything touches the GPU
+    assert L.slicemoe_forward(ctypes.byref(ok), None, None, None, None, 0, None) == B.SLICEMOE_ERR_INVALID_ARG
+    assert L.slicemoe_combine(ctypes.byref(ok), None, None, None, None) == B.SLICEMOE_ERR_INVALID_ARG
+    w = B.slicemoe_weights()
+    one = ctypes.c_void_p(256)  # never dereferenced: the workspace check comes first
+    assert L.slicemoe_forward(ctypes.byref(ok), one, ctypes.byref(w), one, one, 1024, None) == B.SLICEMOE_ERR_WORKSPACE
+    assert L.slicemoe_dispatch(ctypes.byref(ok), one, one, one, one, one, one, one, 16, None) == B.SLICEMOE_ERR_WORKSPACE
+
+
+def test_capacity_and_sizes(B):
+    from paper_2510_04286_amd import workload as wl
+    for name, c in wl.CONFIGS.items():
+        cfg = B.config_of(c)
+        assert B.slicemoe_capacity(cfg) == c.capacity()
+        L = B.slicemoe_get_workspace_layout(cfg)
+        assert L.total == B.slicemoe_workspace_bytes(cfg) > 0
+        offs = [L.topk_idx, L.topk_p, L.counts_raw, L.counts, L.offsets, L.perm, L.inv, L.y, L.stats, L.scratch, L.packed]
+        assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
+        assert L.perm - L.offsets >= (c.E + 1) * 4 and L.stats - L.y >= c.Na * c.ds * 4
+        assert B.slicemoe_dispatch_workspace_bytes(cfg) >= -(-c.Na // 4096) * c.E * 4
+        assert (B.slicemoe_packed_bytes(cfg) > 0) == (c.dtype == "bf16")
+    assert B.slicemoe_capacity(B.make_config(100, 64, 4, 2, 8, 16, capacity_factor=1.1)) == 111  # ceil(1.1f*800/8)
