@@ -162,8 +162,9 @@ def test_expert_ffn_matches_oracle(B, name, T, force_generic):
     err = np.abs(got[:kept] - ref).max() / rms(ref)
     mfma = B.slicemoe_uses_mfma(cfg) == 1
     print(f"\n[ffn {name} T={T} mfma={mfma}] rows={kept} max|err|/rms={err:.3e}")
-    # fp32 arithmetic: 1e-4; bf16 matrix-core path (bf16 hidden activations, y itself not rounded): 1e-2
-    assert err <= (1e-2 if mfma else TOL_F32)
+    # fp32 arithmetic: 1e-4 RMS; bf16 matrix-core path: the layer's bf16 bar applied to y, which is
+    # stricter than asked since y (fp32) has not yet had the final rounding of h'
+    assert err <= (TOL_BF16 if mfma else TOL_F32)
 
 
 def test_expert_ffn_empty_experts_and_ragged_tiles(B):
@@ -186,7 +187,7 @@ def test_expert_ffn_empty_experts_and_ragged_tiles(B):
     B.slicemoe_expert_ffn(cfg, B.to_device(h, shape.dtype), dev(pk.astype(np.float32).reshape(-1)), dev(d["offsets"]),
                           dev(d["perm"]), wd, y)
     err = np.abs(y.cpu().numpy() - ref).max() / rms(ref)
-    assert err <= 1e-2, err
+    assert err <= TOL_BF16, err
 
 
 # ------------------------------------------------------------------ router
