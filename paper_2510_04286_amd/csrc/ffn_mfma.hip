@@ -3,16 +3,22 @@
 //
 //   y[r, :] = GELU(p_r * (x_r W1[e]) + b1[e]) W2[e] + b2[e]          (p (x W1) == (p x) W1)
 //
-// One launch covers all experts.  Work unit: a tile of TM stacked rows of one expert; tiles are
-// enumerated on device from offsets[] (expert-major), each block takes a contiguous range of
-// tiles, so a block changes expert rarely and re-stages weights only then.  A wavefront owns
-// 32*NSUB rows and the whole hidden width; per 32-wide hidden tile it runs GEMM1 (K = ds),
-// applies bias/p/GELU to the 16 accumulators per lane, and feeds them straight into GEMM2 as the
-// B operand (see mfma.h) -- the [rows, He] hidden activations never exist in memory.
-// Expert weights come pre-packed in fragment order and are staged in LDS: all of them when
-// they fit (ds = 64, He = 256: 64 KiB + biases), otherwise in chunks of hidden tiles per row tile.
-// The gather of x rows through perm[] is done by the loads themselves: a lane reads the
-// 16-byte pieces of its own row directly from h in HBM.
+// One launch covers all experts; the per-expert row ranges come from offsets[] on the device.
+// A wavefront owns a unit of 32*NSUB stacked rows and the whole hidden width.  Per 32-wide
+// hidden tile it runs GEMM1 (K = ds), applies bias / p / GELU to its 16 accumulators per lane
+// and feeds them straight into GEMM2 as the B operand (see mfma.h): the [rows, He] hidden
+// activations never exist in memory.  x rows are gathered through perm[] by the loads
+// themselves (each lane reads the 16-byte pieces of its own row from h); loads for the next
+// unit are issued before the current one is computed.  Weights come pre-packed in fragment
+// order and are staged in LDS.
+//
+// Two variants:
+//   resident  a whole expert (W1, W2, biases) fits in LDS (ds = 64, He = 256: 65 KiB, two
+//             blocks per CU).  Stacked rows are split evenly over the blocks regardless of
+//             expert boundaries; a block re-stages weights only when its range crosses into
+//             another expert, and its wavefronts run independently in between.
+//   streamed  larger experts (ds = 128, He = 512: 256 KiB): a block walks tiles of one expert
+//             and streams the weights through LDS in chunks of hidden tiles, per row tile.
 #include "mfma.h"
 
 namespace slicemoe {
@@ -20,25 +26,223 @@ namespace slicemoe {
 constexpr int kFfnThreads = 256;
 constexpr int kFfnWaves = kFfnThreads / 64;
 
-// tanh-form GELU written as z * sigmoid(2*sqrt(2/pi)*(z + 0.044715 z^3)); exp2 and rcp are single
-// hardware instructions.  |error| vs the erf form < 5e-4, below the bf16 rounding applied next.
-__device__ __forceinline__ float gelu_fast(float z)
+// GELU(z) = z * Phi(z) with Phi(z) ~ 0.5 + zc * P(zc^2), zc = clamp(z, -3.5, 3.5), P a degree-5
+// minimax polynomial: |Phi error| < 1.8e-4, i.e. a relative error of GELU well below the bf16
+// rounding (2^-9) applied to the result.  Horner steps with literal coefficients are the cheapest
+// VALU form on gfx950; no transcendental instruction is needed.
+__device__ __forceinline__ float gelu_poly(float z)
 {
-    const float c1 = -2.0f * 0.7978845608028654f * 1.4426950408889634f;
-    const float c3 = c1 * 0.044715f;
-    const float t = z * fmaf(c3, z * z, c1);
-    const float e = __builtin_amdgcn_exp2f(t);
-    return z * __builtin_amdgcn_rcpf(1.0f + e);
+    const float zc = __builtin_amdgcn_fmed3f(z, -3.5f, 3.5f);
+    const float w = zc * zc;
+    float P = -7.907663110e-07f;
+    P = fmaf(P, w, 3.767626183e-05f);
+    P = fmaf(P, w, -7.603790386e-04f);
+    P = fmaf(P, w, 8.699680533e-03f);
+    P = fmaf(P, w, -6.477227479e-02f);
+    P = fmaf(P, w, 3.982652909e-01f);
+    return z * fmaf(zc, P, 0.5f);
+}
+
+template <int DS, int NSUB> struct RowUnit {
+    bf16x8 xb[NSUB][DS / 16];
+    float p[NSUB];
+    int row[NSUB];  // -1: no row
+};
+
+// Issue the gather of one unit: lane j of each 32-row sub-tile reads its row's K pieces.
+template <int DS, int NSUB>
+__device__ __forceinline__ void gather_rows(RowUnit<DS, NSUB> &u, const int (&a)[NSUB], const int (&row)[NSUB],
+                                            const bf16_t *__restrict__ x, const float *__restrict__ pk, int k, int g)
+{
+#pragma unroll
+    for (int sub = 0; sub < NSUB; ++sub) {
+        const bool valid = row[sub] >= 0;
+        u.row[sub] = row[sub];
+        u.p[sub] = valid ? pk[a[sub]] : 0.f;
+        const long long n = a[sub] / k;
+        const uint4 *xp = (const uint4 *)(x + n * DS);
+#pragma unroll
+        for (int ks = 0; ks < DS / 16; ++ks) {
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (valid) v = xp[ks * 2 + g];
+            u.xb[sub][ks] = __builtin_bit_cast(bf16x8, v);
+        }
+    }
+}
+
+// All hidden tiles [ht0, ht0 + nht) staged at w1s / w2s (tile hl at fragment offset hl): GEMM1,
+// activation, GEMM2 accumulation into yacc.
+template <int DS, int NSUB>
+__device__ __forceinline__ void ffn_hidden_tiles(const RowUnit<DS, NSUB> &u, f32x16 (&yacc)[NSUB][DS / 32],
+                                                 const uint4 *__restrict__ w1s, const uint4 *__restrict__ w2s,
+                                                 const float *__restrict__ b1s, int ht0, int nht, int lane, int g)
+{
+    constexpr int KS = DS / 16;
+    constexpr int OT = DS / 32;
+    for (int hl = 0; hl < nht; ++hl) {
+        f32x16 acc[NSUB];
+#pragma unroll
+        for (int sub = 0; sub < NSUB; ++sub)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[sub][r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 a1 = __builtin_bit_cast(bf16x8, w1s[(hl * KS + ks) * 64 + lane]);
+#pragma unroll
+            for (int sub = 0; sub < NSUB; ++sub) acc[sub] = mfma_bf16(a1, u.xb[sub][ks], acc[sub]);
+        }
+        f32x4 bq[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) bq[q] = *(const f32x4 *)(b1s + (ht0 + hl) * 32 + 8 * q + 4 * g);
+        bf16x8 hb[NSUB][2];
+#pragma unroll
+        for (int sub = 0; sub < NSUB; ++sub)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float z = fmaf(acc[sub][r], u.p[sub], bq[r >> 2][r & 3]);
+                hb[sub][r >> 3][r & 7] = (__bf16)gelu_poly(z);
+            }
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int ot = 0; ot < OT; ++ot) {
+                const bf16x8 a2 = __builtin_bit_cast(bf16x8, w2s[((hl * 2 + s) * OT + ot) * 64 + lane]);
+#pragma unroll
+                for (int sub = 0; sub < NSUB; ++sub) yacc[sub][ot] = mfma_bf16(a2, hb[sub][s], yacc[sub][ot]);
+            }
+    }
+}
+
+// y rows (fp32): per output tile a lane holds features 8q + 4g + (0..3) of its own row.
+template <int DS, int NSUB>
+__device__ __forceinline__ void store_rows(const RowUnit<DS, NSUB> &u, const f32x16 (&yacc)[NSUB][DS / 32],
+                                           const float *__restrict__ b2s, float *__restrict__ y, int g)
+{
+#pragma unroll
+    for (int sub = 0; sub < NSUB; ++sub) {
+        if (u.row[sub] < 0) continue;
+        float *yr = y + (size_t)u.row[sub] * DS;
+#pragma unroll
+        for (int ot = 0; ot < DS / 32; ++ot)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int c0 = ot * 32 + 8 * q + 4 * g;
+                const f32x4 bb = *(const f32x4 *)(b2s + c0);
+                f32x4 v;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) v[c] = yacc[sub][ot][4 * q + c] + bb[c];
+                *(f32x4 *)(yr + c0) = v;
+            }
+    }
 }
 
 template <int DS, int NSUB>
-__global__ __launch_bounds__(kFfnThreads) void ffn_mfma_kernel(
+__device__ __forceinline__ void zero_acc(f32x16 (&yacc)[NSUB][DS / 32])
+{
+#pragma unroll
+    for (int sub = 0; sub < NSUB; ++sub)
+#pragma unroll
+        for (int ot = 0; ot < DS / 32; ++ot)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) yacc[sub][ot][r] = 0.f;
+}
+
+// ------------------------------------------------------------------------------ resident
+template <int DS, int NSUB>
+__global__ __launch_bounds__(kFfnThreads, 2) void ffn_resident_kernel(
+    const bf16_t *__restrict__ x, const float *__restrict__ pk, const int32_t *__restrict__ offsets,
+    const int32_t *__restrict__ perm, const char *__restrict__ experts, size_t e_stride, size_t off_w1,
+    size_t off_w2, size_t off_b1, size_t off_b2, int He, int E, int k, float *__restrict__ y)
+{
+    constexpr int KS = DS / 16;
+    constexpr int OT = DS / 32;
+    constexpr int U = 32 * NSUB;  // rows per wavefront unit
+    const int HT = He / 32;
+
+    extern __shared__ __align__(16) char lds[];
+    uint4 *w1s = (uint4 *)lds;                                // [HT][KS][64] fragments
+    uint4 *w2s = w1s + (size_t)HT * KS * 64;                  // [HT][2][OT][64] fragments
+    float *b1s = (float *)(w2s + (size_t)HT * 2 * OT * 64);   // [He]
+    float *b2s = b1s + He;                                    // [DS]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int j = lane & 31;
+    const int g = lane >> 5;
+
+    // even split of the kept rows over the blocks, in whole units
+    const int n_kept = offsets[E];
+    const int units_total = (n_kept + U - 1) / U;
+    const int units_per_block = (units_total + gridDim.x - 1) / gridDim.x;
+    const long long r_begin = (long long)blockIdx.x * units_per_block * U;
+    const int r_end = (int)min((long long)n_kept, r_begin + (long long)units_per_block * U);
+
+    int e = 0;
+    int r = (int)min(r_begin, (long long)n_kept);
+    while (r < r_end) {
+        while (offsets[e + 1] <= r) ++e;
+        const int seg_end = min(offsets[e + 1], r_end);
+        const char *ew = experts + (size_t)e * e_stride;
+        __syncthreads();  // everyone is done with the previous expert's weights
+        {
+            const uint4 *g1 = (const uint4 *)(ew + off_w1);
+            const uint4 *g2 = (const uint4 *)(ew + off_w2);
+            const float *gb1 = (const float *)(ew + off_b1);
+            const float *gb2 = (const float *)(ew + off_b2);
+            for (int i = tid; i < HT * KS * 64; i += kFfnThreads) w1s[i] = g1[i];
+            for (int i = tid; i < HT * 2 * OT * 64; i += kFfnThreads) w2s[i] = g2[i];
+            for (int i = tid; i < He; i += kFfnThreads) b1s[i] = gb1[i];
+            for (int i = tid; i < DS; i += kFfnThreads) b2s[i] = gb2[i];
+        }
+        __syncthreads();
+
+        // units of this segment: unit q covers rows r + q*U ..., this wavefront takes q = wave, wave+4, ...
+        const int nunits = (seg_end - r + U - 1) / U;
+        auto unit_rows = [&](int q, int (&row)[NSUB]) {
+#pragma unroll
+            for (int sub = 0; sub < NSUB; ++sub) {
+                const int rr = r + q * U + sub * 32 + j;
+                row[sub] = (q < nunits && rr < seg_end) ? rr : -1;
+            }
+        };
+        auto load_perm = [&](const int (&row)[NSUB], int (&a)[NSUB]) {
+#pragma unroll
+            for (int sub = 0; sub < NSUB; ++sub) a[sub] = row[sub] >= 0 ? perm[row[sub]] : 0;
+        };
+        int row_c[NSUB], a_c[NSUB], row_n[NSUB], a_n[NSUB];
+        RowUnit<DS, NSUB> cur;
+        unit_rows(wave, row_c);
+        load_perm(row_c, a_c);
+        gather_rows<DS, NSUB>(cur, a_c, row_c, x, pk, k, g);
+        unit_rows(wave + kFfnWaves, row_n);
+        load_perm(row_n, a_n);
+        for (int q = wave; q < nunits; q += kFfnWaves) {
+            // next unit's rows (indices arrived during the previous unit), indices of the one after
+            RowUnit<DS, NSUB> nxt;
+            gather_rows<DS, NSUB>(nxt, a_n, row_n, x, pk, k, g);
+            unit_rows(q + 2 * kFfnWaves, row_n);
+            load_perm(row_n, a_n);
+
+            f32x16 yacc[NSUB][OT];
+            zero_acc<DS, NSUB>(yacc);
+            ffn_hidden_tiles<DS, NSUB>(cur, yacc, w1s, w2s, b1s, 0, HT, lane, g);
+            store_rows<DS, NSUB>(cur, yacc, b2s, y, g);
+            cur = nxt;
+        }
+        r = seg_end;
+    }
+}
+
+// ------------------------------------------------------------------------------ streamed
+template <int DS, int NSUB>
+__global__ __launch_bounds__(kFfnThreads) void ffn_streamed_kernel(
     const bf16_t *__restrict__ x, const float *__restrict__ pk, const int32_t *__restrict__ offsets,
     const int32_t *__restrict__ perm, const char *__restrict__ experts, size_t e_stride, size_t off_w1,
     size_t off_w2, size_t off_b1, size_t off_b2, int He, int E, int k, int hc, float *__restrict__ y)
 {
-    constexpr int KS = DS / 16;  // K-steps of GEMM1
-    constexpr int OT = DS / 32;  // output tiles of GEMM2
+    constexpr int KS = DS / 16;
+    constexpr int OT = DS / 32;
     constexpr int TM = kFfnWaves * NSUB * 32;
     const int HT = He / 32;
     const int nchunks = HT / hc;
@@ -79,140 +283,69 @@ __global__ __launch_bounds__(kFfnThreads) void ffn_mfma_kernel(
         const char *ew = experts + (size_t)e * e_stride;
         const bool new_expert = e != cur_e;
 
-        // ---- gather this wavefront's rows: B fragments of GEMM1 straight from h
-        bf16x8 xb[NSUB][KS];
-        float pr[NSUB];
-        int row[NSUB];
+        int row[NSUB], a[NSUB];
 #pragma unroll
         for (int sub = 0; sub < NSUB; ++sub) {
-            row[sub] = row_begin + (wave * NSUB + sub) * 32 + j;
-            const bool valid = row[sub] < row_end;
-            int a = 0;
-            if (valid) a = perm[row[sub]];
-            pr[sub] = valid ? pk[a] : 0.f;
-            const long long n = a / k;
-            const uint4 *xp = (const uint4 *)(x + n * DS);
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                uint4 v = make_uint4(0, 0, 0, 0);
-                if (valid) v = xp[ks * 2 + g];
-                xb[sub][ks] = __builtin_bit_cast(bf16x8, v);
-            }
-            if (!valid) row[sub] = -1;
+            const int rr = row_begin + (wave * NSUB + sub) * 32 + j;
+            row[sub] = rr < row_end ? rr : -1;
+            a[sub] = row[sub] >= 0 ? perm[rr] : 0;
         }
+        RowUnit<DS, NSUB> cur;
+        gather_rows<DS, NSUB>(cur, a, row, x, pk, k, g);
 
         f32x16 yacc[NSUB][OT];
-#pragma unroll
-        for (int sub = 0; sub < NSUB; ++sub)
-#pragma unroll
-            for (int ot = 0; ot < OT; ++ot)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) yacc[sub][ot][r] = 0.f;
-
+        zero_acc<DS, NSUB>(yacc);
         for (int ch = 0; ch < nchunks; ++ch) {
-            if (new_expert || nchunks > 1) {
-                __syncthreads();  // everyone is done with the previous contents
-                const uint4 *g1 = (const uint4 *)(ew + off_w1) + (size_t)ch * hc * KS * 64;
-                const uint4 *g2 = (const uint4 *)(ew + off_w2) + (size_t)ch * hc * 2 * OT * 64;
-                for (int i = tid; i < hc * KS * 64; i += kFfnThreads) w1s[i] = g1[i];
-                for (int i = tid; i < hc * 2 * OT * 64; i += kFfnThreads) w2s[i] = g2[i];
-                if (new_expert && ch == 0) {
-                    const float *gb1 = (const float *)(ew + off_b1);
-                    const float *gb2 = (const float *)(ew + off_b2);
-                    for (int i = tid; i < He; i += kFfnThreads) b1s[i] = gb1[i];
-                    for (int i = tid; i < DS; i += kFfnThreads) b2s[i] = gb2[i];
-                }
-                __syncthreads();
+            __syncthreads();  // everyone is done with the previous contents
+            const uint4 *g1 = (const uint4 *)(ew + off_w1) + (size_t)ch * hc * KS * 64;
+            const uint4 *g2 = (const uint4 *)(ew + off_w2) + (size_t)ch * hc * 2 * OT * 64;
+            for (int i = tid; i < hc * KS * 64; i += kFfnThreads) w1s[i] = g1[i];
+            for (int i = tid; i < hc * 2 * OT * 64; i += kFfnThreads) w2s[i] = g2[i];
+            if (new_expert && ch == 0) {
+                const float *gb1 = (const float *)(ew + off_b1);
+                const float *gb2 = (const float *)(ew + off_b2);
+                for (int i = tid; i < He; i += kFfnThreads) b1s[i] = gb1[i];
+                for (int i = tid; i < DS; i += kFfnThreads) b2s[i] = gb2[i];
             }
-            for (int hl = 0; hl < hc; ++hl) {
-                const int ht = ch * hc + hl;
-                // ---- GEMM1: 32 hidden features x (NSUB*32) rows, K = DS
-                f32x16 acc[NSUB];
-#pragma unroll
-                for (int sub = 0; sub < NSUB; ++sub)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[sub][r] = 0.f;
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 a1 = __builtin_bit_cast(bf16x8, w1s[(hl * KS + ks) * 64 + lane]);
-#pragma unroll
-                    for (int sub = 0; sub < NSUB; ++sub) acc[sub] = mfma_bf16(a1, xb[sub][ks], acc[sub]);
-                }
-                // ---- bias, Eq. 1 weight, GELU, round to bf16: B fragments of GEMM2
-                f32x4 bq[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) bq[q] = *(const f32x4 *)(b1s + ht * 32 + 8 * q + 4 * g);
-                bf16x8 hb[NSUB][2];
-#pragma unroll
-                for (int sub = 0; sub < NSUB; ++sub)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const float z = fmaf(acc[sub][r], pr[sub], bq[r >> 2][r & 3]);
-                        hb[sub][r >> 3][r & 7] = (__bf16)gelu_fast(z);
-                    }
-                // ---- GEMM2: accumulate this hidden tile into the ds outputs
-#pragma unroll
-                for (int s = 0; s < 2; ++s)
-#pragma unroll
-                    for (int ot = 0; ot < OT; ++ot) {
-                        const bf16x8 a2 = __builtin_bit_cast(bf16x8, w2s[((hl * 2 + s) * OT + ot) * 64 + lane]);
-#pragma unroll
-                        for (int sub = 0; sub < NSUB; ++sub)
-                            yacc[sub][ot] = mfma_bf16(a2, hb[sub][s], yacc[sub][ot]);
-                    }
-            }
+            __syncthreads();
+            ffn_hidden_tiles<DS, NSUB>(cur, yacc, w1s, w2s, b1s, ch * hc, hc, lane, g);
         }
         cur_e = e;
-
-        // ---- y rows (fp32): lane holds, per output tile, features 8q + 4g + (0..3) of its own row
-#pragma unroll
-        for (int sub = 0; sub < NSUB; ++sub) {
-            if (row[sub] < 0) continue;
-            float *yr = y + (size_t)row[sub] * DS;
-#pragma unroll
-            for (int ot = 0; ot < OT; ++ot)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int c0 = ot * 32 + 8 * q + 4 * g;
-                    const f32x4 bb = *(const f32x4 *)(b2s + c0);
-                    f32x4 v;
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) v[c] = yacc[sub][ot][4 * q + c] + bb[c];
-                    *(f32x4 *)(yr + c0) = v;
-                }
-        }
+        store_rows<DS, NSUB>(cur, yacc, b2s, y, g);
     }
 }
 
 struct FfnPlan {
-    int nsub, hc;
+    bool resident;
+    int hc;
     size_t lds;
 };
 
-// Pick rows per wavefront and hidden tiles per LDS chunk.
+// Whole expert resident in LDS when it fits in half of a CU's LDS, else hidden tiles per chunk.
 static FfnPlan plan_ffn(int ds, int He, int E)
 {
     const int HT = He / 32, KS = ds / 16, OT = ds / 32;
     const size_t frag_per_ht = (size_t)(KS + 2 * OT) * 1024;  // bytes of W1+W2 fragments per hidden tile
-    const size_t fixed = (size_t)(He + ds + E + 1) * 4 + 64;
-    FfnPlan p;
-    p.nsub = 2;
     const size_t dev_max = (size_t)max_lds_per_block();
-    // two blocks per CU when a whole expert fits in half of the LDS; a ds = 128 block needs the
-    // whole register file of its CU anyway, so its chunks may take most of the LDS
-    const size_t budget_resident = dev_max < 72 * 1024 ? dev_max : 72 * 1024;
-    const size_t want_stream = ds > 64 ? 140 * 1024 : 64 * 1024;
-    const size_t budget_stream = dev_max < want_stream ? dev_max : want_stream;
-    if (frag_per_ht * HT + fixed <= budget_resident) {
+    FfnPlan p;
+    const size_t resident_bytes = frag_per_ht * HT + (size_t)(He + ds) * 4;
+    if (ds == 64 && resident_bytes <= 78 * 1024 && resident_bytes <= dev_max) {
+        p.resident = true;
         p.hc = HT;
-    } else {
-        p.hc = 1;
-        for (int c = HT; c >= 1; --c)
-            if (HT % c == 0 && frag_per_ht * c + fixed <= budget_stream) {
-                p.hc = c;
-                break;
-            }
+        p.lds = resident_bytes;
+        return p;
     }
+    // a streamed block needs the whole register file of its CU anyway, so chunks may take most of the LDS
+    const size_t fixed = (size_t)(He + ds + E + 1) * 4 + 64;
+    const size_t want = 140 * 1024;
+    const size_t budget = dev_max < want ? dev_max : want;
+    p.resident = false;
+    p.hc = 1;
+    for (int c = HT; c >= 1; --c)
+        if (HT % c == 0 && frag_per_ht * c + fixed <= budget) {
+            p.hc = c;
+            break;
+        }
     p.lds = frag_per_ht * p.hc + fixed;
     return p;
 }
@@ -224,17 +357,29 @@ static hipError_t run_ffn(const slicemoe_config &c, const FfnPlan &pl, const voi
 {
     const PackedLayout L = packed_layout(c);
     const long long Na = (long long)c.T * c.S * c.k;
-    constexpr int TM = kFfnWaves * NSUB * 32;
-    const long long max_tiles = (Na + TM - 1) / TM + c.E;
-    const int blocks_per_cu = pl.lds <= 80 * 1024 ? 2 : 1;
-    long long blocks = (long long)num_compute_units() * blocks_per_cu;
-    if (blocks > max_tiles) blocks = max_tiles;
-    auto kern = ffn_mfma_kernel<DS, NSUB>;
-    hipError_t err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds);
-    if (err != hipSuccess) return err;
-    kern<<<(int)blocks, kFfnThreads, pl.lds, s>>>((const bf16_t *)h, p, offsets, perm,
-                                                  (const char *)packed + L.experts, L.e_stride, L.e_w1, L.e_w2,
-                                                  L.e_b1, L.e_b2, c.He, c.E, c.k, pl.hc, y);
+    const char *experts = (const char *)packed + L.experts;
+    hipError_t err;
+    if (pl.resident) {
+        constexpr int U = 32 * NSUB;
+        long long blocks = (long long)num_compute_units() * 2;
+        const long long max_blocks = (Na + U - 1) / U;
+        if (blocks > max_blocks) blocks = max_blocks;
+        auto kern = ffn_resident_kernel<DS, NSUB>;
+        err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds);
+        if (err != hipSuccess) return err;
+        kern<<<(int)blocks, kFfnThreads, pl.lds, s>>>((const bf16_t *)h, p, offsets, perm, experts, L.e_stride, L.e_w1,
+                                                      L.e_w2, L.e_b1, L.e_b2, c.He, c.E, c.k, y);
+    } else {
+        constexpr int TM = kFfnWaves * NSUB * 32;
+        const long long max_tiles = (Na + TM - 1) / TM + c.E;
+        long long blocks = (long long)num_compute_units() * (pl.lds <= 78 * 1024 ? 2 : 1);
+        if (blocks > max_tiles) blocks = max_tiles;
+        auto kern = ffn_streamed_kernel<DS, NSUB>;
+        err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds);
+        if (err != hipSuccess) return err;
+        kern<<<(int)blocks, kFfnThreads, pl.lds, s>>>((const bf16_t *)h, p, offsets, perm, experts, L.e_stride, L.e_w1,
+                                                      L.e_w2, L.e_b1, L.e_b2, c.He, c.E, c.k, pl.hc, y);
+    }
     return hipGetLastError();
 }
 
