@@ -239,7 +239,7 @@ slicemoe_status slicemoe_dispatch(const slicemoe_config *cfg, const int32_t *top
     if (!topk_idx || !counts_raw || !counts || !offsets || !perm || !inv) return SLICEMOE_ERR_INVALID_ARG;
     if (!workspace || workspace_bytes < dispatch_scratch_bytes(*cfg)) return SLICEMOE_ERR_WORKSPACE;
     if (misaligned(workspace, 256)) return SLICEMOE_ERR_INVALID_ARG;
-    return launch_dispatch(*cfg, topk_idx, counts_raw, counts, offsets, perm, inv, (int32_t *)workspace,
+    return launch_dispatch(*cfg, topk_idx, counts_raw, counts, offsets, perm, inv, (int32_t *)workspace, nullptr,
                            (hipStream_t)stream) == hipSuccess
                ? SLICEMOE_OK
                : SLICEMOE_ERR_HIP;
@@ -317,14 +317,13 @@ slicemoe_status slicemoe_forward(const slicemoe_config *cfg, const void *h, cons
     }
     hipError_t e = mfma ? launch_route_mfma(*cfg, h, packed, idx, p, s) : launch_route_generic(*cfg, h, *w, idx, p, s);
     if (e != hipSuccess) return SLICEMOE_ERR_HIP;
-    e = launch_dispatch(*cfg, idx, counts_raw, counts, offsets, perm, inv, (int32_t *)(ws + L.scratch), s);
+    // the load statistics ride along in the scan kernel of the dispatch
+    e = launch_dispatch(*cfg, idx, counts_raw, counts, offsets, perm, inv, (int32_t *)(ws + L.scratch), stats, s);
     if (e != hipSuccess) return SLICEMOE_ERR_HIP;
     e = mfma ? launch_ffn_mfma(*cfg, h, p, offsets, perm, packed, y, s)
              : launch_ffn_generic(*cfg, h, p, offsets, perm, *w, y, s);
     if (e != hipSuccess) return SLICEMOE_ERR_HIP;
     e = launch_combine(*cfg, y, inv, h_out, s);
-    if (e != hipSuccess) return SLICEMOE_ERR_HIP;
-    e = launch_load_stats(*cfg, counts_raw, counts, stats, s);
     return e == hipSuccess ? SLICEMOE_OK : SLICEMOE_ERR_HIP;
 }
 

@@ -47,7 +47,7 @@ PackedLayout packed_layout(const slicemoe_config &cfg);
 
 // ---- dispatch geometry ----------------------------------------------------------------
 constexpr int kDispThreads = 256;
-constexpr int kDispItems = 16;
+constexpr int kDispItems = 4;
 constexpr int kDispChunk = kDispThreads * kDispItems;  // assignments per block
 
 // ---- kernel launchers (each only enqueues; returns hipGetLastError) --------------------
@@ -57,7 +57,7 @@ hipError_t launch_route_mfma(const slicemoe_config &c, const void *h, const void
                              int32_t *idx, float *p, hipStream_t s);
 hipError_t launch_dispatch(const slicemoe_config &c, const int32_t *idx, int32_t *counts_raw,
                            int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv,
-                           int32_t *block_counts, hipStream_t s);
+                           int32_t *block_counts, float *stats /* nullable */, hipStream_t s);
 hipError_t launch_ffn_generic(const slicemoe_config &c, const void *h, const float *p,
                               const int32_t *offsets, const int32_t *perm, const slicemoe_weights &w,
                               float *y, hipStream_t s);

@@ -37,10 +37,16 @@ __global__ __launch_bounds__(kDispThreads) void dispatch_hist_kernel(
     if (tid < 64) cnt[tid] = 0;
     __syncthreads();
     const int base = blockIdx.x * kDispChunk;
+    int ex[kDispItems];
+#pragma unroll
     for (int i = 0; i < kDispItems; ++i) {
         const int a = base + i * kDispThreads + tid;
-        const bool valid = a < Na;
-        const int e = valid ? clamp_expert(idx[a], E) : 0;
+        ex[i] = a < Na ? clamp_expert(idx[a], E) : -1;
+    }
+#pragma unroll
+    for (int i = 0; i < kDispItems; ++i) {
+        const bool valid = ex[i] >= 0;
+        const int e = valid ? ex[i] : 0;
         const unsigned long long m = same_expert_mask(e, valid, nbits);
         const unsigned long long below = m & ((1ull << lane) - 1ull);
         if (valid && below == 0) atomicAdd(&cnt[e], __popcll(m));
@@ -49,15 +55,46 @@ __global__ __launch_bounds__(kDispThreads) void dispatch_hist_kernel(
     if (tid < E) block_counts[(size_t)blockIdx.x * E + tid] = cnt[tid];
 }
 
+// Load statistics of a routed batch from the per-expert counts: one wavefront, lane e owns
+// expert e (E <= 64), sums by cross-lane reduction.
+//   stats[0] = CV^2 (population variance; the capacity loss of Eq. 2 divided by alpha)
+//   stats[1] = ELE = -sum load_e log load_e / log E (Section 4)     stats[2] = dropped fraction
+//   stats[3] = CV^2 with the sample variance
+__device__ __forceinline__ double wave_sum(double v)
+{
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+__device__ __forceinline__ void load_stats_wave(int raw, int kept_e, bool have, int E, float *__restrict__ stats)
+{
+    const double c = have ? (double)raw : 0.0;
+    const double sum = wave_sum(c);
+    const double kept = wave_sum(have ? (double)kept_e : 0.0);
+    const double mean = sum / E;
+    const double dl = have ? c - mean : 0.0;
+    const double ss = wave_sum(dl * dl);
+    const double l = (have && raw > 0) ? c / sum : 1.0;
+    const double ent = wave_sum(-l * (double)logf((float)l));
+    if ((threadIdx.x & 63) == 0) {
+        stats[0] = mean > 0 ? (float)(ss / E / (mean * mean)) : 0.f;
+        stats[1] = E > 1 ? (float)(ent / (double)logf((float)E)) : 1.f;
+        stats[2] = sum > 0 ? (float)(1.0 - kept / sum) : 0.f;
+        stats[3] = (mean > 0 && E > 1) ? (float)(ss / (E - 1) / (mean * mean)) : 0.f;
+    }
+}
+
 // One block of 1024 threads.  Thread (seg, e) with e = tid % Epow2 sums a contiguous range of
 // chunks for expert e; the per-segment sums are scanned serially per expert (<= 1024/Epow2
 // segments), then each thread rewrites its range as exclusive prefixes.
 __global__ __launch_bounds__(1024) void dispatch_scan_kernel(
     int32_t *__restrict__ block_counts, int nblocks, int E, int Epow2, long long capacity,
-    int32_t *__restrict__ counts_raw, int32_t *__restrict__ counts, int32_t *__restrict__ offsets)
+    int32_t *__restrict__ counts_raw, int32_t *__restrict__ counts, int32_t *__restrict__ offsets,
+    float *__restrict__ stats /* may be null */)
 {
     __shared__ int seg_sum[1024];
     __shared__ int kept[64];
+    __shared__ int raw[64];
     const int tid = threadIdx.x;
     const int e = tid % Epow2;
     const int seg = tid / Epow2;
@@ -81,6 +118,7 @@ __global__ __launch_bounds__(1024) void dispatch_scan_kernel(
         const int c = (capacity >= 0 && run > capacity) ? (int)capacity : run;
         counts[e] = c;
         kept[e] = c;
+        raw[e] = run;
     }
     __syncthreads();
     if (e < E) {
@@ -99,6 +137,10 @@ __global__ __launch_bounds__(1024) void dispatch_scan_kernel(
             run += kept[x];
         }
         offsets[E] = run;
+    }
+    if (stats && tid >= 64 && tid < 128) {  // second wavefront: the first one is busy with offsets
+        const int x = tid - 64;
+        load_stats_wave(x < E ? raw[x] : 0, x < E ? kept[x] : 0, x < E, E, stats);
     }
 }
 
@@ -121,11 +163,14 @@ __global__ __launch_bounds__(kDispThreads) void dispatch_scatter_kernel(
 #pragma unroll
     for (int i = 0; i < kDispItems; ++i) {
         const int a = base + i * kDispThreads + tid;
-        const bool valid = a < Na;
-        const int e = valid ? clamp_expert(idx[a], E) : 0;
+        ex[i] = a < Na ? clamp_expert(idx[a], E) : -1;
+    }
+#pragma unroll
+    for (int i = 0; i < kDispItems; ++i) {
+        const bool valid = ex[i] >= 0;
+        const int e = valid ? ex[i] : 0;
         const unsigned long long m = same_expert_mask(e, valid, nbits);
         const int below = __popcll(m & ((1ull << lane) - 1ull));
-        ex[i] = valid ? e : -1;
         rk[i] = below;
         if (valid && below == 0) wcnt[i][wave][e] = __popcll(m);
     }
@@ -158,7 +203,7 @@ __global__ __launch_bounds__(kDispThreads) void dispatch_scatter_kernel(
 
 hipError_t launch_dispatch(const slicemoe_config &c, const int32_t *idx, int32_t *counts_raw,
                            int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv,
-                           int32_t *block_counts, hipStream_t s)
+                           int32_t *block_counts, float *stats, hipStream_t s)
 {
     const long long Na = (long long)c.T * c.S * c.k;
     const int nblocks = (int)((Na + kDispChunk - 1) / kDispChunk);
@@ -168,37 +213,21 @@ hipError_t launch_dispatch(const slicemoe_config &c, const int32_t *idx, int32_t
     const long long cap = slicemoe_capacity(&c);
     if (nblocks > 0) dispatch_hist_kernel<<<nblocks, kDispThreads, 0, s>>>(idx, (int)Na, c.E, nbits, block_counts);
     dispatch_scan_kernel<<<1, 1024, 0, s>>>(block_counts, nblocks, c.E, Epow2, cap, counts_raw, counts,
-                                           offsets);
+                                           offsets, stats);
     if (nblocks > 0)
         dispatch_scatter_kernel<<<nblocks, kDispThreads, 0, s>>>(idx, (int)Na, c.E, nbits, cap, block_counts,
                                                                 offsets, perm, inv);
     return hipGetLastError();
 }
 
-// ---- load statistics (Eq. 2 statistic, ELE of Section 4) --------------------------------
-__global__ void load_stats_kernel(const int32_t *__restrict__ counts_raw, const int32_t *__restrict__ counts,
-                                  int E, float *__restrict__ stats)
+// ---- load statistics on their own (Eq. 2 statistic, ELE of Section 4) ---------------------
+__global__ __launch_bounds__(64) void load_stats_kernel(const int32_t *__restrict__ counts_raw,
+                                                        const int32_t *__restrict__ counts, int E,
+                                                        float *__restrict__ stats)
 {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    double sum = 0.0, kept = 0.0;
-    for (int e = 0; e < E; ++e) {
-        sum += counts_raw[e];
-        kept += counts[e];
-    }
-    const double mean = sum / E;
-    double ss = 0.0, ent = 0.0;
-    for (int e = 0; e < E; ++e) {
-        const double dl = counts_raw[e] - mean;
-        ss += dl * dl;
-        if (counts_raw[e] > 0) {
-            const double l = counts_raw[e] / sum;
-            ent -= l * log(l);
-        }
-    }
-    stats[0] = mean > 0 ? (float)(ss / E / (mean * mean)) : 0.f;
-    stats[1] = E > 1 ? (float)(ent / log((double)E)) : 1.f;
-    stats[2] = sum > 0 ? (float)(1.0 - kept / sum) : 0.f;
-    stats[3] = (mean > 0 && E > 1) ? (float)(ss / (E - 1) / (mean * mean)) : 0.f;
+    const int x = threadIdx.x;
+    const bool have = x < E;
+    load_stats_wave(have ? counts_raw[x] : 0, have ? counts[x] : 0, have, E, stats);
 }
 
 hipError_t launch_load_stats(const slicemoe_config &c, const int32_t *counts_raw, const int32_t *counts,
