@@ -130,8 +130,8 @@ def main():
     bytes_ = {
         "route": Ns * ds * 2 + Na * 8,
         "dispatch": Na * 4 + n_kept * 4 + Na * 4,
-        "expert_ffn": n_kept * (ds * 2 + 8 + ds * 4),
-        "combine": n_kept * ds * 4 + Na * 4 + Ns * ds * 2,
+        "expert_ffn": n_kept * (ds * 2 + 8 + ds * 2),  # x row + perm/p + fp16 y row
+        "combine": n_kept * ds * 2 + Na * 4 + Ns * ds * 2,
     }
     stages = {}
     for n in names:
@@ -147,7 +147,7 @@ def main():
 
     t_ffn = stage_ms["expert_ffn"] * 1e-3
     achieved = flops["expert_ffn"] / t_ffn / 1e12
-    roofline = {"kernel": "ffn_mfma_kernel", "bound": "mfma", "achieved": round(achieved, 2),
+    roofline = {"kernel": "ffn_resident_kernel" if shape.ds == 64 else "ffn_streamed_kernel", "bound": "mfma", "achieved": round(achieved, 2),
                 "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_BF16_TFLOPS, 4),
                 "traffic": FFN_TRAFFIC_BYTES.get(args.workload), "launch_us": round(t_ffn * 1e6, 2),
                 "flops_per_launch": flops["expert_ffn"], "hbm_bytes_algorithmic": bytes_["expert_ffn"]}

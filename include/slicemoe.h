@@ -19,7 +19,10 @@
  *   - Linear layers are y = x W + b with W stored [in, out] row-major; expert tensors carry
  *     the expert index on the leading axis.
  *   - dtype is the storage type of h, h' and all weights (fp32 or bf16 bit patterns);
- *     accumulation is always fp32.  topk_p and y are always fp32, indices are int32.
+ *     accumulation is always fp32.  topk_p is fp32, indices are int32.  The stacked expert
+ *     outputs y are fp32 with fp32 storage and IEEE fp16 with bf16 storage (three more
+ *     mantissa bits than bf16, so the one rounding of h' after the k-sum stays the only
+ *     significant one; |y| beyond 65504 would overflow).
  *   - Limits: 1 <= k <= min(E, 8), E <= 64, d % S == 0, T*S*k < 2^31.  The matrix-core
  *     (MFMA) kernels need dtype = bf16, Hr = 256, ds in {64, 128}, He % 64 == 0; any
  *     other shape runs on slower generic kernels unless SLICEMOE_FLAG_REQUIRE_MFMA is set.
@@ -93,7 +96,7 @@ typedef struct {
     size_t offsets;    /* int32 [E+1]                                      */
     size_t perm;       /* int32 [T*S*k]                                    */
     size_t inv;        /* int32 [T*S*k]                                    */
-    size_t y;          /* float [T*S*k, ds]                                */
+    size_t y;          /* float or fp16 [T*S*k, ds] (see dtype above)      */
     size_t stats;      /* float [4], see slicemoe_load_stats               */
     size_t scratch;    /* dispatch scratch                                 */
     size_t packed;     /* on-the-fly packed weights                        */
@@ -159,21 +162,21 @@ slicemoe_status slicemoe_dispatch(const slicemoe_config *cfg, const int32_t *top
  *   y[r, :] = GELU((topk_p[a] * x[n, :]) W1[e] + b1[e]) W2[e] + b2[e]
  * The gather of x and the Eq. 1 weighting are fused into the kernel (no stacked copy of the
  * inputs is materialised); the He-wide hidden activations never leave the chip.
- *   y [T*S*k, ds] out float; rows >= offsets[E] are left untouched.
- * The MFMA kernel rounds the hidden activations to bf16 and uses the tanh form of GELU
- * (|error| < 5e-4, below that rounding); the generic kernel uses erf.
+ *   y [T*S*k, ds] out, fp32 (fp32 storage) or fp16 (bf16 storage); rows >= offsets[E] are left untouched.
+ * The MFMA kernel rounds the hidden activations to bf16 and evaluates GELU(z) = z Phi(z) with a
+ * clamped polynomial for Phi (|error| < 1.8e-4, below that rounding); the generic kernel uses erf.
  */
 slicemoe_status slicemoe_expert_ffn(const slicemoe_config *cfg, const void *h, const float *topk_p,
                                     const int32_t *offsets, const int32_t *perm,
-                                    const slicemoe_weights *w, float *y,
+                                    const slicemoe_weights *w, void *y,
                                     void *workspace, size_t workspace_bytes, slicemoe_stream_t stream);
 
 /*
  * Combine (Section 3.1): h'[n, :] = sum over the kept assignments j of slice n of
- * y[inv[n*k + j], :], summed in fp32 in ascending j, rounded once to the storage dtype and
+ * y[inv[n*k + j], :] (fp32 or fp16, as above), summed in fp32 in ascending j, rounded once to the storage dtype and
  * written at h_out[t, s*ds : (s+1)*ds].  A slice with all k assignments dropped gives zeros.
  */
-slicemoe_status slicemoe_combine(const slicemoe_config *cfg, const float *y, const int32_t *inv,
+slicemoe_status slicemoe_combine(const slicemoe_config *cfg, const void *y, const int32_t *inv,
                                  void *h_out, slicemoe_stream_t stream);
 
 /*

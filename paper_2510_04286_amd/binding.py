@@ -127,6 +127,11 @@ def _tdtype(cfg):
     return torch.bfloat16 if cfg.dtype == SLICEMOE_BF16 else torch.float32
 
 
+def y_dtype(cfg):
+    """Element type of the stacked expert outputs y: fp16 with bf16 storage, fp32 with fp32 storage."""
+    return torch.float16 if cfg.dtype == SLICEMOE_BF16 else torch.float32
+
+
 def _weights(cfg, w) -> slicemoe_weights:
     """dict of device tensors (logical layout, optional 'packed' uint8 buffer) -> C struct."""
     dt = _tdtype(cfg)
@@ -220,13 +225,13 @@ def slicemoe_expert_ffn(cfg, h, topk_p, offsets, perm, w, y, workspace=None, str
                                      _ptr(topk_p, torch.float32, Na, "topk_p"),
                                      _ptr(offsets, torch.int32, cfg.E + 1, "offsets"),
                                      _ptr(perm, torch.int32, Na, "perm"), ctypes.byref(ws),
-                                     _ptr(y, torch.float32, Na * (cfg.d // cfg.S), "y"), wsp, wsb, _stream(stream)),
+                                     _ptr(y, y_dtype(cfg), Na * (cfg.d // cfg.S), "y"), wsp, wsb, _stream(stream)),
            "slicemoe_expert_ffn")
 
 
 def slicemoe_combine(cfg, y, inv, h_out, stream=None):
     Na = cfg.T * cfg.S * cfg.k
-    _check(lib().slicemoe_combine(ctypes.byref(cfg), _ptr(y, torch.float32, Na * (cfg.d // cfg.S), "y"),
+    _check(lib().slicemoe_combine(ctypes.byref(cfg), _ptr(y, y_dtype(cfg), Na * (cfg.d // cfg.S), "y"),
                                   _ptr(inv, torch.int32, Na, "inv"),
                                   _ptr(h_out, _tdtype(cfg), cfg.T * cfg.d, "h_out"), _stream(stream)),
            "slicemoe_combine")
@@ -282,7 +287,7 @@ def workspace_views(cfg, workspace: torch.Tensor) -> dict:
     ds = cfg.d // cfg.S
 
     def view(off, n, dt):
-        return workspace[off:off + n * 4].view(dt)
+        return workspace[off:off + n * torch.empty(0, dtype=dt).element_size()].view(dt)
 
     return {
         "topk_idx": view(L.topk_idx, Na, torch.int32).view(-1, cfg.k),
@@ -292,6 +297,6 @@ def workspace_views(cfg, workspace: torch.Tensor) -> dict:
         "offsets": view(L.offsets, cfg.E + 1, torch.int32),
         "perm": view(L.perm, Na, torch.int32),
         "inv": view(L.inv, Na, torch.int32),
-        "y": view(L.y, Na * ds, torch.float32).view(-1, ds),
+        "y": view(L.y, Na * ds, y_dtype(cfg)).view(-1, ds),
         "stats": view(L.stats, 4, torch.float32),
     }

@@ -103,7 +103,7 @@ static void make_layout(const slicemoe_config &c, slicemoe_workspace_layout *o)
     o->offsets = at;    at = align_up(at + (size_t)(c.E + 1) * 4, 256);
     o->perm = at;       at = align_up(at + Na * 4, 256);
     o->inv = at;        at = align_up(at + Na * 4, 256);
-    o->y = at;          at = align_up(at + Na * ds * 4, 256);
+    o->y = at;          at = align_up(at + Na * ds * y_elem_bytes(c.dtype), 256);
     o->stats = at;      at = align_up(at + 4 * 4, 256);
     o->scratch = at;    at += dispatch_scratch_bytes(c);
     o->packed = at;     at = align_up(at + (use_mfma(c) ? packed_layout(c).total : 0), 256);
@@ -246,7 +246,7 @@ slicemoe_status slicemoe_dispatch(const slicemoe_config *cfg, const int32_t *top
 }
 
 slicemoe_status slicemoe_expert_ffn(const slicemoe_config *cfg, const void *h, const float *topk_p,
-                                    const int32_t *offsets, const int32_t *perm, const slicemoe_weights *w, float *y,
+                                    const int32_t *offsets, const int32_t *perm, const slicemoe_weights *w, void *y,
                                     void *workspace, size_t workspace_bytes, slicemoe_stream_t stream)
 {
     const slicemoe_status st = validate(cfg);
@@ -265,7 +265,7 @@ slicemoe_status slicemoe_expert_ffn(const slicemoe_config *cfg, const void *h, c
     return launch_ffn_generic(*cfg, h, topk_p, offsets, perm, *w, y, s) == hipSuccess ? SLICEMOE_OK : SLICEMOE_ERR_HIP;
 }
 
-slicemoe_status slicemoe_combine(const slicemoe_config *cfg, const float *y, const int32_t *inv, void *h_out,
+slicemoe_status slicemoe_combine(const slicemoe_config *cfg, const void *y, const int32_t *inv, void *h_out,
                                  slicemoe_stream_t stream)
 {
     const slicemoe_status st = validate(cfg);
@@ -307,7 +307,7 @@ slicemoe_status slicemoe_forward(const slicemoe_config *cfg, const void *h, cons
     int32_t *offsets = (int32_t *)(ws + L.offsets);
     int32_t *perm = (int32_t *)(ws + L.perm);
     int32_t *inv = (int32_t *)(ws + L.inv);
-    float *y = (float *)(ws + L.y);
+    void *y = (void *)(ws + L.y);
     float *stats = (float *)(ws + L.stats);
 
     const void *packed = nullptr;

@@ -1,11 +1,14 @@
 // Combine stage (paper Section 3.1): the k expert outputs of a slice are summed and the S
 // output slices concatenated.  In the slice view h'[n, :] sits where x[n, :] sat, so the
 // output is one contiguous stream: thread g handles V consecutive output elements, reads the
-// matching V floats of up to k stacked rows (fp32, full-line 16-byte loads), adds them in
-// ascending j and writes one rounded vector.  HBM-bound; no reuse, so no LDS.
+// matching V values of up to k stacked rows (16-byte loads), adds them in fp32 in ascending j
+// and writes one rounded vector.  y is fp32 (fp32 storage) or fp16 (bf16 storage).  HBM-bound;
+// no reuse, so no LDS.
 #include "common.h"
 
 namespace slicemoe {
+
+typedef _Float16 half_t;
 
 template <typename T, int V> struct OutVec;
 template <> struct OutVec<float, 4> {
@@ -16,15 +19,6 @@ template <> struct OutVec<float, 1> {
 };
 template <> struct OutVec<bf16_t, 1> {
     static __device__ __forceinline__ void store(bf16_t *o, const float *v) { *o = f32_to_bf16(v[0]); }
-};
-template <> struct OutVec<bf16_t, 4> {
-    static __device__ __forceinline__ void store(bf16_t *o, const float *v)
-    {
-        uint2 u;
-        u.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
-        u.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
-        *(uint2 *)o = u;
-    }
 };
 template <> struct OutVec<bf16_t, 8> {
     static __device__ __forceinline__ void store(bf16_t *o, const float *v)
@@ -38,8 +32,36 @@ template <> struct OutVec<bf16_t, 8> {
     }
 };
 
-template <typename T, int V>
-__global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ y, const int32_t *__restrict__ inv,
+// V values of a stacked row added into acc
+template <typename YT, int V> struct RowAdd;
+template <> struct RowAdd<float, 4> {
+    static __device__ __forceinline__ void add(const float *src, float *acc)
+    {
+        const float4 t = *(const float4 *)src;
+        acc[0] += t.x;
+        acc[1] += t.y;
+        acc[2] += t.z;
+        acc[3] += t.w;
+    }
+};
+template <> struct RowAdd<float, 1> {
+    static __device__ __forceinline__ void add(const float *src, float *acc) { acc[0] += src[0]; }
+};
+template <> struct RowAdd<half_t, 1> {
+    static __device__ __forceinline__ void add(const half_t *src, float *acc) { acc[0] += (float)src[0]; }
+};
+template <> struct RowAdd<half_t, 8> {
+    static __device__ __forceinline__ void add(const half_t *src, float *acc)
+    {
+        typedef half_t h8 __attribute__((ext_vector_type(8)));
+        const h8 t = *(const h8 *)src;
+#pragma unroll
+        for (int v = 0; v < 8; ++v) acc[v] += (float)t[v];
+    }
+};
+
+template <typename T, typename YT, int V>
+__global__ __launch_bounds__(256) void combine_kernel(const YT *__restrict__ y, const int32_t *__restrict__ inv,
                                                       T *__restrict__ out, long long n_vec, int ds, int k)
 {
     const int vec_per_slice = ds / V;
@@ -53,26 +75,14 @@ __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ 
         for (int j = 0; j < k; ++j) {
             const int r = inv[n * k + j];
             if (r < 0) continue;
-            const float *src = y + (size_t)r * ds + c0;
-            if (V >= 4) {
-#pragma unroll
-                for (int v = 0; v < V; v += 4) {
-                    const float4 t = *(const float4 *)(src + v);
-                    acc[v] += t.x;
-                    acc[v + 1] += t.y;
-                    acc[v + 2] += t.z;
-                    acc[v + 3] += t.w;
-                }
-            } else {
-                acc[0] += src[0];
-            }
+            RowAdd<YT, V>::add(y + (size_t)r * ds + c0, acc);
         }
         OutVec<T, V>::store(out + (size_t)n * ds + c0, acc);
     }
 }
 
-template <typename T, int V>
-static hipError_t run(const slicemoe_config &c, const float *y, const int32_t *inv, void *h_out, hipStream_t s)
+template <typename T, typename YT, int V>
+static hipError_t run(const slicemoe_config &c, const void *y, const int32_t *inv, void *h_out, hipStream_t s)
 {
     const long long Ns = (long long)c.T * c.S;
     const int ds = c.d / c.S;
@@ -81,21 +91,20 @@ static hipError_t run(const slicemoe_config &c, const float *y, const int32_t *i
     long long blocks = (n_vec + 255) / 256;
     const long long cap = (long long)num_compute_units() * 64;
     if (blocks > cap) blocks = cap;
-    combine_kernel<T, V><<<(int)blocks, 256, 0, s>>>(y, inv, (T *)h_out, n_vec, ds, c.k);
+    combine_kernel<T, YT, V><<<(int)blocks, 256, 0, s>>>((const YT *)y, inv, (T *)h_out, n_vec, ds, c.k);
     return hipGetLastError();
 }
 
-hipError_t launch_combine(const slicemoe_config &c, const float *y, const int32_t *inv, void *h_out,
+hipError_t launch_combine(const slicemoe_config &c, const void *y, const int32_t *inv, void *h_out,
                           hipStream_t s)
 {
     const int ds = c.d / c.S;
     if (c.dtype == SLICEMOE_BF16) {
-        if (ds % 8 == 0) return run<bf16_t, 8>(c, y, inv, h_out, s);
-        if (ds % 4 == 0) return run<bf16_t, 4>(c, y, inv, h_out, s);
-        return run<bf16_t, 1>(c, y, inv, h_out, s);
+        if (ds % 8 == 0) return run<bf16_t, half_t, 8>(c, y, inv, h_out, s);
+        return run<bf16_t, half_t, 1>(c, y, inv, h_out, s);
     }
-    if (ds % 4 == 0) return run<float, 4>(c, y, inv, h_out, s);
-    return run<float, 1>(c, y, inv, h_out, s);
+    if (ds % 4 == 0) return run<float, float, 4>(c, y, inv, h_out, s);
+    return run<float, float, 1>(c, y, inv, h_out, s);
 }
 
 }  // namespace slicemoe

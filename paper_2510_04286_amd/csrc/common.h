@@ -11,6 +11,9 @@ namespace slicemoe {
 
 typedef unsigned short bf16_t;  // storage bit pattern of a bfloat16
 
+// Element size of the stacked expert outputs y: fp32 with fp32 storage, fp16 with bf16 storage.
+__host__ __device__ __forceinline__ size_t y_elem_bytes(int dtype) { return dtype == SLICEMOE_BF16 ? 2 : 4; }
+
 // ---- device helpers -------------------------------------------------------------------
 __device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
@@ -60,11 +63,11 @@ hipError_t launch_dispatch(const slicemoe_config &c, const int32_t *idx, int32_t
                            int32_t *block_counts, float *stats /* nullable */, hipStream_t s);
 hipError_t launch_ffn_generic(const slicemoe_config &c, const void *h, const float *p,
                               const int32_t *offsets, const int32_t *perm, const slicemoe_weights &w,
-                              float *y, hipStream_t s);
+                              void *y, hipStream_t s);
 hipError_t launch_ffn_mfma(const slicemoe_config &c, const void *h, const float *p,
                            const int32_t *offsets, const int32_t *perm, const void *packed,
-                           float *y, hipStream_t s);
-hipError_t launch_combine(const slicemoe_config &c, const float *y, const int32_t *inv, void *h_out,
+                           void *y, hipStream_t s);
+hipError_t launch_combine(const slicemoe_config &c, const void *y, const int32_t *inv, void *h_out,
                           hipStream_t s);
 hipError_t launch_load_stats(const slicemoe_config &c, const int32_t *counts_raw, const int32_t *counts,
                              float *stats, hipStream_t s);

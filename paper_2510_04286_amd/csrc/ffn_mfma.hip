@@ -10,21 +10,24 @@
 // activations never exist in memory.  x rows are gathered through perm[] by the loads
 // themselves (each lane reads the 16-byte pieces of its own row from h); loads for the next
 // unit are issued before the current one is computed.  Weights come pre-packed in fragment
-// order and are staged in LDS.
+// order and are staged in LDS.  y is written as fp16 (three more mantissa bits than the bf16
+// storage type, so the rounding of h' after the k-sum stays the only significant one); the two
+// half-wavefronts exchange registers so that every lane stores whole 16-byte pieces of a row.
 //
 // Two variants:
-//   resident  a whole expert (W1, W2, biases) fits in LDS (ds = 64, He = 256: 65 KiB, two
-//             blocks per CU).  Stacked rows are split evenly over the blocks regardless of
-//             expert boundaries; a block re-stages weights only when its range crosses into
-//             another expert, and its wavefronts run independently in between.
+//   resident  a whole expert (W1, W2, biases) fits in LDS (ds = 64, He = 256: 65 KiB).  One
+//             block of 8 wavefronts per CU; stacked rows are split evenly over the blocks
+//             regardless of expert boundaries; a block re-stages weights (asynchronous
+//             global->LDS loads, overlapped with the first row gather) only when its range
+//             crosses into another expert, and its wavefronts run independently in between.
 //   streamed  larger experts (ds = 128, He = 512: 256 KiB): a block walks tiles of one expert
 //             and streams the weights through LDS in chunks of hidden tiles, per row tile.
 #include "mfma.h"
 
 namespace slicemoe {
 
-constexpr int kFfnThreads = 256;
-constexpr int kFfnWaves = kFfnThreads / 64;
+typedef _Float16 half_t;
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
 // GELU(z) = z * Phi(z) with Phi(z) ~ 0.5 + zc * P(zc^2), zc = clamp(z, -3.5, 3.5), P a degree-5
 // minimax polynomial: |Phi error| < 1.8e-4, i.e. a relative error of GELU well below the bf16
@@ -113,25 +116,51 @@ __device__ __forceinline__ void ffn_hidden_tiles(const RowUnit<DS, NSUB> &u, f32
     }
 }
 
-// y rows (fp32): per output tile a lane holds features 8q + 4g + (0..3) of its own row.
+__device__ __forceinline__ uint32_t pack_half2(float a, float b)
+{
+    f16x2 v;
+    v[0] = (half_t)a;
+    v[1] = (half_t)b;
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+// y rows as fp16.  Per output tile a lane holds features 8q + 4g + (0..3) of its own row, i.e. half
+// of each 16-byte piece; lanes j and j + 32 trade halves (v_permlane32_swap) so that lane (j, g)
+// ends up with the whole pieces q = 2*qp + g and stores them with one 16-byte write each.
 template <int DS, int NSUB>
 __device__ __forceinline__ void store_rows(const RowUnit<DS, NSUB> &u, const f32x16 (&yacc)[NSUB][DS / 32],
-                                           const float *__restrict__ b2s, float *__restrict__ y, int g)
+                                           const float *__restrict__ b2s, half_t *__restrict__ y, int g)
 {
 #pragma unroll
     for (int sub = 0; sub < NSUB; ++sub) {
-        if (u.row[sub] < 0) continue;
-        float *yr = y + (size_t)u.row[sub] * DS;
+        half_t *yr = y + (size_t)(u.row[sub] < 0 ? 0 : u.row[sub]) * DS;
 #pragma unroll
         for (int ot = 0; ot < DS / 32; ++ot)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int c0 = ot * 32 + 8 * q + 4 * g;
-                const f32x4 bb = *(const f32x4 *)(b2s + c0);
-                f32x4 v;
+            for (int qp = 0; qp < 2; ++qp) {
+                uint32_t lo[2], hi[2];  // lo: piece q = 2qp, hi: piece q = 2qp + 1 (this lane's half of each)
 #pragma unroll
-                for (int c = 0; c < 4; ++c) v[c] = yacc[sub][ot][4 * q + c] + bb[c];
-                *(f32x4 *)(yr + c0) = v;
+                for (int t = 0; t < 2; ++t) {
+                    const int q = 2 * qp + t;
+                    const f32x4 bb = *(const f32x4 *)(b2s + ot * 32 + 8 * q + 4 * g);
+                    const uint32_t d0 = pack_half2(yacc[sub][ot][4 * q + 0] + bb[0], yacc[sub][ot][4 * q + 1] + bb[1]);
+                    const uint32_t d1 = pack_half2(yacc[sub][ot][4 * q + 2] + bb[2], yacc[sub][ot][4 * q + 3] + bb[3]);
+                    if (t == 0) {
+                        lo[0] = d0;
+                        lo[1] = d1;
+                    } else {
+                        hi[0] = d0;
+                        hi[1] = d1;
+                    }
+                }
+                // after the swaps: lanes 0-31 hold (own lo, partner's lo) = piece 2qp; lanes 32-63 hold
+                // (partner's hi, own hi) = piece 2qp + 1, both in feature order
+                const auto s0 = __builtin_amdgcn_permlane32_swap(lo[0], hi[0], false, false);
+                const auto s1 = __builtin_amdgcn_permlane32_swap(lo[1], hi[1], false, false);
+                if (u.row[sub] >= 0) {
+                    const uint4 v = make_uint4(s0[0], s1[0], s0[1], s1[1]);
+                    *(uint4 *)(yr + ot * 32 + 8 * (2 * qp + g)) = v;
+                }
             }
     }
 }
@@ -147,12 +176,27 @@ __device__ __forceinline__ void zero_acc(f32x16 (&yacc)[NSUB][DS / 32])
             for (int r = 0; r < 16; ++r) yacc[sub][ot][r] = 0.f;
 }
 
+// Asynchronous copy of n16 16-byte pieces from global memory to LDS by the whole block: each
+// wavefront-level instruction moves 1 KiB (lane i -> dst + 16*i) without passing through registers.
+// The caller waits (vmcnt) and synchronises before reading.
+template <int THREADS>
+__device__ __forceinline__ void async_copy_to_lds(const uint4 *__restrict__ src, uint4 *dst, int n16, int tid)
+{
+    const int lane = tid & 63, wave = tid >> 6;
+    for (int c = wave; c < n16 / 64; c += THREADS / 64)
+        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)(src + c * 64 + lane),
+                                         (void __attribute__((address_space(3))) *)(dst + c * 64), 16, 0, 0);
+}
+
 // ------------------------------------------------------------------------------ resident
+constexpr int kResThreads = 512;
+constexpr int kResWaves = kResThreads / 64;
+
 template <int DS, int NSUB>
-__global__ __launch_bounds__(kFfnThreads, 2) void ffn_resident_kernel(
+__global__ __launch_bounds__(kResThreads, 2) void ffn_resident_kernel(
     const bf16_t *__restrict__ x, const float *__restrict__ pk, const int32_t *__restrict__ offsets,
     const int32_t *__restrict__ perm, const char *__restrict__ experts, size_t e_stride, size_t off_w1,
-    size_t off_w2, size_t off_b1, size_t off_b2, int He, int E, int k, float *__restrict__ y)
+    size_t off_w2, size_t off_b1, size_t off_b2, int He, int E, int k, half_t *__restrict__ y)
 {
     constexpr int KS = DS / 16;
     constexpr int OT = DS / 32;
@@ -171,33 +215,23 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_resident_kernel(
     const int j = lane & 31;
     const int g = lane >> 5;
 
+    // lane e keeps the end of expert e's row range: expert lookups are one ballot, not a chain of loads
+    const int off_hi = offsets[min(lane + 1, E)];
+    const int n_kept = __shfl(off_hi, E - 1);
+
     // even split of the kept rows over the blocks, in whole units
-    const int n_kept = offsets[E];
     const int units_total = (n_kept + U - 1) / U;
     const int units_per_block = (units_total + gridDim.x - 1) / gridDim.x;
     const long long r_begin = (long long)blockIdx.x * units_per_block * U;
     const int r_end = (int)min((long long)n_kept, r_begin + (long long)units_per_block * U);
 
-    int e = 0;
     int r = (int)min(r_begin, (long long)n_kept);
     while (r < r_end) {
-        while (offsets[e + 1] <= r) ++e;
-        const int seg_end = min(offsets[e + 1], r_end);
+        const int e = __popcll(__ballot(lane < E && off_hi <= r));
+        const int seg_end = min(__shfl(off_hi, e), r_end);
         const char *ew = experts + (size_t)e * e_stride;
-        __syncthreads();  // everyone is done with the previous expert's weights
-        {
-            const uint4 *g1 = (const uint4 *)(ew + off_w1);
-            const uint4 *g2 = (const uint4 *)(ew + off_w2);
-            const float *gb1 = (const float *)(ew + off_b1);
-            const float *gb2 = (const float *)(ew + off_b2);
-            for (int i = tid; i < HT * KS * 64; i += kFfnThreads) w1s[i] = g1[i];
-            for (int i = tid; i < HT * 2 * OT * 64; i += kFfnThreads) w2s[i] = g2[i];
-            for (int i = tid; i < He; i += kFfnThreads) b1s[i] = gb1[i];
-            for (int i = tid; i < DS; i += kFfnThreads) b2s[i] = gb2[i];
-        }
-        __syncthreads();
 
-        // units of this segment: unit q covers rows r + q*U ..., this wavefront takes q = wave, wave+4, ...
+        // units of this segment: unit q covers rows r + q*U ..., this wavefront takes q = wave, wave+8, ...
         const int nunits = (seg_end - r + U - 1) / U;
         auto unit_rows = [&](int q, int (&row)[NSUB]) {
 #pragma unroll
@@ -210,18 +244,32 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_resident_kernel(
 #pragma unroll
             for (int sub = 0; sub < NSUB; ++sub) a[sub] = row[sub] >= 0 ? perm[row[sub]] : 0;
         };
+        // row indices of the first two units go out first, the weight copy overlaps their latency
         int row_c[NSUB], a_c[NSUB], row_n[NSUB], a_n[NSUB];
-        RowUnit<DS, NSUB> cur;
         unit_rows(wave, row_c);
         load_perm(row_c, a_c);
-        gather_rows<DS, NSUB>(cur, a_c, row_c, x, pk, k, g);
-        unit_rows(wave + kFfnWaves, row_n);
+        unit_rows(wave + kResWaves, row_n);
         load_perm(row_n, a_n);
-        for (int q = wave; q < nunits; q += kFfnWaves) {
+
+        __syncthreads();  // everyone is done with the previous expert's weights
+        async_copy_to_lds<kResThreads>((const uint4 *)(ew + off_w1), w1s, HT * KS * 64, tid);
+        async_copy_to_lds<kResThreads>((const uint4 *)(ew + off_w2), w2s, HT * 2 * OT * 64, tid);
+        {
+            const float *gb1 = (const float *)(ew + off_b1);
+            const float *gb2 = (const float *)(ew + off_b2);
+            for (int i = tid; i < He; i += kResThreads) b1s[i] = gb1[i];
+            for (int i = tid; i < DS; i += kResThreads) b2s[i] = gb2[i];
+        }
+        RowUnit<DS, NSUB> cur;
+        gather_rows<DS, NSUB>(cur, a_c, row_c, x, pk, k, g);
+        __builtin_amdgcn_s_waitcnt(0);  // the asynchronous copies have landed
+        __syncthreads();
+
+        for (int q = wave; q < nunits; q += kResWaves) {
             // next unit's rows (indices arrived during the previous unit), indices of the one after
             RowUnit<DS, NSUB> nxt;
             gather_rows<DS, NSUB>(nxt, a_n, row_n, x, pk, k, g);
-            unit_rows(q + 2 * kFfnWaves, row_n);
+            unit_rows(q + 2 * kResWaves, row_n);
             load_perm(row_n, a_n);
 
             f32x16 yacc[NSUB][OT];
@@ -235,11 +283,14 @@ __global__ __launch_bounds__(kFfnThreads, 2) void ffn_resident_kernel(
 }
 
 // ------------------------------------------------------------------------------ streamed
+constexpr int kFfnThreads = 256;
+constexpr int kFfnWaves = kFfnThreads / 64;
+
 template <int DS, int NSUB>
 __global__ __launch_bounds__(kFfnThreads) void ffn_streamed_kernel(
     const bf16_t *__restrict__ x, const float *__restrict__ pk, const int32_t *__restrict__ offsets,
     const int32_t *__restrict__ perm, const char *__restrict__ experts, size_t e_stride, size_t off_w1,
-    size_t off_w2, size_t off_b1, size_t off_b2, int He, int E, int k, int hc, float *__restrict__ y)
+    size_t off_w2, size_t off_b1, size_t off_b2, int He, int E, int k, int hc, half_t *__restrict__ y)
 {
     constexpr int KS = DS / 16;
     constexpr int OT = DS / 32;
@@ -297,16 +348,16 @@ __global__ __launch_bounds__(kFfnThreads) void ffn_streamed_kernel(
         zero_acc<DS, NSUB>(yacc);
         for (int ch = 0; ch < nchunks; ++ch) {
             __syncthreads();  // everyone is done with the previous contents
-            const uint4 *g1 = (const uint4 *)(ew + off_w1) + (size_t)ch * hc * KS * 64;
-            const uint4 *g2 = (const uint4 *)(ew + off_w2) + (size_t)ch * hc * 2 * OT * 64;
-            for (int i = tid; i < hc * KS * 64; i += kFfnThreads) w1s[i] = g1[i];
-            for (int i = tid; i < hc * 2 * OT * 64; i += kFfnThreads) w2s[i] = g2[i];
+            async_copy_to_lds<kFfnThreads>((const uint4 *)(ew + off_w1) + (size_t)ch * hc * KS * 64, w1s, hc * KS * 64, tid);
+            async_copy_to_lds<kFfnThreads>((const uint4 *)(ew + off_w2) + (size_t)ch * hc * 2 * OT * 64, w2s,
+                                           hc * 2 * OT * 64, tid);
             if (new_expert && ch == 0) {
                 const float *gb1 = (const float *)(ew + off_b1);
                 const float *gb2 = (const float *)(ew + off_b2);
                 for (int i = tid; i < He; i += kFfnThreads) b1s[i] = gb1[i];
                 for (int i = tid; i < DS; i += kFfnThreads) b2s[i] = gb2[i];
             }
+            __builtin_amdgcn_s_waitcnt(0);
             __syncthreads();
             ffn_hidden_tiles<DS, NSUB>(cur, yacc, w1s, w2s, b1s, ch * hc, hc, lane, g);
         }
@@ -352,40 +403,42 @@ static FfnPlan plan_ffn(int ds, int He, int E)
 
 template <int DS, int NSUB>
 static hipError_t run_ffn(const slicemoe_config &c, const FfnPlan &pl, const void *h, const float *p,
-                          const int32_t *offsets, const int32_t *perm, const void *packed, float *y,
+                          const int32_t *offsets, const int32_t *perm, const void *packed, void *y,
                           hipStream_t s)
 {
     const PackedLayout L = packed_layout(c);
     const long long Na = (long long)c.T * c.S * c.k;
     const char *experts = (const char *)packed + L.experts;
     hipError_t err;
-    if (pl.resident) {
-        constexpr int U = 32 * NSUB;
-        long long blocks = (long long)num_compute_units() * 2;
-        const long long max_blocks = (Na + U - 1) / U;
-        if (blocks > max_blocks) blocks = max_blocks;
-        auto kern = ffn_resident_kernel<DS, NSUB>;
-        err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds);
-        if (err != hipSuccess) return err;
-        kern<<<(int)blocks, kFfnThreads, pl.lds, s>>>((const bf16_t *)h, p, offsets, perm, experts, L.e_stride, L.e_w1,
-                                                      L.e_w2, L.e_b1, L.e_b2, c.He, c.E, c.k, y);
-    } else {
-        constexpr int TM = kFfnWaves * NSUB * 32;
-        const long long max_tiles = (Na + TM - 1) / TM + c.E;
-        long long blocks = (long long)num_compute_units() * (pl.lds <= 78 * 1024 ? 2 : 1);
-        if (blocks > max_tiles) blocks = max_tiles;
-        auto kern = ffn_streamed_kernel<DS, NSUB>;
-        err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds);
-        if (err != hipSuccess) return err;
-        kern<<<(int)blocks, kFfnThreads, pl.lds, s>>>((const bf16_t *)h, p, offsets, perm, experts, L.e_stride, L.e_w1,
-                                                      L.e_w2, L.e_b1, L.e_b2, c.He, c.E, c.k, pl.hc, y);
+    if constexpr (DS == 64) {
+        if (pl.resident) {
+            constexpr int U = 32 * NSUB;
+            long long blocks = (long long)num_compute_units();
+            const long long max_blocks = (Na + U - 1) / U;
+            if (blocks > max_blocks) blocks = max_blocks;
+            auto kern = ffn_resident_kernel<DS, NSUB>;
+            err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds);
+            if (err != hipSuccess) return err;
+            kern<<<(int)blocks, kResThreads, pl.lds, s>>>((const bf16_t *)h, p, offsets, perm, experts, L.e_stride,
+                                                          L.e_w1, L.e_w2, L.e_b1, L.e_b2, c.He, c.E, c.k, (half_t *)y);
+            return hipGetLastError();
+        }
     }
+    constexpr int TM = kFfnWaves * NSUB * 32;
+    const long long max_tiles = (Na + TM - 1) / TM + c.E;
+    long long blocks = (long long)num_compute_units() * (pl.lds <= 78 * 1024 ? 2 : 1);
+    if (blocks > max_tiles) blocks = max_tiles;
+    auto kern = ffn_streamed_kernel<DS, NSUB>;
+    err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds);
+    if (err != hipSuccess) return err;
+    kern<<<(int)blocks, kFfnThreads, pl.lds, s>>>((const bf16_t *)h, p, offsets, perm, experts, L.e_stride, L.e_w1,
+                                                  L.e_w2, L.e_b1, L.e_b2, c.He, c.E, c.k, pl.hc, (half_t *)y);
     return hipGetLastError();
 }
 
 hipError_t launch_ffn_mfma(const slicemoe_config &c, const void *h, const float *p,
                            const int32_t *offsets, const int32_t *perm, const void *packed,
-                           float *y, hipStream_t s)
+                           void *y, hipStream_t s)
 {
     const long long Na = (long long)c.T * c.S * c.k;
     if (Na == 0) return hipSuccess;

@@ -74,13 +74,14 @@ __global__ __launch_bounds__(kGenThreads) void route_generic_kernel(
 }
 
 // Expert FFN of Section 3.1 on stacked rows with the Eq. 1 input weighting and the gather fused:
-// y[r] = GELU((p x) W1[e] + b1[e]) W2[e] + b2[e], exact (erf) GELU.
-template <typename T>
+// y[r] = GELU((p x) W1[e] + b1[e]) W2[e] + b2[e], exact (erf) GELU.  y is fp32 for fp32 storage and
+// fp16 for bf16 storage (same convention as the matrix-core kernel).
+template <typename T, typename YT>
 __global__ __launch_bounds__(kGenThreads) void ffn_generic_kernel(
     const T *__restrict__ x, const float *__restrict__ pk, const int32_t *__restrict__ offsets,
     const int32_t *__restrict__ perm, int ds, int He, int E, int k,
     const T *__restrict__ W1, const T *__restrict__ b1, const T *__restrict__ W2, const T *__restrict__ b2,
-    float *__restrict__ y)
+    YT *__restrict__ y)
 {
     extern __shared__ float smem[];
     float *xs = smem;             // [kRB][ds]  (already multiplied by p)
@@ -126,7 +127,7 @@ __global__ __launch_bounds__(kGenThreads) void ffn_generic_kernel(
         const T *w = W2 + (size_t)e * He * ds + c;
         float acc = Storage<T>::load(b2 + (size_t)e * ds + c);
         for (int j = 0; j < He; ++j) acc = fmaf(zs[r * He + j], Storage<T>::load(w + (size_t)j * ds), acc);
-        y[(r0 + r) * ds + c] = acc;
+        y[(r0 + r) * ds + c] = (YT)acc;
     }
 }
 
@@ -151,7 +152,7 @@ hipError_t launch_route_generic(const slicemoe_config &c, const void *h, const s
 
 hipError_t launch_ffn_generic(const slicemoe_config &c, const void *h, const float *p,
                               const int32_t *offsets, const int32_t *perm, const slicemoe_weights &w,
-                              float *y, hipStream_t s)
+                              void *y, hipStream_t s)
 {
     const long long Na = (long long)c.T * c.S * c.k;
     if (Na == 0) return hipSuccess;
@@ -159,13 +160,13 @@ hipError_t launch_ffn_generic(const slicemoe_config &c, const void *h, const flo
     const int blocks = (int)((Na + kRB - 1) / kRB);
     const size_t smem = sizeof(float) * (size_t)kRB * (ds + c.He);
     if (c.dtype == SLICEMOE_BF16)
-        ffn_generic_kernel<bf16_t><<<blocks, kGenThreads, smem, s>>>(
+        ffn_generic_kernel<bf16_t, _Float16><<<blocks, kGenThreads, smem, s>>>(
             (const bf16_t *)h, p, offsets, perm, ds, c.He, c.E, c.k, (const bf16_t *)w.W1,
-            (const bf16_t *)w.b1, (const bf16_t *)w.W2, (const bf16_t *)w.b2, y);
+            (const bf16_t *)w.b1, (const bf16_t *)w.W2, (const bf16_t *)w.b2, (_Float16 *)y);
     else
-        ffn_generic_kernel<float><<<blocks, kGenThreads, smem, s>>>(
+        ffn_generic_kernel<float, float><<<blocks, kGenThreads, smem, s>>>(
             (const float *)h, p, offsets, perm, ds, c.He, c.E, c.k, (const float *)w.W1,
-            (const float *)w.b1, (const float *)w.W2, (const float *)w.b2, y);
+            (const float *)w.b1, (const float *)w.W2, (const float *)w.b2, (float *)y);
     return hipGetLastError();
 }
 

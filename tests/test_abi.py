@@ -77,7 +77,7 @@ def test_capacity_and_sizes(B):
         assert L.total == B.slicemoe_workspace_bytes(cfg) > 0
         offs = [L.topk_idx, L.topk_p, L.counts_raw, L.counts, L.offsets, L.perm, L.inv, L.y, L.stats, L.scratch, L.packed]
         assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
-        assert L.perm - L.offsets >= (c.E + 1) * 4 and L.stats - L.y >= c.Na * c.ds * 4
-        assert B.slicemoe_dispatch_workspace_bytes(cfg) >= -(-c.Na // 4096) * c.E * 4
+        assert L.perm - L.offsets >= (c.E + 1) * 4 and L.stats - L.y >= c.Na * c.ds * (2 if c.dtype == 'bf16' else 4)
+        assert B.slicemoe_dispatch_workspace_bytes(cfg) >= -(-c.Na // 1024) * c.E * 4
         assert (B.slicemoe_packed_bytes(cfg) > 0) == (c.dtype == "bf16")
     assert B.slicemoe_capacity(B.make_config(100, 64, 4, 2, 8, 16, capacity_factor=1.1)) == 111  # ceil(1.1f*800/8)

@@ -45,15 +45,15 @@ DISPATCH_CASES = [
     # T, S, k, E, capacity_factor, zipf
     (1, 1, 1, 1, 0.0, 0.0),
     (3, 5, 2, 7, 0.0, 0.0),          # far less than one chunk, E not a power of two
-    (512, 4, 2, 8, 0.0, 0.0),        # tiny config: exactly one chunk
-    (513, 4, 2, 8, 0.0, 1.0),        # ragged tail of 8 assignments in the second chunk
+    (512, 4, 2, 8, 0.0, 0.0),        # tiny config: exactly four chunks
+    (513, 4, 2, 8, 0.0, 1.0),        # ragged tail of 8 assignments in the last chunk
     (1000, 7, 3, 33, 0.0, 1.2),      # E just above 32, k = 3
     (4096, 8, 2, 16, 0.0, 0.0),      # LM-shaped
     (2000, 8, 8, 64, 1.0, 1.2),      # k = 8, E = 64, capacity drop
     (16384, 16, 2, 32, 0.0, 0.0),    # headline
     (16384, 16, 2, 32, 1.25, 1.2),   # skewed: Zipf(1.2) popularity, capacity 20480
     (777, 3, 1, 5, 0.05, 0.7),       # nearly everything dropped
-    (65536, 32, 2, 64, 0.0, 0.3),    # large: 4 194 304 assignments, 1024 chunks
+    (65536, 32, 2, 64, 0.0, 0.3),    # large: 4 194 304 assignments, 4096 chunks
 ]
 
 
@@ -124,8 +124,11 @@ def test_combine_matches_oracle(B, name, T):
     y = wl.normal(9, 0, 0, kept * shape.ds).reshape(kept, shape.ds).astype(np.float32)
     ref = oracle.combine(y, d["inv"], shape.Ns, shape.k)
     tdt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
-    ybuf = torch.zeros(shape.Na * shape.ds, dtype=torch.float32, device="cuda:0")
-    ybuf[:kept * shape.ds] = dev(y.reshape(-1))
+    ydt = B.y_dtype(cfg)
+    y = y.astype(np.float16).astype(np.float32) if ydt == torch.float16 else y  # values the y buffer can hold
+    ref = oracle.combine(y, d["inv"], shape.Ns, shape.k)
+    ybuf = torch.zeros(shape.Na * shape.ds, dtype=ydt, device="cuda:0")
+    ybuf[:kept * shape.ds] = dev(y.reshape(-1)).to(ydt)
     out = torch.full((shape.T, shape.d), 7.0, dtype=tdt, device="cuda:0")
     B.slicemoe_combine(cfg, ybuf, dev(d["inv"]), out)
     got = out.float().cpu().numpy().reshape(-1, shape.ds).astype(np.float64)
@@ -152,19 +155,20 @@ def test_expert_ffn_matches_oracle(B, name, T, force_generic):
     kept = int(d["offsets"][-1])
     ref = oracle.expert_rows(x, r["idx"], r["pk"], d["perm"], kept, w["W1"], w["b1"], w["W2"], w["b2"])
     wd = B.pack(cfg, B.weights_to_device(w, shape.dtype))
-    y = torch.full((shape.Na, shape.ds), 123.0, dtype=torch.float32, device="cuda:0")
+    y = torch.full((shape.Na, shape.ds), 123.0, dtype=B.y_dtype(cfg), device="cuda:0")
     perm = d["perm"].copy()
     perm[kept:] = 0
     B.slicemoe_expert_ffn(cfg, B.to_device(h, shape.dtype), dev(r["pk"].astype(np.float32).reshape(-1)),
                           dev(d["offsets"]), dev(perm), wd, y)
-    got = y.cpu().numpy().astype(np.float64)
+    got = y.float().cpu().numpy().astype(np.float64)
     assert np.all(got[kept:] == 123.0)  # rows past the kept ones untouched
     err = np.abs(got[:kept] - ref).max() / rms(ref)
     mfma = B.slicemoe_uses_mfma(cfg) == 1
     print(f"\n[ffn {name} T={T} mfma={mfma}] rows={kept} max|err|/rms={err:.3e}")
-    # fp32 arithmetic: 1e-4 RMS; bf16 matrix-core path: the layer's bf16 bar applied to y, which is
-    # stricter than asked since y (fp32) has not yet had the final rounding of h'
-    assert err <= (TOL_BF16 if mfma else TOL_F32)
+    # fp32 storage: 1e-4 RMS.  bf16 storage (y is fp16, on either kernel family): the layer's bf16 bar
+    # applied to y, stricter than asked since y has not yet had the final rounding of h'; the generic
+    # kernels (fp32 arithmetic, fp16 y) must do ten times better than that
+    assert err <= (TOL_F32 if shape.dtype == "f32" else (TOL_BF16 if mfma else TOL_BF16 / 10))
 
 
 def test_expert_ffn_empty_experts_and_ragged_tiles(B):
@@ -183,10 +187,10 @@ def test_expert_ffn_empty_experts_and_ragged_tiles(B):
     ref = oracle.expert_rows(x, idx, pk, d["perm"], shape.Na, w["W1"], w["b1"], w["W2"], w["b2"])
     cfg = B.config_of(shape)
     wd = B.pack(cfg, B.weights_to_device(w, shape.dtype))
-    y = torch.zeros((shape.Na, shape.ds), dtype=torch.float32, device="cuda:0")
+    y = torch.zeros((shape.Na, shape.ds), dtype=B.y_dtype(cfg), device="cuda:0")
     B.slicemoe_expert_ffn(cfg, B.to_device(h, shape.dtype), dev(pk.astype(np.float32).reshape(-1)), dev(d["offsets"]),
                           dev(d["perm"]), wd, y)
-    err = np.abs(y.cpu().numpy() - ref).max() / rms(ref)
+    err = np.abs(y.float().cpu().numpy() - ref).max() / rms(ref)
     assert err <= TOL_BF16, err
 
 
