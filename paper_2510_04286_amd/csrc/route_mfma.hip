@@ -16,7 +16,6 @@
 
 namespace slicemoe {
 
-constexpr int kRouteThreads = 256;
 constexpr int kRouteHr = 256;
 constexpr int kRouteHT = kRouteHr / 32;
 
@@ -26,14 +25,18 @@ __device__ __forceinline__ uint32_t pack_hi16(float lo_elem, float hi_elem)
     return (__float_as_uint(lo_elem) >> 16) | (__float_as_uint(hi_elem) & 0xFFFF0000u);
 }
 
-template <int DS, int ET>
-__global__ __launch_bounds__(kRouteThreads) void route_mfma_kernel(
+// One block per CU shares one LDS copy of the router: THREADS = 1024 (16 wavefronts, <= 128 VGPRs)
+// for the small shapes, 512 where the accumulators of two expert tiles or K = 128 need more registers.
+template <int DS, int ET, int THREADS>
+__global__ __launch_bounds__(THREADS) void route_mfma_kernel(
     const bf16_t *__restrict__ x, long long Ns, int E, int k, const char *__restrict__ packed,
     size_t off_w1, size_t off_w2, size_t off_b1, size_t off_b2, int32_t *__restrict__ idx,
     float *__restrict__ pk)
 {
     constexpr int KS = DS / 16;
     constexpr int HT = kRouteHT;
+    constexpr int kRouteThreads = THREADS;
+    constexpr int kRouteWaves = THREADS / 64;
     extern __shared__ __align__(16) char lds[];
     uint4 *w1s = (uint4 *)lds;                         // [HT][KS][64]
     uint4 *w2s = w1s + HT * KS * 64;                   // [ET][HT][2][64]
@@ -47,31 +50,44 @@ __global__ __launch_bounds__(kRouteThreads) void route_mfma_kernel(
     const int g = lane >> 5;
 
     {
+        // the whole router goes global -> LDS asynchronously (1 KiB per wavefront instruction)
         const uint4 *g1 = (const uint4 *)(packed + off_w1);
         const uint4 *g2 = (const uint4 *)(packed + off_w2);
         const float *gb1 = (const float *)(packed + off_b1);
         const float *gb2 = (const float *)(packed + off_b2);
-        for (int i = tid; i < HT * KS * 64; i += kRouteThreads) w1s[i] = g1[i];
-        for (int i = tid; i < ET * HT * 2 * 64; i += kRouteThreads) w2s[i] = g2[i];
+        for (int c = wave; c < HT * KS; c += kRouteThreads / 64)
+            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)(g1 + c * 64 + lane),
+                                             (void __attribute__((address_space(3))) *)(w1s + c * 64), 16, 0, 0);
+        for (int c = wave; c < ET * HT * 2; c += kRouteThreads / 64)
+            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)(g2 + c * 64 + lane),
+                                             (void __attribute__((address_space(3))) *)(w2s + c * 64), 16, 0, 0);
         for (int i = tid; i < kRouteHr; i += kRouteThreads) b1s[i] = gb1[i];
         for (int i = tid; i < ET * 32; i += kRouteThreads) b2s[i] = gb2[i];
     }
+    // first tile's rows are requested before waiting for the weights
+    const long long ntiles = (Ns + 31) / 32;
+    const long long tile_stride = (long long)gridDim.x * kRouteWaves;
+    auto load_x = [&](long long tile, bf16x8 (&xb)[KS]) {
+        const long long n = tile * 32 + j;
+        const bool valid = tile < ntiles && n < Ns;
+        const uint4 *xp = (const uint4 *)(x + (valid ? n : 0) * DS);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (valid) v = xp[ks * 2 + g];
+            xb[ks] = __builtin_bit_cast(bf16x8, v);
+        }
+    };
+    bf16x8 xb[KS];
+    load_x((long long)blockIdx.x * kRouteWaves + wave, xb);
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
-    const long long ntiles = (Ns + 31) / 32;
-    for (long long tile = (long long)blockIdx.x * 4 + wave; tile < ntiles; tile += (long long)gridDim.x * 4) {
+    for (long long tile = (long long)blockIdx.x * kRouteWaves + wave; tile < ntiles; tile += tile_stride) {
         const long long n = tile * 32 + j;
         const bool valid = n < Ns;
-        bf16x8 xb[KS];
-        {
-            const uint4 *xp = (const uint4 *)(x + (valid ? n : 0) * DS);
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                uint4 v = make_uint4(0, 0, 0, 0);
-                if (valid) v = xp[ks * 2 + g];
-                xb[ks] = __builtin_bit_cast(bf16x8, v);
-            }
-        }
+        bf16x8 xn[KS];
+        load_x(tile + tile_stride, xn);  // next tile, consumed after this one
         f32x16 gacc[ET];
 #pragma unroll
         for (int et = 0; et < ET; ++et)
@@ -170,10 +186,12 @@ __global__ __launch_bounds__(kRouteThreads) void route_mfma_kernel(
                 pk[n * k + jj] = __expf(bv - m) * rden;
             }
         }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) xb[ks] = xn[ks];
     }
 }
 
-template <int DS, int ET>
+template <int DS, int ET, int THREADS>
 static hipError_t run_route(const slicemoe_config &c, const void *h, const void *packed, int32_t *idx, float *p,
                             hipStream_t s)
 {
@@ -182,13 +200,14 @@ static hipError_t run_route(const slicemoe_config &c, const void *h, const void 
     constexpr int KS = DS / 16;
     const size_t lds = (size_t)(kRouteHT * KS * 64 + ET * kRouteHT * 2 * 64) * 16 + (kRouteHr + ET * 32) * 4;
     const long long ntiles = (Ns + 31) / 32;
-    long long blocks = (ntiles + 3) / 4;
-    const long long cap = (long long)num_compute_units() * (lds <= 80 * 1024 ? 2 : 1);
+    constexpr int kRouteWaves = THREADS / 64;
+    long long blocks = (ntiles + kRouteWaves - 1) / kRouteWaves;
+    const long long cap = (long long)num_compute_units();
     if (blocks > cap) blocks = cap;
-    auto kern = route_mfma_kernel<DS, ET>;
+    auto kern = route_mfma_kernel<DS, ET, THREADS>;
     hipError_t err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (err != hipSuccess) return err;
-    kern<<<(int)blocks, kRouteThreads, lds, s>>>((const bf16_t *)h, Ns, c.E, c.k, (const char *)packed, L.r_w1,
+    kern<<<(int)blocks, THREADS, lds, s>>>((const bf16_t *)h, Ns, c.E, c.k, (const char *)packed, L.r_w1,
                                                  L.r_w2, L.r_b1, L.r_b2, idx, p);
     return hipGetLastError();
 }
@@ -199,8 +218,9 @@ hipError_t launch_route_mfma(const slicemoe_config &c, const void *h, const void
     if ((long long)c.T * c.S == 0) return hipSuccess;
     const int ds = c.d / c.S;
     const int et = (c.E + 31) / 32;
-    if (ds == 64) return et == 1 ? run_route<64, 1>(c, h, packed, idx, p, s) : run_route<64, 2>(c, h, packed, idx, p, s);
-    return et == 1 ? run_route<128, 1>(c, h, packed, idx, p, s) : run_route<128, 2>(c, h, packed, idx, p, s);
+    if (ds == 64)
+        return et == 1 ? run_route<64, 1, 1024>(c, h, packed, idx, p, s) : run_route<64, 2, 512>(c, h, packed, idx, p, s);
+    return et == 1 ? run_route<128, 1, 512>(c, h, packed, idx, p, s) : run_route<128, 2, 512>(c, h, packed, idx, p, s);
 }
 
 }  // namespace slicemoe
