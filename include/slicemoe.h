@@ -163,8 +163,9 @@ slicemoe_status slicemoe_dispatch(const slicemoe_config *cfg, const int32_t *top
  * The gather of x and the Eq. 1 weighting are fused into the kernel (no stacked copy of the
  * inputs is materialised); the He-wide hidden activations never leave the chip.
  *   y [T*S*k, ds] out, fp32 (fp32 storage) or fp16 (bf16 storage); rows >= offsets[E] are left untouched.
- * The MFMA kernel rounds the hidden activations to bf16 and evaluates GELU(z) = z Phi(z) with a
- * clamped polynomial for Phi (|error| < 1.8e-4, below that rounding); the generic kernel uses erf.
+ * The MFMA kernel evaluates GELU(z) = z Phi(z) in packed fp16 with a polynomial for Phi and feeds
+ * fp16 hidden activations to its second GEMM (activation error of the size of one bf16 rounding,
+ * hidden activations beyond +-2.6e5 would overflow); the generic kernel uses erf in fp32.
  */
 slicemoe_status slicemoe_expert_ffn(const slicemoe_config *cfg, const void *h, const float *topk_p,
                                     const int32_t *offsets, const int32_t *perm,

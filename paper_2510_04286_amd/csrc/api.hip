@@ -77,7 +77,7 @@ PackedLayout packed_layout(const slicemoe_config &c)
     size_t e = 0;
     L.e_w1 = e;  e = align_up(e + (size_t)L.ds * L.He * 2, 256);
     L.e_w2 = e;  e = align_up(e + (size_t)L.He * L.ds * 2, 256);
-    L.e_b1 = e;  e = align_up(e + (size_t)L.He * 4, 256);
+    L.e_b1 = e;  e = align_up(e + (size_t)L.He * 2, 256);
     L.e_b2 = e;  e = align_up(e + (size_t)L.ds * 4, 256);
     L.e_stride = e;
     L.total = L.experts + L.e_stride * (size_t)L.E;

@@ -5,21 +5,36 @@
 //
 // One launch covers all experts; the per-expert row ranges come from offsets[] on the device.
 // A wavefront owns a unit of 32*NSUB stacked rows and the whole hidden width.  Per 32-wide
-// hidden tile it runs GEMM1 (K = ds), applies bias / p / GELU to its 16 accumulators per lane
-// and feeds them straight into GEMM2 as the B operand (see mfma.h): the [rows, He] hidden
-// activations never exist in memory.  x rows are gathered through perm[] by the loads
-// themselves (each lane reads the 16-byte pieces of its own row from h); loads for the next
-// unit are issued before the current one is computed.  Weights come pre-packed in fragment
-// order and are staged in LDS.  y is written as fp16 (three more mantissa bits than the bf16
-// storage type, so the rounding of h' after the k-sum stays the only significant one); the two
-// half-wavefronts exchange registers so that every lane stores whole 16-byte pieces of a row.
+// hidden tile it runs GEMM1 (bf16 MFMA, K = ds), turns its 16 fp32 accumulators per lane into 8
+// packed fp16 pairs of activations and feeds them straight into GEMM2 (fp16 MFMA) as the B
+// operand (see mfma.h): the [rows, He] hidden activations never exist in memory.  x rows are
+// gathered through perm[] by the loads themselves; the rows of the next unit are loaded while
+// the current one is computed.  Weights come pre-packed in fragment order and sit in LDS.
+// y is written as fp16; the two half-wavefronts exchange registers so that every lane stores
+// whole 16-byte pieces of a row.
+//
+// Activation stage (the part that bounds this kernel: with ds = 64 every hidden element is fed
+// by only 16 matrix-core cycles per lane, so the vector ALU work per element decides the speed).
+// It runs entirely on packed fp16 instructions, two hidden elements per instruction:
+//   A  = cvt_pkrtz(acc0, acc1)                 fp32 accumulators -> fp16 pair
+//   s  = A * (kappa p) + kappa b1              s = kappa z, kappa = 1/4           (Eq. 1 scale + bias)
+//   v  = s * s - w0
+//   Q  = Horner in v, degree kGeluM            s Q(v) ~ Phi(z) - 1/2 on |z| <= zc, and > 1/2 beyond
+//   F  = clamp01(s * Q + 1/2)                  ~ Phi(z): the instruction's own [0,1] clamp saturates it
+//   g  = s * F                                 = kappa GELU(z)
+// W2 is packed pre-multiplied by 1/kappa, so GEMM2 needs no rescaling.  fp16 has three more
+// mantissa bits than the bf16 storage type; evaluated this way the activation error is of the
+// size of one bf16 rounding: at most 2.5e-3 (rms 5e-4) of the larger of |z| and |p a| (the same
+// roundings are replayed on the CPU in tests/test_gelu_poly.py).
+// Hidden activations beyond +-65504 / kappa would overflow fp16.
 //
 // Two variants:
-//   resident  a whole expert (W1, W2, biases) fits in LDS (ds = 64, He = 256: 65 KiB).  One
-//             block of 8 wavefronts per CU; stacked rows are split evenly over the blocks
-//             regardless of expert boundaries; a block re-stages weights (asynchronous
-//             global->LDS loads, overlapped with the first row gather) only when its range
-//             crosses into another expert, and its wavefronts run independently in between.
+//   resident  a whole expert (W1, W2, biases) fits in LDS (ds = 64, He <= 256).  One block of 16
+//             wavefronts per CU (four per SIMD, so that one wavefront's matrix work overlaps
+//             another's vector work); stacked rows are split evenly over the blocks regardless of
+//             expert boundaries; a block re-stages weights only when its range crosses into
+//             another expert.  Wavefront priority follows the number of units a wavefront still
+//             has to do, which keeps the 16 wavefronts finishing together.
 //   streamed  larger experts (ds = 128, He = 512: 256 KiB): a block walks tiles of one expert
 //             and streams the weights through LDS in chunks of hidden tiles, per row tile.
 #include "mfma.h"
@@ -27,101 +42,113 @@
 namespace slicemoe {
 
 typedef _Float16 half_t;
-typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
-// GELU(z) = z * Phi(z) with Phi(z) ~ 0.5 + zc * P(zc^2), zc = clamp(z, -3.5, 3.5), P a degree-5
-// minimax polynomial: |Phi error| < 1.8e-4, i.e. a relative error of GELU well below the bf16
-// rounding (2^-9) applied to the result.  Horner steps with literal coefficients are the cheapest
-// VALU form on gfx950; no transcendental instruction is needed.
-__device__ __forceinline__ float gelu_poly(float z)
+// Packed fp16 constants of the activation stage, passed by value (uniform: they live in SGPRs).
+struct EpiConst {
+    uint32_t neg_w0;
+    uint32_t q[kGeluM + 1];
+    uint32_t half;
+};
+
+static uint32_t pack2_f16(float f)
 {
-    const float zc = __builtin_amdgcn_fmed3f(z, -3.5f, 3.5f);
-    const float w = zc * zc;
-    float P = -7.907663110e-07f;
-    P = fmaf(P, w, 3.767626183e-05f);
-    P = fmaf(P, w, -7.603790386e-04f);
-    P = fmaf(P, w, 8.699680533e-03f);
-    P = fmaf(P, w, -6.477227479e-02f);
-    P = fmaf(P, w, 3.982652909e-01f);
-    return z * fmaf(zc, P, 0.5f);
+    const _Float16 h = (_Float16)f;
+    uint16_t u;
+    __builtin_memcpy(&u, &h, 2);
+    return (uint32_t)u | ((uint32_t)u << 16);
+}
+
+static EpiConst make_epi_const()
+{
+    EpiConst K;
+    K.neg_w0 = pack2_f16(-kGeluW0);
+    for (int i = 0; i <= kGeluM; ++i) K.q[i] = pack2_f16(kGeluQ[i]);
+    K.half = pack2_f16(0.5f);
+    return K;
+}
+
+__device__ __forceinline__ h2 as_h2(uint32_t u) { return __builtin_bit_cast(h2, u); }
+__device__ __forceinline__ h2 pk_fma(h2 a, h2 b, h2 c) { return __builtin_elementwise_fma(a, b, c); }
+// fused multiply-add with the instruction's output clamp to [0, 1]
+__device__ __forceinline__ h2 pk_fma_clamp01(h2 a, h2 b, h2 c)
+{
+    h2 d;
+    asm("v_pk_fma_f16 %0, %1, %2, %3 clamp" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+    return d;
+}
+
+// 16 accumulators of one 32x32 tile -> 8 packed fp16 pairs of kappa * GELU(z); pair i holds the
+// accumulator registers 2i and 2i+1, i.e. contraction slots of GEMM2 in register order.
+__device__ __forceinline__ void activation_tile(const f32x16 &acc, h2 p2, const h2 (&bias)[8], const EpiConst &K, uint4 (&out)[2])
+{
+    uint32_t o[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const h2 A = __builtin_bit_cast(h2, __builtin_amdgcn_cvt_pkrtz(acc[2 * i], acc[2 * i + 1]));
+        const h2 s = pk_fma(A, p2, bias[i]);
+        const h2 v = pk_fma(s, s, as_h2(K.neg_w0));
+        h2 Q = pk_fma(v, as_h2(K.q[kGeluM]), as_h2(K.q[kGeluM - 1]));
+#pragma unroll
+        for (int c = kGeluM - 2; c >= 0; --c) Q = pk_fma(Q, v, as_h2(K.q[c]));
+        const h2 F = pk_fma_clamp01(s, Q, as_h2(K.half));
+        o[i] = __builtin_bit_cast(uint32_t, s * F);
+    }
+    out[0] = make_uint4(o[0], o[1], o[2], o[3]);
+    out[1] = make_uint4(o[4], o[5], o[6], o[7]);
 }
 
 template <int DS, int NSUB> struct RowUnit {
     bf16x8 xb[NSUB][DS / 16];
-    float p[NSUB];
-    int row[NSUB];  // -1: no row
+    h2 p2[NSUB];   // (kappa p, kappa p), zero for a lane without a row
+    int row[NSUB]; // -1: no row
 };
 
-// Issue the gather of one unit: lane j of each 32-row sub-tile reads its row's K pieces.
-template <int DS, int NSUB>
-__device__ __forceinline__ void gather_rows(RowUnit<DS, NSUB> &u, const int (&a)[NSUB], const int (&row)[NSUB],
-                                            const bf16_t *__restrict__ x, const float *__restrict__ pk, int k, int g)
+// The 16 fp16 biases (already scaled by kappa) of hidden tile ht for lane group g, in accumulator order.
+__device__ __forceinline__ void load_bias_tile(const uint4 *__restrict__ b1s, int ht, int g, h2 (&bias)[8])
 {
+    const uint4 b0 = b1s[(ht * 2 + g) * 2 + 0], b1 = b1s[(ht * 2 + g) * 2 + 1];
+    bias[0] = as_h2(b0.x); bias[1] = as_h2(b0.y); bias[2] = as_h2(b0.z); bias[3] = as_h2(b0.w);
+    bias[4] = as_h2(b1.x); bias[5] = as_h2(b1.y); bias[6] = as_h2(b1.z); bias[7] = as_h2(b1.w);
+}
+
+template <int DS, int NSUB>
+__device__ __forceinline__ void gemm1_tile(const RowUnit<DS, NSUB> &u, const uint4 *__restrict__ w1s, int hl, int lane,
+                                           f32x16 (&acc)[NSUB])
+{
+    constexpr int KS = DS / 16;
 #pragma unroll
-    for (int sub = 0; sub < NSUB; ++sub) {
-        const bool valid = row[sub] >= 0;
-        u.row[sub] = row[sub];
-        u.p[sub] = valid ? pk[a[sub]] : 0.f;
-        const long long n = a[sub] / k;
-        const uint4 *xp = (const uint4 *)(x + n * DS);
+    for (int sub = 0; sub < NSUB; ++sub)
 #pragma unroll
-        for (int ks = 0; ks < DS / 16; ++ks) {
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (valid) v = xp[ks * 2 + g];
-            u.xb[sub][ks] = __builtin_bit_cast(bf16x8, v);
-        }
+        for (int r = 0; r < 16; ++r) acc[sub][r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8 a1 = __builtin_bit_cast(bf16x8, w1s[(hl * KS + ks) * 64 + lane]);
+#pragma unroll
+        for (int sub = 0; sub < NSUB; ++sub) acc[sub] = mfma_bf16(a1, u.xb[sub][ks], acc[sub]);
     }
 }
 
-// All hidden tiles [ht0, ht0 + nht) staged at w1s / w2s (tile hl at fragment offset hl): GEMM1,
-// activation, GEMM2 accumulation into yacc.
 template <int DS, int NSUB>
-__device__ __forceinline__ void ffn_hidden_tiles(const RowUnit<DS, NSUB> &u, f32x16 (&yacc)[NSUB][DS / 32],
-                                                 const uint4 *__restrict__ w1s, const uint4 *__restrict__ w2s,
-                                                 const float *__restrict__ b1s, int ht0, int nht, int lane, int g)
+__device__ __forceinline__ void gemm2_tile(const uint4 (&hb)[NSUB][2], const uint4 *__restrict__ w2s, int hl, int lane,
+                                           f32x16 (&yacc)[NSUB][DS / 32])
 {
-    constexpr int KS = DS / 16;
     constexpr int OT = DS / 32;
-    for (int hl = 0; hl < nht; ++hl) {
-        f32x16 acc[NSUB];
 #pragma unroll
-        for (int sub = 0; sub < NSUB; ++sub)
+    for (int s = 0; s < 2; ++s)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[sub][r] = 0.f;
+        for (int ot = 0; ot < OT; ++ot) {
+            const f16x8 a2 = __builtin_bit_cast(f16x8, w2s[((hl * 2 + s) * OT + ot) * 64 + lane]);
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const bf16x8 a1 = __builtin_bit_cast(bf16x8, w1s[(hl * KS + ks) * 64 + lane]);
-#pragma unroll
-            for (int sub = 0; sub < NSUB; ++sub) acc[sub] = mfma_bf16(a1, u.xb[sub][ks], acc[sub]);
+            for (int sub = 0; sub < NSUB; ++sub)
+                yacc[sub][ot] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a2, __builtin_bit_cast(f16x8, hb[sub][s]), yacc[sub][ot], 0, 0, 0);
         }
-        f32x4 bq[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) bq[q] = *(const f32x4 *)(b1s + (ht0 + hl) * 32 + 8 * q + 4 * g);
-        bf16x8 hb[NSUB][2];
-#pragma unroll
-        for (int sub = 0; sub < NSUB; ++sub)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float z = fmaf(acc[sub][r], u.p[sub], bq[r >> 2][r & 3]);
-                hb[sub][r >> 3][r & 7] = (__bf16)gelu_poly(z);
-            }
-#pragma unroll
-        for (int s = 0; s < 2; ++s)
-#pragma unroll
-            for (int ot = 0; ot < OT; ++ot) {
-                const bf16x8 a2 = __builtin_bit_cast(bf16x8, w2s[((hl * 2 + s) * OT + ot) * 64 + lane]);
-#pragma unroll
-                for (int sub = 0; sub < NSUB; ++sub) yacc[sub][ot] = mfma_bf16(a2, hb[sub][s], yacc[sub][ot]);
-            }
-    }
 }
 
 __device__ __forceinline__ uint32_t pack_half2(float a, float b)
 {
-    f16x2 v;
-    v[0] = (half_t)a;
-    v[1] = (half_t)b;
-    return __builtin_bit_cast(uint32_t, v);
+    return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(a, b));
 }
 
 // y rows as fp16.  Per output tile a lane holds features 8q + 4g + (0..3) of its own row, i.e. half
@@ -176,6 +203,151 @@ __device__ __forceinline__ void zero_acc(f32x16 (&yacc)[NSUB][DS / 32])
             for (int r = 0; r < 16; ++r) yacc[sub][ot][r] = 0.f;
 }
 
+// Stacked row of lane j in sub-tile `sub` of the unit starting at `base` (or -1 past `end`), and its
+// assignment id; a lane without a row reads perm[0], which keeps every later access in bounds.
+template <int NSUB>
+__device__ __forceinline__ void unit_rows(int base, int end, bool unit_ok, int j, const int32_t *__restrict__ perm,
+                                          int (&row)[NSUB], int (&a)[NSUB])
+{
+#pragma unroll
+    for (int sub = 0; sub < NSUB; ++sub) {
+        const int rr = base + sub * 32 + j;
+        const bool ok = unit_ok && rr < end;
+        row[sub] = ok ? rr : -1;
+        a[sub] = perm[ok ? rr : 0];
+    }
+}
+
+// Issue the gather of one unit: lane (j, g) reads the 16-byte pieces 2*ks + g of its row.
+template <int DS, int NSUB>
+__device__ __forceinline__ void load_rows(RowUnit<DS, NSUB> &u, const int (&a)[NSUB], const int (&row)[NSUB],
+                                          const bf16_t *__restrict__ x, const float *__restrict__ pk, int k, int g,
+                                          float (&p)[NSUB])
+{
+#pragma unroll
+    for (int sub = 0; sub < NSUB; ++sub) {
+        u.row[sub] = row[sub];
+        const long long n = a[sub] / k;
+        const uint4 *xp = (const uint4 *)(x + n * DS) + g;
+#pragma unroll
+        for (int ks = 0; ks < DS / 16; ++ks) u.xb[sub][ks] = __builtin_bit_cast(bf16x8, xp[ks * 2]);
+        p[sub] = pk[a[sub]];
+    }
+}
+
+template <int DS, int NSUB>
+__device__ __forceinline__ void set_p(RowUnit<DS, NSUB> &u, const float (&p)[NSUB])
+{
+#pragma unroll
+    for (int sub = 0; sub < NSUB; ++sub) {
+        const float pv = u.row[sub] >= 0 ? p[sub] * kGeluKappa : 0.f;
+        u.p2[sub] = __builtin_bit_cast(h2, __builtin_amdgcn_cvt_pkrtz(pv, pv));
+    }
+}
+
+// ------------------------------------------------------------------------------ resident
+constexpr int kResThreads = 1024;
+constexpr int kResWaves = kResThreads / 64;
+constexpr int kResU = 32;  // rows per wavefront unit (NSUB = 1)
+
+// One expert block in LDS exactly as it is packed in memory (W1 | W2 | b1 fp16 | b2 fp32, see pack.hip).
+template <int HT>
+__global__ __launch_bounds__(kResThreads) void ffn_resident_kernel(
+    const bf16_t *__restrict__ x, const float *__restrict__ pk, const int32_t *__restrict__ offsets,
+    const int32_t *__restrict__ perm, const char *__restrict__ experts, size_t e_stride, size_t off_w2,
+    size_t off_b1, size_t off_b2, int E, int k, EpiConst K, half_t *__restrict__ y)
+{
+    constexpr int DS = 64;
+    extern __shared__ __align__(16) char lds[];
+    const uint4 *w1s = (const uint4 *)lds;                  // [HT][4][64] fragments
+    const uint4 *w2s = (const uint4 *)(lds + off_w2);       // [HT][2][2][64] fragments
+    const uint4 *b1s = (const uint4 *)(lds + off_b1);       // [HT][2][16] fp16
+    const float *b2s = (const float *)(lds + off_b2);       // [64]
+
+    const int tid = threadIdx.x, lane = tid & 63, j = lane & 31, g = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    // lane e keeps the end of expert e's row range: expert lookups are one ballot, not a chain of loads
+    const int off_hi = offsets[min(lane + 1, E)];
+    const int n_kept = __builtin_amdgcn_readfirstlane(__shfl(off_hi, E - 1));
+
+    // even split of the kept rows over the blocks, in whole units; blocks that share an XCD (blockIdx % 8)
+    // take consecutive row ranges, so an expert's weights are fetched into few L2s
+    const int units_total = (n_kept + kResU - 1) / kResU;
+    const int units_per_block = (units_total + gridDim.x - 1) / gridDim.x;
+    const int vblock = gridDim.x % 8 == 0 ? (int)(blockIdx.x % 8) * (int)(gridDim.x / 8) + (int)(blockIdx.x / 8) : (int)blockIdx.x;
+    const long long r_begin = (long long)vblock * units_per_block * kResU;
+    const int r_end = (int)min((long long)n_kept, r_begin + (long long)units_per_block * kResU);
+
+    int r = (int)min(r_begin, (long long)n_kept);
+    while (r < r_end) {
+        const int e = __builtin_amdgcn_readfirstlane(__popcll(__ballot(lane < E && off_hi <= r)));
+        const int seg_end = min(__builtin_amdgcn_readfirstlane(__shfl(off_hi, e)), r_end);
+        const char *ew = experts + (size_t)e * e_stride;
+        const int nunits = (seg_end - r + kResU - 1) / kResU;   // this wavefront takes units wave, wave + 16, ...
+
+        __syncthreads();  // everyone is done with the previous expert's weights
+        // stage the expert block: plain 16-byte loads, then LDS writes
+        const int pieces = (int)(e_stride / 16);
+        constexpr int kMaxPer = (HT * 8192 + HT * 64 + 512 + kResThreads * 16 - 1) / (kResThreads * 16);   // covers e_stride
+        uint4 wtmp[kMaxPer];
+#pragma unroll
+        for (int i = 0; i < kMaxPer; ++i) {
+            const int idx = tid + i * kResThreads;
+            wtmp[i] = ((const uint4 *)ew)[idx < pieces ? idx : 0];
+        }
+        int q_c = wave;
+        int row_c[1], a_c[1], row_n[1], a_n[1];
+        float p_c[1], p_n[1];
+        unit_rows<1>(r + q_c * kResU, seg_end, q_c < nunits, j, perm, row_c, a_c);
+        RowUnit<DS, 1> cur, nxt;
+        load_rows<DS, 1>(cur, a_c, row_c, x, pk, k, g, p_c);
+#pragma unroll
+        for (int i = 0; i < kMaxPer; ++i) {
+            const int idx = tid + i * kResThreads;
+            if (idx < pieces) ((uint4 *)lds)[idx] = wtmp[i];
+        }
+        set_p<DS, 1>(cur, p_c);
+        __syncthreads();
+
+        while (q_c < nunits) {
+            const int q_n = q_c + kResWaves;
+            {   // fewer units left -> lower priority: the wavefronts of a block finish together
+                const int left = (nunits - 1 - q_c) / kResWaves;
+                if (left >= 3) __builtin_amdgcn_s_setprio(3);
+                else if (left == 2) __builtin_amdgcn_s_setprio(2);
+                else if (left == 1) __builtin_amdgcn_s_setprio(1);
+                else __builtin_amdgcn_s_setprio(0);
+            }
+            unit_rows<1>(r + q_n * kResU, seg_end, q_n < nunits, j, perm, row_n, a_n);
+
+            f32x16 yacc[1][2];
+            zero_acc<DS, 1>(yacc);
+            f32x16 acc[2][1];
+            uint4 hb[1][2];
+            gemm1_tile<DS, 1>(cur, w1s, 0, lane, acc[0]);
+#pragma unroll
+            for (int hl = 0; hl < HT; ++hl) {
+                if (hl + 1 < HT) gemm1_tile<DS, 1>(cur, w1s, hl + 1, lane, acc[(hl + 1) & 1]);
+                h2 bias[8];
+                load_bias_tile(b1s, hl, g, bias);
+                activation_tile(acc[hl & 1][0], cur.p2[0], bias, K, hb[0]);
+                gemm2_tile<DS, 1>(hb, w2s, hl, lane, yacc);
+                if (hl == (HT - 1) / 2) load_rows<DS, 1>(nxt, a_n, row_n, x, pk, k, g, p_n);   // half a unit of lead time
+            }
+            store_rows<DS, 1>(cur, yacc, b2s, y, g);
+            cur = nxt;
+            set_p<DS, 1>(cur, p_n);
+            q_c = q_n;
+        }
+        r = seg_end;
+    }
+}
+
+// ------------------------------------------------------------------------------ streamed
+constexpr int kFfnThreads = 256;
+constexpr int kFfnWaves = kFfnThreads / 64;
+
 // Asynchronous copy of n16 16-byte pieces from global memory to LDS by the whole block: each
 // wavefront-level instruction moves 1 KiB (lane i -> dst + 16*i) without passing through registers.
 // The caller waits (vmcnt) and synchronises before reading.
@@ -188,109 +360,11 @@ __device__ __forceinline__ void async_copy_to_lds(const uint4 *__restrict__ src,
                                          (void __attribute__((address_space(3))) *)(dst + c * 64), 16, 0, 0);
 }
 
-// ------------------------------------------------------------------------------ resident
-constexpr int kResThreads = 512;
-constexpr int kResWaves = kResThreads / 64;
-
-template <int DS, int NSUB>
-__global__ __launch_bounds__(kResThreads, 2) void ffn_resident_kernel(
-    const bf16_t *__restrict__ x, const float *__restrict__ pk, const int32_t *__restrict__ offsets,
-    const int32_t *__restrict__ perm, const char *__restrict__ experts, size_t e_stride, size_t off_w1,
-    size_t off_w2, size_t off_b1, size_t off_b2, int He, int E, int k, half_t *__restrict__ y)
-{
-    constexpr int KS = DS / 16;
-    constexpr int OT = DS / 32;
-    constexpr int U = 32 * NSUB;  // rows per wavefront unit
-    const int HT = He / 32;
-
-    extern __shared__ __align__(16) char lds[];
-    uint4 *w1s = (uint4 *)lds;                                // [HT][KS][64] fragments
-    uint4 *w2s = w1s + (size_t)HT * KS * 64;                  // [HT][2][OT][64] fragments
-    float *b1s = (float *)(w2s + (size_t)HT * 2 * OT * 64);   // [He]
-    float *b2s = b1s + He;                                    // [DS]
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int j = lane & 31;
-    const int g = lane >> 5;
-
-    // lane e keeps the end of expert e's row range: expert lookups are one ballot, not a chain of loads
-    const int off_hi = offsets[min(lane + 1, E)];
-    const int n_kept = __shfl(off_hi, E - 1);
-
-    // even split of the kept rows over the blocks, in whole units
-    const int units_total = (n_kept + U - 1) / U;
-    const int units_per_block = (units_total + gridDim.x - 1) / gridDim.x;
-    const long long r_begin = (long long)blockIdx.x * units_per_block * U;
-    const int r_end = (int)min((long long)n_kept, r_begin + (long long)units_per_block * U);
-
-    int r = (int)min(r_begin, (long long)n_kept);
-    while (r < r_end) {
-        const int e = __popcll(__ballot(lane < E && off_hi <= r));
-        const int seg_end = min(__shfl(off_hi, e), r_end);
-        const char *ew = experts + (size_t)e * e_stride;
-
-        // units of this segment: unit q covers rows r + q*U ..., this wavefront takes q = wave, wave+8, ...
-        const int nunits = (seg_end - r + U - 1) / U;
-        auto unit_rows = [&](int q, int (&row)[NSUB]) {
-#pragma unroll
-            for (int sub = 0; sub < NSUB; ++sub) {
-                const int rr = r + q * U + sub * 32 + j;
-                row[sub] = (q < nunits && rr < seg_end) ? rr : -1;
-            }
-        };
-        auto load_perm = [&](const int (&row)[NSUB], int (&a)[NSUB]) {
-#pragma unroll
-            for (int sub = 0; sub < NSUB; ++sub) a[sub] = row[sub] >= 0 ? perm[row[sub]] : 0;
-        };
-        // row indices of the first two units go out first, the weight copy overlaps their latency
-        int row_c[NSUB], a_c[NSUB], row_n[NSUB], a_n[NSUB];
-        unit_rows(wave, row_c);
-        load_perm(row_c, a_c);
-        unit_rows(wave + kResWaves, row_n);
-        load_perm(row_n, a_n);
-
-        __syncthreads();  // everyone is done with the previous expert's weights
-        async_copy_to_lds<kResThreads>((const uint4 *)(ew + off_w1), w1s, HT * KS * 64, tid);
-        async_copy_to_lds<kResThreads>((const uint4 *)(ew + off_w2), w2s, HT * 2 * OT * 64, tid);
-        {
-            const float *gb1 = (const float *)(ew + off_b1);
-            const float *gb2 = (const float *)(ew + off_b2);
-            for (int i = tid; i < He; i += kResThreads) b1s[i] = gb1[i];
-            for (int i = tid; i < DS; i += kResThreads) b2s[i] = gb2[i];
-        }
-        RowUnit<DS, NSUB> cur;
-        gather_rows<DS, NSUB>(cur, a_c, row_c, x, pk, k, g);
-        __builtin_amdgcn_s_waitcnt(0);  // the asynchronous copies have landed
-        __syncthreads();
-
-        for (int q = wave; q < nunits; q += kResWaves) {
-            // next unit's rows (indices arrived during the previous unit), indices of the one after
-            RowUnit<DS, NSUB> nxt;
-            gather_rows<DS, NSUB>(nxt, a_n, row_n, x, pk, k, g);
-            unit_rows(q + 2 * kResWaves, row_n);
-            load_perm(row_n, a_n);
-
-            f32x16 yacc[NSUB][OT];
-            zero_acc<DS, NSUB>(yacc);
-            ffn_hidden_tiles<DS, NSUB>(cur, yacc, w1s, w2s, b1s, 0, HT, lane, g);
-            store_rows<DS, NSUB>(cur, yacc, b2s, y, g);
-            cur = nxt;
-        }
-        r = seg_end;
-    }
-}
-
-// ------------------------------------------------------------------------------ streamed
-constexpr int kFfnThreads = 256;
-constexpr int kFfnWaves = kFfnThreads / 64;
-
 template <int DS, int NSUB>
 __global__ __launch_bounds__(kFfnThreads) void ffn_streamed_kernel(
     const bf16_t *__restrict__ x, const float *__restrict__ pk, const int32_t *__restrict__ offsets,
     const int32_t *__restrict__ perm, const char *__restrict__ experts, size_t e_stride, size_t off_w1,
-    size_t off_w2, size_t off_b1, size_t off_b2, int He, int E, int k, int hc, half_t *__restrict__ y)
+    size_t off_w2, size_t off_b1, size_t off_b2, int He, int E, int k, int hc, EpiConst K, half_t *__restrict__ y)
 {
     constexpr int KS = DS / 16;
     constexpr int OT = DS / 32;
@@ -301,8 +375,8 @@ __global__ __launch_bounds__(kFfnThreads) void ffn_streamed_kernel(
     extern __shared__ __align__(16) char lds[];
     uint4 *w1s = (uint4 *)lds;                                     // [hc][KS][64] fragments
     uint4 *w2s = w1s + (size_t)hc * KS * 64;                       // [hc][2][OT][64] fragments
-    float *b1s = (float *)(w2s + (size_t)hc * 2 * OT * 64);        // [He]
-    float *b2s = b1s + He;                                         // [DS]
+    uint4 *b1s = w2s + (size_t)hc * 2 * OT * 64;                   // [HT][2][16] fp16 = He * 2 bytes
+    float *b2s = (float *)(b1s + He / 8);                          // [DS]
     int *tile_prefix = (int *)(b2s + DS);                          // [E+1]
 
     const int tid = threadIdx.x;
@@ -335,14 +409,11 @@ __global__ __launch_bounds__(kFfnThreads) void ffn_streamed_kernel(
         const bool new_expert = e != cur_e;
 
         int row[NSUB], a[NSUB];
-#pragma unroll
-        for (int sub = 0; sub < NSUB; ++sub) {
-            const int rr = row_begin + (wave * NSUB + sub) * 32 + j;
-            row[sub] = rr < row_end ? rr : -1;
-            a[sub] = row[sub] >= 0 ? perm[rr] : 0;
-        }
+        float p[NSUB];
+        unit_rows<NSUB>(row_begin + wave * NSUB * 32, row_end, true, j, perm, row, a);
         RowUnit<DS, NSUB> cur;
-        gather_rows<DS, NSUB>(cur, a, row, x, pk, k, g);
+        load_rows<DS, NSUB>(cur, a, row, x, pk, k, g, p);
+        set_p<DS, NSUB>(cur, p);
 
         f32x16 yacc[NSUB][OT];
         zero_acc<DS, NSUB>(yacc);
@@ -352,14 +423,23 @@ __global__ __launch_bounds__(kFfnThreads) void ffn_streamed_kernel(
             async_copy_to_lds<kFfnThreads>((const uint4 *)(ew + off_w2) + (size_t)ch * hc * 2 * OT * 64, w2s,
                                            hc * 2 * OT * 64, tid);
             if (new_expert && ch == 0) {
-                const float *gb1 = (const float *)(ew + off_b1);
+                const uint4 *gb1 = (const uint4 *)(ew + off_b1);
                 const float *gb2 = (const float *)(ew + off_b2);
-                for (int i = tid; i < He; i += kFfnThreads) b1s[i] = gb1[i];
+                for (int i = tid; i < He / 8; i += kFfnThreads) b1s[i] = gb1[i];
                 for (int i = tid; i < DS; i += kFfnThreads) b2s[i] = gb2[i];
             }
             __builtin_amdgcn_s_waitcnt(0);
             __syncthreads();
-            ffn_hidden_tiles<DS, NSUB>(cur, yacc, w1s, w2s, b1s, ch * hc, hc, lane, g);
+            for (int hl = 0; hl < hc; ++hl) {
+                f32x16 acc[NSUB];
+                gemm1_tile<DS, NSUB>(cur, w1s, hl, lane, acc);
+                h2 bias[8];
+                load_bias_tile(b1s, ch * hc + hl, g, bias);
+                uint4 hb[NSUB][2];
+#pragma unroll
+                for (int sub = 0; sub < NSUB; ++sub) activation_tile(acc[sub], cur.p2[sub], bias, K, hb[sub]);
+                gemm2_tile<DS, NSUB>(hb, w2s, hl, lane, yacc);
+            }
         }
         cur_e = e;
         store_rows<DS, NSUB>(cur, yacc, b2s, y, g);
@@ -372,22 +452,22 @@ struct FfnPlan {
     size_t lds;
 };
 
-// Whole expert resident in LDS when it fits in half of a CU's LDS, else hidden tiles per chunk.
-static FfnPlan plan_ffn(int ds, int He, int E)
+// Whole expert resident in LDS for ds = 64 and He in {64, 128, 256}, else hidden tiles per chunk.
+static FfnPlan plan_ffn(const PackedLayout &L)
 {
+    const int ds = L.ds, He = L.He, E = L.E;
     const int HT = He / 32, KS = ds / 16, OT = ds / 32;
     const size_t frag_per_ht = (size_t)(KS + 2 * OT) * 1024;  // bytes of W1+W2 fragments per hidden tile
     const size_t dev_max = (size_t)max_lds_per_block();
     FfnPlan p;
-    const size_t resident_bytes = frag_per_ht * HT + (size_t)(He + ds) * 4;
-    if (ds == 64 && resident_bytes <= 78 * 1024 && resident_bytes <= dev_max) {
+    if (ds == 64 && (He == 64 || He == 128 || He == 256) && L.e_stride <= dev_max) {
         p.resident = true;
         p.hc = HT;
-        p.lds = resident_bytes;
+        p.lds = L.e_stride;
         return p;
     }
     // a streamed block needs the whole register file of its CU anyway, so chunks may take most of the LDS
-    const size_t fixed = (size_t)(He + ds + E + 1) * 4 + 64;
+    const size_t fixed = (size_t)He * 2 + (size_t)(ds + E + 1) * 4 + 64;
     const size_t want = 140 * 1024;
     const size_t budget = dev_max < want ? dev_max : want;
     p.resident = false;
@@ -401,38 +481,38 @@ static FfnPlan plan_ffn(int ds, int He, int E)
     return p;
 }
 
-template <int DS, int NSUB>
-static hipError_t run_ffn(const slicemoe_config &c, const FfnPlan &pl, const void *h, const float *p,
-                          const int32_t *offsets, const int32_t *perm, const void *packed, void *y,
-                          hipStream_t s)
+template <int HT>
+static hipError_t run_resident(const slicemoe_config &c, const PackedLayout &L, const FfnPlan &pl, const void *h,
+                               const float *p, const int32_t *offsets, const int32_t *perm, const char *experts,
+                               void *y, hipStream_t s)
 {
-    const PackedLayout L = packed_layout(c);
     const long long Na = (long long)c.T * c.S * c.k;
-    const char *experts = (const char *)packed + L.experts;
-    hipError_t err;
-    if constexpr (DS == 64) {
-        if (pl.resident) {
-            constexpr int U = 32 * NSUB;
-            long long blocks = (long long)num_compute_units();
-            const long long max_blocks = (Na + U - 1) / U;
-            if (blocks > max_blocks) blocks = max_blocks;
-            auto kern = ffn_resident_kernel<DS, NSUB>;
-            err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds);
-            if (err != hipSuccess) return err;
-            kern<<<(int)blocks, kResThreads, pl.lds, s>>>((const bf16_t *)h, p, offsets, perm, experts, L.e_stride,
-                                                          L.e_w1, L.e_w2, L.e_b1, L.e_b2, c.He, c.E, c.k, (half_t *)y);
-            return hipGetLastError();
-        }
-    }
+    const long long max_units = (Na + kResU - 1) / kResU;
+    long long blocks = (max_units + kResWaves - 1) / kResWaves;
+    if (blocks > num_compute_units()) blocks = num_compute_units();
+    auto kern = ffn_resident_kernel<HT>;
+    hipError_t err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds);
+    if (err != hipSuccess) return err;
+    kern<<<(int)blocks, kResThreads, pl.lds, s>>>((const bf16_t *)h, p, offsets, perm, experts, L.e_stride, L.e_w2, L.e_b1,
+                                                  L.e_b2, c.E, c.k, make_epi_const(), (half_t *)y);
+    return hipGetLastError();
+}
+
+template <int DS, int NSUB>
+static hipError_t run_streamed(const slicemoe_config &c, const PackedLayout &L, const FfnPlan &pl, const void *h,
+                               const float *p, const int32_t *offsets, const int32_t *perm, const char *experts,
+                               void *y, hipStream_t s)
+{
+    const long long Na = (long long)c.T * c.S * c.k;
     constexpr int TM = kFfnWaves * NSUB * 32;
     const long long max_tiles = (Na + TM - 1) / TM + c.E;
     long long blocks = (long long)num_compute_units() * (pl.lds <= 78 * 1024 ? 2 : 1);
     if (blocks > max_tiles) blocks = max_tiles;
     auto kern = ffn_streamed_kernel<DS, NSUB>;
-    err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds);
+    hipError_t err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds);
     if (err != hipSuccess) return err;
-    kern<<<(int)blocks, kFfnThreads, pl.lds, s>>>((const bf16_t *)h, p, offsets, perm, experts, L.e_stride, L.e_w1,
-                                                  L.e_w2, L.e_b1, L.e_b2, c.He, c.E, c.k, pl.hc, (half_t *)y);
+    kern<<<(int)blocks, kFfnThreads, pl.lds, s>>>((const bf16_t *)h, p, offsets, perm, experts, L.e_stride, L.e_w1, L.e_w2,
+                                                  L.e_b1, L.e_b2, c.He, c.E, c.k, pl.hc, make_epi_const(), (half_t *)y);
     return hipGetLastError();
 }
 
@@ -442,10 +522,16 @@ hipError_t launch_ffn_mfma(const slicemoe_config &c, const void *h, const float 
 {
     const long long Na = (long long)c.T * c.S * c.k;
     if (Na == 0) return hipSuccess;
-    const int ds = c.d / c.S;
-    const FfnPlan pl = plan_ffn(ds, c.He, c.E);
-    if (ds == 64) return run_ffn<64, 2>(c, pl, h, p, offsets, perm, packed, y, s);
-    return run_ffn<128, 2>(c, pl, h, p, offsets, perm, packed, y, s);
+    const PackedLayout L = packed_layout(c);
+    const FfnPlan pl = plan_ffn(L);
+    const char *experts = (const char *)packed + L.experts;
+    if (pl.resident) {
+        if (L.He == 256) return run_resident<8>(c, L, pl, h, p, offsets, perm, experts, y, s);
+        if (L.He == 128) return run_resident<4>(c, L, pl, h, p, offsets, perm, experts, y, s);
+        return run_resident<2>(c, L, pl, h, p, offsets, perm, experts, y, s);
+    }
+    if (L.ds == 64) return run_streamed<64, 2>(c, L, pl, h, p, offsets, perm, experts, y, s);
+    return run_streamed<128, 2>(c, L, pl, h, p, offsets, perm, experts, y, s);
 }
 
 }  // namespace slicemoe

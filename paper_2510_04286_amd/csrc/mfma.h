@@ -14,6 +14,7 @@
 // The contraction order is free, so the weights of GEMM2 are simply packed in that slot order.
 #pragma once
 #include "common.h"
+#include "gelu_poly.h"
 
 namespace slicemoe {
 

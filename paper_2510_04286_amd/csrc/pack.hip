@@ -5,7 +5,12 @@
 // Router   W1 frags [Hr/32][ds/16][64 lanes]      lane (i, g), slot m: Wr1[16*ks + 8*g + m][32*ht + i]
 //          W2 frags [Epad/32][Hr/32][2][64]       lane (i, g), slot m: Wr2[32*ht + chain_feature(s,g,m)][32*et + i]
 // Expert e W1 frags [He/32][ds/16][64]            W1[e][16*ks + 8*g + m][32*ht + i]
-//          W2 frags [He/32][2][ds/32][64]         W2[e][32*ht + chain_feature(s,g,m)][32*ot + i]
+//          W2 frags [He/32][2][ds/32][64]         W2[e][32*ht + chain_feature(s,g,m)][32*ot + i] / kappa, as fp16
+//          b1       [He/32][2 lane groups][16]    kappa * b1[e][32*ht + acc_feature(r, g)], as fp16
+//          b2       [ds] fp32
+// The expert kernel evaluates its activation on s = kappa z in packed fp16 (see ffn_mfma.hip), so
+// its second GEMM runs on fp16 fragments; bf16 weights convert exactly to fp16 unless they are
+// smaller than 2^-14 / 4 (rounded, absolute error below 2^-27) or beyond +-16376 (clamped).
 #include "mfma.h"
 
 namespace slicemoe {
@@ -45,7 +50,8 @@ __global__ void pack_layer1_kernel(const bf16_t *__restrict__ W, int K, int N, s
 // contraction slots follow the accumulator layout of GEMM1.  order_outer_first = true lays
 // fragments out as [nt][ht][s][lane] (router), false as [ht][s][nt][lane] (experts).
 __global__ void pack_layer2_kernel(const bf16_t *__restrict__ W, int K, int N, int Npad, size_t src_stride,
-                                   char *__restrict__ dst, size_t dst_stride, int nmat, bool order_outer_first)
+                                   char *__restrict__ dst, size_t dst_stride, int nmat, bool order_outer_first,
+                                   bool as_f16, float f16_scale)
 {
     const int HT = K / 32, NT = Npad / 32;
     const long long per = (long long)HT * 2 * NT * 64;
@@ -71,9 +77,30 @@ __global__ void pack_layer2_kernel(const bf16_t *__restrict__ W, int K, int N, i
     const int col = 32 * nt + i;
     const bf16_t *src = W + (size_t)mat * src_stride;
     bf16_t v[8];
-    for (int m = 0; m < 8; ++m)
-        v[m] = col < N ? src[(size_t)(32 * ht + chain_feature(s, g, m)) * N + col] : (bf16_t)0;
+    for (int m = 0; m < 8; ++m) {
+        const bf16_t w = col < N ? src[(size_t)(32 * ht + chain_feature(s, g, m)) * N + col] : (bf16_t)0;
+        if (as_f16) {
+            const float f = fminf(fmaxf(bf16_to_f32(w) * f16_scale, -65504.f), 65504.f);
+            const _Float16 hv = (_Float16)f;
+            v[m] = __builtin_bit_cast(bf16_t, hv);
+        } else {
+            v[m] = w;
+        }
+    }
     store_frag(dst + (size_t)mat * dst_stride + (size_t)(f - (long long)mat * per) * 16, v);
+}
+
+// Expert first-layer biases as fp16, scaled, in the accumulator order of each hidden tile.
+__global__ void pack_bias_f16_kernel(const bf16_t *__restrict__ b, int n, size_t src_stride, char *__restrict__ dst,
+                                     size_t dst_stride, int nmat, float scale)
+{
+    const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (long long)n * nmat) return;
+    const int mat = (int)(t / n);
+    const int i = (int)(t - (long long)mat * n);
+    const int ht = i / 32, g = (i % 32) / 16, r = i % 16;
+    const float f = fminf(fmaxf(bf16_to_f32(b[(size_t)mat * src_stride + 32 * ht + acc_feature(r, g)]) * scale, -65504.f), 65504.f);
+    ((_Float16 *)(dst + (size_t)mat * dst_stride))[i] = (_Float16)f;
 }
 
 __global__ void pack_bias_kernel(const bf16_t *__restrict__ b, int n, int npad, size_t src_stride,
@@ -98,7 +125,7 @@ hipError_t launch_pack(const slicemoe_config &c, const slicemoe_weights &w, void
     pack_layer1_kernel<<<blocks_for((long long)(Hr / 32) * (ds / 16) * 64), 256, 0, s>>>(
         (const bf16_t *)w.Wr1, ds, Hr, 0, base + L.r_w1, 0, 1);
     pack_layer2_kernel<<<blocks_for((long long)(Hr / 32) * 2 * (Epad / 32) * 64), 256, 0, s>>>(
-        (const bf16_t *)w.Wr2, Hr, E, Epad, 0, base + L.r_w2, 0, 1, true);
+        (const bf16_t *)w.Wr2, Hr, E, Epad, 0, base + L.r_w2, 0, 1, true, false, 1.f);
     pack_bias_kernel<<<blocks_for(Hr), 256, 0, s>>>((const bf16_t *)w.br1, Hr, Hr, 0, base + L.r_b1, 0, 1);
     pack_bias_kernel<<<blocks_for(Epad), 256, 0, s>>>((const bf16_t *)w.br2, E, Epad, 0, base + L.r_b2, 0, 1);
     // experts
@@ -106,9 +133,9 @@ hipError_t launch_pack(const slicemoe_config &c, const slicemoe_weights &w, void
     pack_layer1_kernel<<<blocks_for((long long)E * (He / 32) * (ds / 16) * 64), 256, 0, s>>>(
         (const bf16_t *)w.W1, ds, He, (size_t)ds * He, eb + L.e_w1, L.e_stride, E);
     pack_layer2_kernel<<<blocks_for((long long)E * (He / 32) * 2 * (ds / 32) * 64), 256, 0, s>>>(
-        (const bf16_t *)w.W2, He, ds, ds, (size_t)He * ds, eb + L.e_w2, L.e_stride, E, false);
-    pack_bias_kernel<<<blocks_for((long long)E * He), 256, 0, s>>>((const bf16_t *)w.b1, He, He, He, eb + L.e_b1,
-                                                                   L.e_stride, E);
+        (const bf16_t *)w.W2, He, ds, ds, (size_t)He * ds, eb + L.e_w2, L.e_stride, E, false, true, 1.f / kGeluKappa);
+    pack_bias_f16_kernel<<<blocks_for((long long)E * He), 256, 0, s>>>((const bf16_t *)w.b1, He, He, eb + L.e_b1,
+                                                                       L.e_stride, E, kGeluKappa);
     pack_bias_kernel<<<blocks_for((long long)E * ds), 256, 0, s>>>((const bf16_t *)w.b2, ds, ds, ds, eb + L.e_b2,
                                                                    L.e_stride, E);
     return hipGetLastError();
