@@ -24,7 +24,7 @@
 //   g  = s * F                                 = kappa GELU(z)
 // W2 is packed pre-multiplied by 1/kappa, so GEMM2 needs no rescaling.  fp16 has three more
 // mantissa bits than the bf16 storage type; evaluated this way the activation error is of the
-// size of one bf16 rounding: at most 2.5e-3 (rms below 8e-4) of the larger of |z| and |p a| (the same
+// size of a bf16 rounding: at most 2^-8 (rms below 8e-4) of the larger of |z| and |p a| (the same
 // roundings are replayed on the CPU in tests/test_gelu_poly.py).
 // Hidden activations beyond +-65504 / kappa would overflow fp16.
 //
