@@ -84,52 +84,93 @@ __device__ __forceinline__ void load_stats_wave(int raw, int kept_e, bool have, 
     }
 }
 
-// One block of 1024 threads.  Thread (seg, e) with e = tid % Epow2 sums a contiguous range of
-// chunks for expert e; the per-segment sums are scanned serially per expert (<= 1024/Epow2
-// segments), then each thread rewrites its range as exclusive prefixes.
+// One block of 1024 threads walks the [nblocks][E] table in tiles of kScanTile entries staged in
+// LDS (coalesced 16-byte loads and stores; the table is tiny, the kernel is latency-bound, so every
+// global access is issued in one batch).  Inside a tile, thread (seg, e) with e = tid % Epow2 owns a
+// contiguous run of chunks of expert e: it sums them, the per-segment sums are scanned serially per
+// expert (<= 1024/Epow2 segments) on top of the running total carried from the previous tiles, and
+// each thread rewrites its run as exclusive prefixes.
+constexpr int kScanTile = 8192;   // table entries per tile: 32 KiB of LDS
+
 __global__ __launch_bounds__(1024) void dispatch_scan_kernel(
     int32_t *__restrict__ block_counts, int nblocks, int E, int Epow2, long long capacity,
     int32_t *__restrict__ counts_raw, int32_t *__restrict__ counts, int32_t *__restrict__ offsets,
     float *__restrict__ stats /* may be null */)
 {
+    __shared__ __align__(16) int tile[kScanTile];
     __shared__ int seg_sum[1024];
+    __shared__ int carry[64];
     __shared__ int kept[64];
-    __shared__ int raw[64];
     const int tid = threadIdx.x;
     const int e = tid % Epow2;
     const int seg = tid / Epow2;
     const int nseg = 1024 / Epow2;
-    const int per = (nblocks + nseg - 1) / nseg;
-    const int b0 = seg * per;
-    const int b1 = min(nblocks, b0 + per);
-    int s = 0;
-    if (e < E)
-        for (int b = b0; b < b1; ++b) s += block_counts[(size_t)b * E + e];
-    seg_sum[tid] = s;
-    __syncthreads();
-    if (seg == 0 && e < E) {
-        int run = 0;
-        for (int g = 0; g < nseg; ++g) {
-            const int t = seg_sum[g * Epow2 + e];
-            seg_sum[g * Epow2 + e] = run;
-            run += t;
+    const int chunks_per_tile = kScanTile / E;          // whole chunks only
+    const long long total_entries = (long long)nblocks * E;
+    if (tid < 64) carry[tid] = 0;
+
+    for (int c0 = 0; c0 < nblocks; c0 += chunks_per_tile) {
+        const int nc = min(chunks_per_tile, nblocks - c0);
+        const long long first = (long long)c0 * E;            // entry index of the tile start
+        const int n_entries = nc * E;
+        // stage: 16-byte pieces where the tile start is 16-byte aligned (E % 4 == 0 or first tile), else scalars
+        const bool vec = ((first & 3) == 0);
+        __syncthreads();   // previous tile fully written back, carry visible
+        if (vec) {
+            for (int i = tid * 4; i < n_entries; i += 1024 * 4) {
+                if (i + 4 <= n_entries) *(int4 *)(tile + i) = *(const int4 *)(block_counts + first + i);
+                else for (int q = i; q < n_entries; ++q) tile[q] = block_counts[first + q];
+            }
+        } else {
+            for (int i = tid; i < n_entries; i += 1024) tile[i] = block_counts[first + i];
         }
-        counts_raw[e] = run;
+        __syncthreads();
+        const int per = (nc + nseg - 1) / nseg;
+        const int b0 = seg * per;
+        const int b1 = min(nc, b0 + per);
+        int s = 0;
+        if (e < E)
+            for (int b = b0; b < b1; ++b) s += tile[b * E + e];
+        seg_sum[tid] = s;
+        __syncthreads();
+        if (seg == 0 && e < E) {
+            int run = carry[e];
+            for (int g = 0; g < nseg; ++g) {
+                const int t = seg_sum[g * Epow2 + e];
+                seg_sum[g * Epow2 + e] = run;
+                run += t;
+            }
+            carry[e] = run;
+        }
+        __syncthreads();
+        if (e < E) {
+            int run = seg_sum[tid];
+            for (int b = b0; b < b1; ++b) {
+                const int t = tile[b * E + e];
+                tile[b * E + e] = run;
+                run += t;
+            }
+        }
+        __syncthreads();
+        if (vec) {
+            for (int i = tid * 4; i < n_entries; i += 1024 * 4) {
+                if (i + 4 <= n_entries) *(int4 *)(block_counts + first + i) = *(const int4 *)(tile + i);
+                else for (int q = i; q < n_entries; ++q) block_counts[first + q] = tile[q];
+            }
+        } else {
+            for (int i = tid; i < n_entries; i += 1024) block_counts[first + i] = tile[i];
+        }
+    }
+    (void)total_entries;
+    __syncthreads();
+    if (tid < E) {
+        const int run = carry[tid];
+        counts_raw[tid] = run;
         const int c = (capacity >= 0 && run > capacity) ? (int)capacity : run;
-        counts[e] = c;
-        kept[e] = c;
-        raw[e] = run;
+        counts[tid] = c;
+        kept[tid] = c;
     }
     __syncthreads();
-    if (e < E) {
-        int run = seg_sum[tid];
-        for (int b = b0; b < b1; ++b) {
-            const size_t at = (size_t)b * E + e;
-            const int t = block_counts[at];
-            block_counts[at] = run;
-            run += t;
-        }
-    }
     if (tid == 0) {
         int run = 0;
         for (int x = 0; x < E; ++x) {
@@ -140,7 +181,7 @@ __global__ __launch_bounds__(1024) void dispatch_scan_kernel(
     }
     if (stats && tid >= 64 && tid < 128) {  // second wavefront: the first one is busy with offsets
         const int x = tid - 64;
-        load_stats_wave(x < E ? raw[x] : 0, x < E ? kept[x] : 0, x < E, E, stats);
+        load_stats_wave(x < E ? carry[x] : 0, x < E ? kept[x] : 0, x < E, E, stats);
     }
 }
 

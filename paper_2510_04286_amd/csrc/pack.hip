@@ -3,7 +3,7 @@
 // contraction dimension.  Biases are widened to fp32.  One thread per fragment / bias element.
 //
 // Router   W1 frags [Hr/32][ds/16][64 lanes]      lane (i, g), slot m: Wr1[16*ks + 8*g + m][32*ht + i]
-//          W2 frags [Epad/32][Hr/32][2][64]       lane (i, g), slot m: Wr2[32*ht + chain_feature(s,g,m)][32*et + i]
+//          W2 frags [Epad/32][Hr/32][2][64]       lane (i, g), slot m: Wr2[32*ht + chain_feature(s,g,m)][32*et + i], as fp16
 // Expert e W1 frags [He/32][ds/16][64]            W1[e][16*ks + 8*g + m][32*ht + i]
 //          W2 frags [He/32][2][ds/32][64]         W2[e][32*ht + chain_feature(s,g,m)][32*ot + i] / kappa, as fp16
 //          b1       [He/32][2 lane groups][16]    kappa * b1[e][32*ht + acc_feature(r, g)], as fp16
@@ -125,7 +125,7 @@ hipError_t launch_pack(const slicemoe_config &c, const slicemoe_weights &w, void
     pack_layer1_kernel<<<blocks_for((long long)(Hr / 32) * (ds / 16) * 64), 256, 0, s>>>(
         (const bf16_t *)w.Wr1, ds, Hr, 0, base + L.r_w1, 0, 1);
     pack_layer2_kernel<<<blocks_for((long long)(Hr / 32) * 2 * (Epad / 32) * 64), 256, 0, s>>>(
-        (const bf16_t *)w.Wr2, Hr, E, Epad, 0, base + L.r_w2, 0, 1, true, false, 1.f);
+        (const bf16_t *)w.Wr2, Hr, E, Epad, 0, base + L.r_w2, 0, 1, true, true, 1.f);
     pack_bias_kernel<<<blocks_for(Hr), 256, 0, s>>>((const bf16_t *)w.br1, Hr, Hr, 0, base + L.r_b1, 0, 1);
     pack_bias_kernel<<<blocks_for(Epad), 256, 0, s>>>((const bf16_t *)w.br2, E, Epad, 0, base + L.r_b2, 0, 1);
     // experts

@@ -4,10 +4,13 @@
 // agree with a reference except on near-ties:
 //   GEMM1  bf16 x bf16 products are exact in fp32, accumulated in fp32 (bias preloaded into
 //          the accumulators).
-//   GEMM2  u stays fp32.  It is split exactly into three bf16 terms u = u0 + u1 + u2 (each the
-//          truncation of the running remainder: 8 + 8 + 8 significant bits), and the MFMA is
-//          issued once per term against the bf16 weights -- three exact-product passes instead
-//          of a slow fp32 matrix instruction.
+//   GEMM2  u stays fp32-grade.  It is split into two fp16 terms u = u0 + u1 + (< 2^-22 u), u0 the
+//          round-toward-zero fp16 of u and u1 that of the exact remainder u - u0 (one mixed-precision
+//          multiply-add), and the fp16 MFMA is issued once per term against the fp16 copy of the
+//          bf16 weights: 22 significant bits per hidden activation, below the rounding of the fp32
+//          accumulation itself, instead of a slow fp32 matrix instruction.  Pairs of activations are
+//          converted by one packed instruction, which directly yields the B operand of GEMM2.
+//          (Hidden activations beyond 65504 would saturate the fp16 terms.)
 // Both GEMMs run transposed (see mfma.h): a lane owns one slice and, per 32-expert tile, 16 of
 // its logits; the other 16 sit in lane ^ 32.  Softmax and top-k therefore need only registers
 // and one cross-lane exchange per step.  A block keeps the whole router (<= 100 KiB packed) in
@@ -19,11 +22,8 @@ namespace slicemoe {
 constexpr int kRouteHr = 256;
 constexpr int kRouteHT = kRouteHr / 32;
 
-__device__ __forceinline__ uint32_t pack_hi16(float lo_elem, float hi_elem)
-{
-    // two bf16 truncations in one register: element 0 in the low half
-    return (__float_as_uint(lo_elem) >> 16) | (__float_as_uint(hi_elem) & 0xFFFF0000u);
-}
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 // One block per CU shares one LDS copy of the router: THREADS = 1024 (16 wavefronts, <= 128 VGPRs)
 // for the small shapes, 512 where the accumulators of two expert tiles or K = 128 need more registers.
@@ -94,6 +94,7 @@ __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) gacc[et][r] = 0.f;
 
+#pragma unroll 1
         for (int ht = 0; ht < HT; ++ht) {
             // GEMM1 with the bias preloaded
             f32x16 acc;
@@ -106,35 +107,30 @@ __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
                 acc = mfma_bf16(__builtin_bit_cast(bf16x8, w1s[(ht * KS + ks) * 64 + lane]), xb[ks], acc);
-            // ReLU and the exact three-term bf16 split
-            uint32_t t0[8], t1[8], t2[8];
+            // ReLU and the two-term fp16 split, two activations per conversion
+            uint32_t t0[8], t1[8];
 #pragma unroll
-            for (int r = 0; r < 16; r += 2) {
-                float u[2], r1[2], r2[2];
-#pragma unroll
-                for (int c = 0; c < 2; ++c) {
-                    u[c] = fmaxf(acc[r + c], 0.f);
-                    const float h0 = __uint_as_float(__float_as_uint(u[c]) & 0xFFFF0000u);
-                    r1[c] = u[c] - h0;
-                    const float h1 = __uint_as_float(__float_as_uint(r1[c]) & 0xFFFF0000u);
-                    r2[c] = r1[c] - h1;
-                }
-                t0[r >> 1] = pack_hi16(u[0], u[1]);
-                t1[r >> 1] = pack_hi16(r1[0], r1[1]);
-                t2[r >> 1] = pack_hi16(r2[0], r2[1]);
+            for (int i = 0; i < 8; ++i) {
+                // ReLU as one median-of-three (fmaxf would spend a second instruction on NaN canonicalisation)
+                const float u0 = __builtin_amdgcn_fmed3f(acc[2 * i], 0.f, __builtin_inff());
+                const float u1 = __builtin_amdgcn_fmed3f(acc[2 * i + 1], 0.f, __builtin_inff());
+                const h2 hi = __builtin_bit_cast(h2, __builtin_amdgcn_cvt_pkrtz(u0, u1));
+                float r0, r1;   // exact remainders u - (float)hi, one mixed-precision multiply-add each
+                asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel_hi:[1,0,0]" : "=v"(r0) : "v"(hi), "v"(u0));
+                asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(r1) : "v"(hi), "v"(u1));
+                t0[i] = __builtin_bit_cast(uint32_t, hi);
+                t1[i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(r0, r1));
             }
-            // GEMM2: three passes per K-step
+            // GEMM2: two passes per K-step, small term first
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
-                const bf16x8 u0 = __builtin_bit_cast(bf16x8, make_uint4(t0[4 * s], t0[4 * s + 1], t0[4 * s + 2], t0[4 * s + 3]));
-                const bf16x8 u1 = __builtin_bit_cast(bf16x8, make_uint4(t1[4 * s], t1[4 * s + 1], t1[4 * s + 2], t1[4 * s + 3]));
-                const bf16x8 u2 = __builtin_bit_cast(bf16x8, make_uint4(t2[4 * s], t2[4 * s + 1], t2[4 * s + 2], t2[4 * s + 3]));
+                const f16x8 u0 = __builtin_bit_cast(f16x8, make_uint4(t0[4 * s], t0[4 * s + 1], t0[4 * s + 2], t0[4 * s + 3]));
+                const f16x8 u1 = __builtin_bit_cast(f16x8, make_uint4(t1[4 * s], t1[4 * s + 1], t1[4 * s + 2], t1[4 * s + 3]));
 #pragma unroll
                 for (int et = 0; et < ET; ++et) {
-                    const bf16x8 a2 = __builtin_bit_cast(bf16x8, w2s[((et * HT + ht) * 2 + s) * 64 + lane]);
-                    gacc[et] = mfma_bf16(a2, u2, gacc[et]);
-                    gacc[et] = mfma_bf16(a2, u1, gacc[et]);
-                    gacc[et] = mfma_bf16(a2, u0, gacc[et]);
+                    const f16x8 a2 = __builtin_bit_cast(f16x8, w2s[((et * HT + ht) * 2 + s) * 64 + lane]);
+                    gacc[et] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a2, u1, gacc[et], 0, 0, 0);
+                    gacc[et] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a2, u0, gacc[et], 0, 0, 0);
                 }
             }
         }
