@@ -287,26 +287,14 @@ __global__ __launch_bounds__(kResThreads) void ffn_resident_kernel(
         const int nunits = (seg_end - r + kResU - 1) / kResU;   // this wavefront takes units wave, wave + 16, ...
 
         __syncthreads();  // everyone is done with the previous expert's weights
-        // stage the expert block: plain 16-byte loads, then LDS writes
-        const int pieces = (int)(e_stride / 16);
-        constexpr int kMaxPer = (HT * 8192 + HT * 64 + 512 + kResThreads * 16 - 1) / (kResThreads * 16);   // covers e_stride
-        uint4 wtmp[kMaxPer];
-#pragma unroll
-        for (int i = 0; i < kMaxPer; ++i) {
-            const int idx = tid + i * kResThreads;
-            wtmp[i] = ((const uint4 *)ew)[idx < pieces ? idx : 0];
-        }
         int q_c = wave;
         int row_c[1], a_c[1], row_n[1], a_n[1];
         float p_c[1], p_n[1];
-        unit_rows<1>(r + q_c * kResU, seg_end, q_c < nunits, j, perm, row_c, a_c);
+        unit_rows<1>(r + q_c * kResU, seg_end, q_c < nunits, j, perm, row_c, a_c);   // index load rides along with the weights
+        // stage the expert block (one linear copy: it is packed exactly as the kernel reads it)
+        stage_to_lds<kResThreads>(ew, lds, (int)(e_stride / 16), tid);
         RowUnit<DS, 1> cur, nxt;
         load_rows<DS, 1>(cur, a_c, row_c, x, pk, k, g, p_c);
-#pragma unroll
-        for (int i = 0; i < kMaxPer; ++i) {
-            const int idx = tid + i * kResThreads;
-            if (idx < pieces) ((uint4 *)lds)[idx] = wtmp[i];
-        }
         set_p<DS, 1>(cur, p_c);
         __syncthreads();
 
@@ -347,18 +335,6 @@ __global__ __launch_bounds__(kResThreads) void ffn_resident_kernel(
 // ------------------------------------------------------------------------------ streamed
 constexpr int kFfnThreads = 256;
 constexpr int kFfnWaves = kFfnThreads / 64;
-
-// Asynchronous copy of n16 16-byte pieces from global memory to LDS by the whole block: each
-// wavefront-level instruction moves 1 KiB (lane i -> dst + 16*i) without passing through registers.
-// The caller waits (vmcnt) and synchronises before reading.
-template <int THREADS>
-__device__ __forceinline__ void async_copy_to_lds(const uint4 *__restrict__ src, uint4 *dst, int n16, int tid)
-{
-    const int lane = tid & 63, wave = tid >> 6;
-    for (int c = wave; c < n16 / 64; c += THREADS / 64)
-        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)(src + c * 64 + lane),
-                                         (void __attribute__((address_space(3))) *)(dst + c * 64), 16, 0, 0);
-}
 
 template <int DS, int NSUB>
 __global__ __launch_bounds__(kFfnThreads) void ffn_streamed_kernel(
@@ -419,16 +395,14 @@ __global__ __launch_bounds__(kFfnThreads) void ffn_streamed_kernel(
         zero_acc<DS, NSUB>(yacc);
         for (int ch = 0; ch < nchunks; ++ch) {
             __syncthreads();  // everyone is done with the previous contents
-            async_copy_to_lds<kFfnThreads>((const uint4 *)(ew + off_w1) + (size_t)ch * hc * KS * 64, w1s, hc * KS * 64, tid);
-            async_copy_to_lds<kFfnThreads>((const uint4 *)(ew + off_w2) + (size_t)ch * hc * 2 * OT * 64, w2s,
-                                           hc * 2 * OT * 64, tid);
+            stage_to_lds<kFfnThreads>((const uint4 *)(ew + off_w1) + (size_t)ch * hc * KS * 64, w1s, hc * KS * 64, tid);
+            stage_to_lds<kFfnThreads>((const uint4 *)(ew + off_w2) + (size_t)ch * hc * 2 * OT * 64, w2s, hc * 2 * OT * 64, tid);
             if (new_expert && ch == 0) {
                 const uint4 *gb1 = (const uint4 *)(ew + off_b1);
                 const float *gb2 = (const float *)(ew + off_b2);
                 for (int i = tid; i < He / 8; i += kFfnThreads) b1s[i] = gb1[i];
                 for (int i = tid; i < DS; i += kFfnThreads) b2s[i] = gb2[i];
             }
-            __builtin_amdgcn_s_waitcnt(0);
             __syncthreads();
             for (int hl = 0; hl < hc; ++hl) {
                 f32x16 acc[NSUB];

@@ -30,7 +30,7 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 template <int DS, int ET, int THREADS>
 __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
     const bf16_t *__restrict__ x, long long Ns, int E, int k, const char *__restrict__ packed,
-    size_t off_w1, size_t off_w2, size_t off_b1, size_t off_b2, int32_t *__restrict__ idx,
+    size_t off_w1, size_t off_b1, size_t off_b2, int32_t *__restrict__ idx,
     float *__restrict__ pk)
 {
     constexpr int KS = DS / 16;
@@ -45,45 +45,43 @@ __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int j = lane & 31;
     const int g = lane >> 5;
 
-    {
-        // the whole router goes global -> LDS asynchronously (1 KiB per wavefront instruction)
-        const uint4 *g1 = (const uint4 *)(packed + off_w1);
-        const uint4 *g2 = (const uint4 *)(packed + off_w2);
-        const float *gb1 = (const float *)(packed + off_b1);
-        const float *gb2 = (const float *)(packed + off_b2);
-        for (int c = wave; c < HT * KS; c += kRouteThreads / 64)
-            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)(g1 + c * 64 + lane),
-                                             (void __attribute__((address_space(3))) *)(w1s + c * 64), 16, 0, 0);
-        for (int c = wave; c < ET * HT * 2; c += kRouteThreads / 64)
-            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)(g2 + c * 64 + lane),
-                                             (void __attribute__((address_space(3))) *)(w2s + c * 64), 16, 0, 0);
-        for (int i = tid; i < kRouteHr; i += kRouteThreads) b1s[i] = gb1[i];
-        for (int i = tid; i < ET * 32; i += kRouteThreads) b2s[i] = gb2[i];
-    }
-    // first tile's rows are requested before waiting for the weights
+    // first tile's rows are requested before the weights
     const long long ntiles = (Ns + 31) / 32;
     const long long tile_stride = (long long)gridDim.x * kRouteWaves;
     auto load_x = [&](long long tile, bf16x8 (&xb)[KS]) {
         const long long n = tile * 32 + j;
         const bool valid = tile < ntiles && n < Ns;
-        const uint4 *xp = (const uint4 *)(x + (valid ? n : 0) * DS);
+        const uint4 *xp = (const uint4 *)(x + (valid ? n : 0) * DS) + g;   // a lane without a slice reads slice 0
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (valid) v = xp[ks * 2 + g];
-            xb[ks] = __builtin_bit_cast(bf16x8, v);
-        }
+        for (int ks = 0; ks < KS; ++ks) xb[ks] = __builtin_bit_cast(bf16x8, xp[ks * 2]);
     };
     bf16x8 xb[KS];
     load_x((long long)blockIdx.x * kRouteWaves + wave, xb);
-    __builtin_amdgcn_s_waitcnt(0);
+    {
+        // the whole router (W1 and W2 fragments are adjacent in the packed buffer) goes global -> registers -> LDS
+        constexpr int kPieces = HT * KS * 64 + ET * HT * 2 * 64;
+        const float *gb1 = (const float *)(packed + off_b1);
+        const float *gb2 = (const float *)(packed + off_b2);
+        const float bv1 = gb1[tid < kRouteHr ? tid : 0];
+        const float bv2 = gb2[tid < ET * 32 ? tid : 0];
+        stage_to_lds<THREADS>(packed + off_w1, w1s, kPieces, tid);
+        if (tid < kRouteHr) b1s[tid] = bv1;
+        if (tid < ET * 32) b2s[tid] = bv2;
+    }
     __syncthreads();
 
     for (long long tile = (long long)blockIdx.x * kRouteWaves + wave; tile < ntiles; tile += tile_stride) {
+        {   // fewer tiles left -> lower priority, so the wavefronts of a block finish together
+            const long long left = (ntiles - 1 - tile) / tile_stride;
+            if (left >= 3) __builtin_amdgcn_s_setprio(3);
+            else if (left == 2) __builtin_amdgcn_s_setprio(2);
+            else if (left == 1) __builtin_amdgcn_s_setprio(1);
+            else __builtin_amdgcn_s_setprio(0);
+        }
         const long long n = tile * 32 + j;
         const bool valid = n < Ns;
         bf16x8 xn[KS];
@@ -203,8 +201,9 @@ static hipError_t run_route(const slicemoe_config &c, const void *h, const void 
     auto kern = route_mfma_kernel<DS, ET, THREADS>;
     hipError_t err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (err != hipSuccess) return err;
-    kern<<<(int)blocks, THREADS, lds, s>>>((const bf16_t *)h, Ns, c.E, c.k, (const char *)packed, L.r_w1,
-                                                 L.r_w2, L.r_b1, L.r_b2, idx, p);
+    if (L.r_w2 != L.r_w1 + (size_t)kRouteHT * KS * 64 * 16) return hipErrorInvalidValue;   // the kernel copies W1 | W2 as one run
+    kern<<<(int)blocks, THREADS, lds, s>>>((const bf16_t *)h, Ns, c.E, c.k, (const char *)packed, L.r_w1, L.r_b1, L.r_b2,
+                                           idx, p);
     return hipGetLastError();
 }
 
