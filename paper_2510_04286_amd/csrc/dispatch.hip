@@ -6,7 +6,8 @@
 //   1. histogram   block_counts[b][e] = # assignments of chunk b bound for expert e
 //   2. scan        per expert, exclusive prefix over chunks (in place) -> rank of a chunk's first
 //                  assignment inside its expert; totals -> counts_raw, counts, offsets
-//   3. scatter     stable rank of every assignment inside its chunk, final row, perm / inv
+//   3. scatter     stable rank of every assignment inside its chunk, final row, perm / inv;
+//                  one extra block computes the load statistics from the counts
 // Stability needs ranks in ascending a.  A block walks its chunk in rounds of 256 consecutive
 // ids; inside a wavefront the rank among equal experts comes from ballots (one per bit of the
 // expert id gives every lane the mask of lanes holding the same expert), across wavefronts and
@@ -86,35 +87,47 @@ __device__ __forceinline__ void load_stats_wave(int raw, int kept_e, bool have, 
 
 // One block of 1024 threads walks the [nblocks][E] table in tiles of kScanTile entries staged in
 // LDS (coalesced 16-byte loads and stores; the table is tiny, the kernel is latency-bound, so every
-// global access is issued in one batch).  Inside a tile, thread (seg, e) with e = tid % Epow2 owns a
-// contiguous run of chunks of expert e: it sums them, the per-segment sums are scanned serially per
-// expert (<= 1024/Epow2 segments) on top of the running total carried from the previous tiles, and
-// each thread rewrites its run as exclusive prefixes.
-constexpr int kScanTile = 8192;   // table entries per tile: 32 KiB of LDS
+// global access is issued in one batch and every scan is a wavefront shuffle scan).  Inside a tile,
+// thread (seg, e) with e = tid % Epow2 owns a contiguous run of chunks of expert e and sums it; the
+// nseg <= 64 segment sums of an expert are then re-read segment-fastest, so that they sit in
+// consecutive lanes, and scanned with shuffles on top of the running total carried from the previous
+// tiles; finally each thread rewrites its run as exclusive prefixes.
+constexpr int kScanTileMax = 32768;   // table entries per tile at most: 128 KiB of LDS (the headline table is 16384)
+
+__device__ __forceinline__ int group_inclusive_scan(int v, int pos, int width)
+{
+    for (int o = 1; o < width; o <<= 1) {
+        const int t = __shfl_up(v, o);
+        if (pos >= o) v += t;
+    }
+    return v;
+}
 
 __global__ __launch_bounds__(1024) void dispatch_scan_kernel(
     int32_t *__restrict__ block_counts, int nblocks, int E, int Epow2, long long capacity,
-    int32_t *__restrict__ counts_raw, int32_t *__restrict__ counts, int32_t *__restrict__ offsets,
-    float *__restrict__ stats /* may be null */)
+    int32_t *__restrict__ counts_raw, int32_t *__restrict__ counts, int32_t *__restrict__ offsets, int tile_entries)
 {
-    __shared__ __align__(16) int tile[kScanTile];
+    extern __shared__ __align__(16) int tile[];   // [tile_entries]
     __shared__ int seg_sum[1024];
     __shared__ int carry[64];
-    __shared__ int kept[64];
     const int tid = threadIdx.x;
+    const int nseg = min(64, 1024 / Epow2);       // power of two: a segment group never straddles a wavefront
+    // tile passes: expert fastest (consecutive lanes touch consecutive LDS words)
     const int e = tid % Epow2;
     const int seg = tid / Epow2;
-    const int nseg = 1024 / Epow2;
-    const int chunks_per_tile = kScanTile / E;          // whole chunks only
-    const long long total_entries = (long long)nblocks * E;
+    const bool active = e < E && seg < nseg;
+    // scan of the segment sums: segment fastest (an expert's sums sit in consecutive lanes)
+    const int e2 = tid / nseg;
+    const int seg2 = tid % nseg;
+    const bool active2 = e2 < E;
+    const int chunks_per_tile = tile_entries / E;    // whole chunks only
     if (tid < 64) carry[tid] = 0;
 
     for (int c0 = 0; c0 < nblocks; c0 += chunks_per_tile) {
         const int nc = min(chunks_per_tile, nblocks - c0);
         const long long first = (long long)c0 * E;            // entry index of the tile start
         const int n_entries = nc * E;
-        // stage: 16-byte pieces where the tile start is 16-byte aligned (E % 4 == 0 or first tile), else scalars
-        const bool vec = ((first & 3) == 0);
+        const bool vec = ((first & 3) == 0);                  // 16-byte pieces need an aligned tile start
         __syncthreads();   // previous tile fully written back, carry visible
         if (vec) {
             for (int i = tid * 4; i < n_entries; i += 1024 * 4) {
@@ -129,22 +142,21 @@ __global__ __launch_bounds__(1024) void dispatch_scan_kernel(
         const int b0 = seg * per;
         const int b1 = min(nc, b0 + per);
         int s = 0;
-        if (e < E)
+        if (active)
             for (int b = b0; b < b1; ++b) s += tile[b * E + e];
-        seg_sum[tid] = s;
+        if (active) seg_sum[seg * Epow2 + e] = s;
         __syncthreads();
-        if (seg == 0 && e < E) {
-            int run = carry[e];
-            for (int g = 0; g < nseg; ++g) {
-                const int t = seg_sum[g * Epow2 + e];
-                seg_sum[g * Epow2 + e] = run;
-                run += t;
-            }
-            carry[e] = run;
+        {
+            const int v = active2 ? seg_sum[seg2 * Epow2 + e2] : 0;
+            const int incl = group_inclusive_scan(v, seg2, nseg);
+            const int base = active2 ? carry[e2] : 0;
+            __syncthreads();                                   // everyone has read seg_sum and carry
+            if (active2) seg_sum[seg2 * Epow2 + e2] = base + incl - v;   // exclusive prefix of the segment
+            if (active2 && seg2 == nseg - 1) carry[e2] = base + incl;
         }
         __syncthreads();
-        if (e < E) {
-            int run = seg_sum[tid];
+        if (active) {
+            int run = seg_sum[seg * Epow2 + e];
             for (int b = b0; b < b1; ++b) {
                 const int t = tile[b * E + e];
                 tile[b * E + e] = run;
@@ -161,38 +173,33 @@ __global__ __launch_bounds__(1024) void dispatch_scan_kernel(
             for (int i = tid; i < n_entries; i += 1024) block_counts[first + i] = tile[i];
         }
     }
-    (void)total_entries;
     __syncthreads();
-    if (tid < E) {
-        const int run = carry[tid];
-        counts_raw[tid] = run;
-        const int c = (capacity >= 0 && run > capacity) ? (int)capacity : run;
-        counts[tid] = c;
-        kept[tid] = c;
-    }
-    __syncthreads();
-    if (tid == 0) {
-        int run = 0;
-        for (int x = 0; x < E; ++x) {
-            offsets[x] = run;
-            run += kept[x];
+    if (tid < 64) {   // one wavefront: lane x owns expert x
+        const int raw = tid < E ? carry[tid] : 0;
+        const int c = (capacity >= 0 && raw > capacity) ? (int)capacity : raw;
+        const int incl = group_inclusive_scan(c, tid, 64);
+        if (tid < E) {
+            counts_raw[tid] = raw;
+            counts[tid] = c;
+            offsets[tid] = incl - c;
         }
-        offsets[E] = run;
-    }
-    if (stats && tid >= 64 && tid < 128) {  // second wavefront: the first one is busy with offsets
-        const int x = tid - 64;
-        load_stats_wave(x < E ? carry[x] : 0, x < E ? kept[x] : 0, x < E, E, stats);
+        if (tid == E - 1) offsets[E] = incl;
     }
 }
 
 __global__ __launch_bounds__(kDispThreads) void dispatch_scatter_kernel(
     const int32_t *__restrict__ idx, int Na, int E, int nbits, long long capacity,
     const int32_t *__restrict__ block_base, const int32_t *__restrict__ offsets,
-    int32_t *__restrict__ perm, int32_t *__restrict__ inv)
+    int32_t *__restrict__ perm, int32_t *__restrict__ inv, int nchunks, const int32_t *__restrict__ counts_raw,
+    const int32_t *__restrict__ counts, float *__restrict__ stats /* may be null */)
 {
     constexpr int kWaves = kDispThreads / 64;
     __shared__ int wcnt[kDispItems][kWaves][64];
     const int tid = threadIdx.x;
+    if ((int)blockIdx.x == nchunks) {   // one extra block: the load statistics, off everyone's critical path
+        if (stats && tid < 64) load_stats_wave(tid < E ? counts_raw[tid] : 0, tid < E ? counts[tid] : 0, tid < E, E, stats);
+        return;
+    }
     const int lane = tid & 63;
     const int wave = tid >> 6;
     for (int i = tid; i < kDispItems * kWaves * 64; i += kDispThreads) (&wcnt[0][0][0])[i] = 0;
@@ -253,11 +260,21 @@ hipError_t launch_dispatch(const slicemoe_config &c, const int32_t *idx, int32_t
     const int Epow2 = 1 << nbits;
     const long long cap = slicemoe_capacity(&c);
     if (nblocks > 0) dispatch_hist_kernel<<<nblocks, kDispThreads, 0, s>>>(idx, (int)Na, c.E, nbits, block_counts);
-    dispatch_scan_kernel<<<1, 1024, 0, s>>>(block_counts, nblocks, c.E, Epow2, cap, counts_raw, counts,
-                                           offsets, stats);
-    if (nblocks > 0)
-        dispatch_scatter_kernel<<<nblocks, kDispThreads, 0, s>>>(idx, (int)Na, c.E, nbits, cap, block_counts,
-                                                                offsets, perm, inv);
+    {
+        long long want = (long long)nblocks * c.E;
+        int tile_entries = (int)(want < 1024 ? 1024 : (want > kScanTileMax ? kScanTileMax : (want + 3) / 4 * 4));
+        const int lds_cap = (max_lds_per_block() - 8 * 1024) / 4;
+        if (tile_entries > lds_cap) tile_entries = lds_cap / 4 * 4;
+        if (tile_entries < c.E) return hipErrorInvalidValue;
+        hipError_t err = hipFuncSetAttribute((const void *)dispatch_scan_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             tile_entries * 4);
+        if (err != hipSuccess) return err;
+        dispatch_scan_kernel<<<1, 1024, (size_t)tile_entries * 4, s>>>(block_counts, nblocks, c.E, Epow2, cap, counts_raw,
+                                                                     counts, offsets, tile_entries);
+    }
+    if (nblocks > 0 || stats)
+        dispatch_scatter_kernel<<<nblocks + (stats ? 1 : 0), kDispThreads, 0, s>>>(
+            idx, (int)Na, c.E, nbits, cap, block_counts, offsets, perm, inv, nblocks, counts_raw, counts, stats);
     return hipGetLastError();
 }
 

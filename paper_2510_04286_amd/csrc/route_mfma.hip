@@ -35,7 +35,6 @@ __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
 {
     constexpr int KS = DS / 16;
     constexpr int HT = kRouteHT;
-    constexpr int kRouteThreads = THREADS;
     constexpr int kRouteWaves = THREADS / 64;
     extern __shared__ __align__(16) char lds[];
     uint4 *w1s = (uint4 *)lds;                         // [HT][KS][64]
