@@ -145,12 +145,21 @@ def main():
             s["hbm_frac"] = round(bytes_[n] / t / 1e9 / PEAK_HBM_GBS, 4)
         stages[n] = s
 
+    # shader clock sustained under matrix + vector load (the peaks are quoted at 2.4 GHz)
+    probe = torch.zeros(2 * 1024, dtype=torch.int64, device=dev)   # 4 blocks of 4 wavefronts per CU, as the expert kernel
+    B.slicemoe_probe_clock(probe, 1024, 10000)
+    torch.cuda.synchronize()
+    pc = probe.view(-1, 2).cpu().numpy().astype(np.float64)
+    clock_ghz = float(pc[:, 0].sum() / pc[:, 1].sum() * 0.1)
+
     t_ffn = stage_ms["expert_ffn"] * 1e-3
     achieved = flops["expert_ffn"] / t_ffn / 1e12
     roofline = {"kernel": "ffn_resident_kernel" if shape.ds == 64 else "ffn_streamed_kernel", "bound": "mfma", "achieved": round(achieved, 2),
                 "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_BF16_TFLOPS, 4),
                 "traffic": FFN_TRAFFIC_BYTES.get(args.workload), "launch_us": round(t_ffn * 1e6, 2),
-                "flops_per_launch": flops["expert_ffn"], "hbm_bytes_algorithmic": bytes_["expert_ffn"]}
+                "flops_per_launch": flops["expert_ffn"], "hbm_bytes_algorithmic": bytes_["expert_ffn"],
+                "sustained_clock_ghz": round(clock_ghz, 3),
+                "frac_of_peak_at_sustained_clock": round(achieved / (PEAK_MFMA_BF16_TFLOPS * clock_ghz / 2.4), 4)}
 
     cpu = None
     if not args.no_cpu_baseline:

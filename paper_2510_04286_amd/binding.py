@@ -28,7 +28,7 @@ EXPORTS = [
     "slicemoe_status_string", "slicemoe_uses_mfma", "slicemoe_capacity", "slicemoe_workspace_bytes",
     "slicemoe_dispatch_workspace_bytes", "slicemoe_get_workspace_layout", "slicemoe_packed_bytes",
     "slicemoe_pack_weights", "slicemoe_route", "slicemoe_dispatch", "slicemoe_expert_ffn",
-    "slicemoe_combine", "slicemoe_load_stats", "slicemoe_forward",
+    "slicemoe_combine", "slicemoe_load_stats", "slicemoe_forward", "slicemoe_probe_clock",
 ]
 
 
@@ -89,6 +89,8 @@ def lib() -> ctypes.CDLL:
         L.slicemoe_load_stats.argtypes = [cfgp, vp, vp, vp, vp]
         L.slicemoe_forward.restype = ctypes.c_int
         L.slicemoe_forward.argtypes = [cfgp, vp, wp, vp, vp, st, vp]
+        L.slicemoe_probe_clock.restype = ctypes.c_int
+        L.slicemoe_probe_clock.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, vp]
         _lib = L
     return _lib
 
@@ -249,6 +251,11 @@ def slicemoe_forward(cfg, h, w, h_out, workspace, stream=None):
     _check(lib().slicemoe_forward(ctypes.byref(cfg), _ptr(h, _tdtype(cfg), cfg.T * cfg.d, "h"), ctypes.byref(ws),
                                   _ptr(h_out, _tdtype(cfg), cfg.T * cfg.d, "h_out"), wsp, wsb, _stream(stream)),
            "slicemoe_forward")
+
+
+def slicemoe_probe_clock(cycles_and_ticks, nblocks: int, iters: int, stream=None):
+    _check(lib().slicemoe_probe_clock(_ptr(cycles_and_ticks, torch.int64, 2 * nblocks, "cycles_and_ticks"), nblocks, iters,
+                                      _stream(stream)), "slicemoe_probe_clock")
 
 
 # ------------------------------------------------------------------ plumbing helpers (device memory only)

@@ -327,4 +327,12 @@ slicemoe_status slicemoe_forward(const slicemoe_config *cfg, const void *h, cons
     return e == hipSuccess ? SLICEMOE_OK : SLICEMOE_ERR_HIP;
 }
 
+slicemoe_status slicemoe_probe_clock(uint64_t *cycles_and_ticks, int32_t nblocks, int32_t iters, slicemoe_stream_t stream)
+{
+    if (!cycles_and_ticks || nblocks < 1 || nblocks > 65536 || iters < 1 || iters > (1 << 24)) return SLICEMOE_ERR_INVALID_ARG;
+    return launch_clock_probe((unsigned long long *)cycles_and_ticks, nblocks, iters, (hipStream_t)stream) == hipSuccess
+               ? SLICEMOE_OK
+               : SLICEMOE_ERR_HIP;
+}
+
 }  // extern "C"

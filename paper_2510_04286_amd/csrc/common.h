@@ -99,6 +99,7 @@ hipError_t launch_combine(const slicemoe_config &c, const void *y, const int32_t
 hipError_t launch_load_stats(const slicemoe_config &c, const int32_t *counts_raw, const int32_t *counts,
                              float *stats, hipStream_t s);
 hipError_t launch_pack(const slicemoe_config &c, const slicemoe_weights &w, void *packed, hipStream_t s);
+hipError_t launch_clock_probe(unsigned long long *out, int nblocks, int iters, hipStream_t s);
 
 int num_compute_units();
 int max_lds_per_block();  // bytes of LDS one workgroup may use on the current device
