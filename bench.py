@@ -24,7 +24,7 @@ PEAK_MFMA_BF16_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0           # MI355X HBM3E
 # HBM bytes per launch of the expert FFN kernel on the headline workload, from rocprofv3 --pmc
 # (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size); None until measured.
-FFN_TRAFFIC_BYTES = {"headline": 117571283}
+FFN_TRAFFIC_BYTES = {"headline": 115647560}
 
 
 def main():
@@ -147,7 +147,7 @@ def main():
 
     # shader clock sustained under matrix + vector load (the peaks are quoted at 2.4 GHz)
     probe = torch.zeros(2 * 1024, dtype=torch.int64, device=dev)   # 4 blocks of 4 wavefronts per CU, as the expert kernel
-    B.slicemoe_probe_clock(probe, 1024, 10000)
+    B.slicemoe_probe_clock(probe, 1024, 2000)
     torch.cuda.synchronize()
     pc = probe.view(-1, 2).cpu().numpy().astype(np.float64)
     clock_ghz = float(pc[:, 0].sum() / pc[:, 1].sum() * 0.1)
