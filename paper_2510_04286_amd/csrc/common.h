@@ -37,25 +37,28 @@ template <> struct Storage<bf16_t> {
 __host__ __device__ __forceinline__ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // Block-wide copy of n_pieces 16-byte pieces from global memory to LDS through registers, in rounds of
-// four pieces per thread: the loads of a round are all in flight before its first LDS write, so a round
-// costs one memory round trip.  (The direct global->LDS path moves only 16 bytes per cycle and CU.)
+// ROUND (4 or 8) pieces per thread: the loads of a round are all in flight before its first LDS write, so
+// a round costs one memory round trip.  (The direct global->LDS path moves only 16 bytes per cycle and CU.)
 // Callers synchronise before reading the copy.
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-template <int THREADS>
+template <int THREADS, int ROUND = 4>
 __device__ __forceinline__ void stage_to_lds(const void *__restrict__ src, void *dst, int n_pieces, int tid)
 {
+    static_assert(ROUND == 4 || ROUND == 8, "rounds of 4 or 8 pieces");
     const u32x4 *g = (const u32x4 *)src;
     u32x4 *l = (u32x4 *)dst;
-    for (int base = 0; base < n_pieces; base += 4 * THREADS) {
-        u32x4 t[4];
+    for (int base = 0; base < n_pieces; base += ROUND * THREADS) {
+        u32x4 t[ROUND];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < ROUND; ++i) {
             const int idx = base + tid + i * THREADS;
             t[i] = g[idx < n_pieces ? idx : 0];
         }
-        asm volatile("" : "+v"(t[0]), "+v"(t[1]), "+v"(t[2]), "+v"(t[3]));   // all four requested before any is used
+        // every piece of the round is requested before any is used
+        if constexpr (ROUND == 4) asm volatile("" : "+v"(t[0]), "+v"(t[1]), "+v"(t[2]), "+v"(t[3]));
+        else asm volatile("" : "+v"(t[0]), "+v"(t[1]), "+v"(t[2]), "+v"(t[3]), "+v"(t[4]), "+v"(t[5]), "+v"(t[6]), "+v"(t[7]));
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < ROUND; ++i) {
             const int idx = base + tid + i * THREADS;
             if (idx < n_pieces) l[idx] = t[i];
         }

@@ -333,7 +333,7 @@ __global__ __launch_bounds__(kResThreads) void ffn_resident_kernel(
 }
 
 // ------------------------------------------------------------------------------ streamed
-constexpr int kFfnThreads = 256;
+constexpr int kFfnThreads = 512;   // two wavefronts per SIMD: one's matrix work overlaps the other's vector work
 constexpr int kFfnWaves = kFfnThreads / 64;
 
 template <int DS, int NSUB>
@@ -345,6 +345,7 @@ __global__ __launch_bounds__(kFfnThreads) void ffn_streamed_kernel(
     constexpr int KS = DS / 16;
     constexpr int OT = DS / 32;
     constexpr int TM = kFfnWaves * NSUB * 32;
+    constexpr int kRound = DS <= 64 ? 8 : 4;   // pieces in flight per thread while staging (register budget)
     const int HT = He / 32;
     const int nchunks = HT / hc;
 
@@ -395,8 +396,8 @@ __global__ __launch_bounds__(kFfnThreads) void ffn_streamed_kernel(
         zero_acc<DS, NSUB>(yacc);
         for (int ch = 0; ch < nchunks; ++ch) {
             __syncthreads();  // everyone is done with the previous contents
-            stage_to_lds<kFfnThreads>((const uint4 *)(ew + off_w1) + (size_t)ch * hc * KS * 64, w1s, hc * KS * 64, tid);
-            stage_to_lds<kFfnThreads>((const uint4 *)(ew + off_w2) + (size_t)ch * hc * 2 * OT * 64, w2s, hc * 2 * OT * 64, tid);
+            stage_to_lds<kFfnThreads, kRound>((const uint4 *)(ew + off_w1) + (size_t)ch * hc * KS * 64, w1s, hc * KS * 64, tid);
+            stage_to_lds<kFfnThreads, kRound>((const uint4 *)(ew + off_w2) + (size_t)ch * hc * 2 * OT * 64, w2s, hc * 2 * OT * 64, tid);
             if (new_expert && ch == 0) {
                 const uint4 *gb1 = (const uint4 *)(ew + off_b1);
                 const float *gb2 = (const float *)(ew + off_b2);
