@@ -194,6 +194,30 @@ def test_expert_ffn_empty_experts_and_ragged_tiles(B):
     assert err <= TOL_BF16, err
 
 
+@pytest.mark.parametrize("name,T", [("headline", 512), ("large", 128)])
+def test_expert_ffn_large_preactivations(B, name, T):
+    """Gates of 1 and first-layer weights scaled up: |z| reaches past 6, so the polynomial's whole fitted range and
+    the saturation beyond it are exercised on the matrix-core kernels (resident and streamed)."""
+    import torch
+    shape, h, w = make_inputs(wl.CONFIGS[name], T)
+    w = dict(w)
+    w["W1"] = (w["W1"] * 2.0).astype(w["W1"].dtype)   # a power of two: still exact bf16 values
+    x = h.reshape(-1, shape.ds)
+    r = oracle.route(x, w["Wr1"], w["br1"], w["Wr2"], w["br2"], shape.k)
+    pk = np.ones_like(r["pk"])
+    d = oracle.dispatch(r["idx"], shape.E, -1)
+    ref = oracle.expert_rows(x, r["idx"], pk, d["perm"], shape.Na, w["W1"], w["b1"], w["W2"], w["b2"])
+    cfg = B.config_of(shape)
+    assert B.slicemoe_uses_mfma(cfg) == 1
+    wd = B.pack(cfg, B.weights_to_device(w, shape.dtype))
+    y = torch.zeros((shape.Na, shape.ds), dtype=B.y_dtype(cfg), device="cuda:0")
+    B.slicemoe_expert_ffn(cfg, B.to_device(h, shape.dtype), dev(pk.astype(np.float32).reshape(-1)), dev(d["offsets"]),
+                          dev(d["perm"]), wd, y)
+    err = np.abs(y.float().cpu().numpy() - ref).max() / rms(ref)
+    print(f"\n[ffn large-z {name}] max|err|/rms={err:.3e}")
+    assert err <= TOL_BF16, err
+
+
 # ------------------------------------------------------------------ router
 ROUTE_CASES = [("tiny", 512, 0), ("lm", 4096, 0), ("headline", 4096, 0), ("skewed", 4096, 0), ("large", 1024, 0),
                ("lm", 512, 1)]
