@@ -108,9 +108,11 @@ __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
             uint32_t t0[8], t1[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                // ReLU as one median-of-three (fmaxf would spend a second instruction on NaN canonicalisation)
-                const float u0 = __builtin_amdgcn_fmed3f(acc[2 * i], 0.f, __builtin_inff());
-                const float u1 = __builtin_amdgcn_fmed3f(acc[2 * i + 1], 0.f, __builtin_inff());
+                // ReLU as one signed-integer max on the bit patterns (negative floats are negative integers); a float
+                // max would spend a second instruction on NaN canonicalisation
+                const float a0 = acc[2 * i], a1 = acc[2 * i + 1];
+                const int b0 = __float_as_int(a0), b1 = __float_as_int(a1);
+                const float u0 = __int_as_float(b0 > 0 ? b0 : 0), u1 = __int_as_float(b1 > 0 ? b1 : 0);
                 const h2 hi = __builtin_bit_cast(h2, __builtin_amdgcn_cvt_pkrtz(u0, u1));
                 float r0, r1;   // exact remainders u - (float)hi, one mixed-precision multiply-add each
                 asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel_hi:[1,0,0]" : "=v"(r0) : "v"(hi), "v"(u0));
