@@ -85,11 +85,15 @@ __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
         const bool valid = n < Ns;
         bf16x8 xn[KS];
         load_x(tile + tile_stride, xn);  // next tile, consumed after this one
-        f32x16 gacc[ET];
+        f32x16 gacc[ET];   // logit accumulators start from the second-layer bias
 #pragma unroll
         for (int et = 0; et < ET; ++et)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) gacc[et][r] = 0.f;
+            for (int q = 0; q < 4; ++q) {
+                const f32x4 b = *(const f32x4 *)(b2s + et * 32 + 8 * q + 4 * g);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) gacc[et][4 * q + c] = b[c];
+            }
 
 #pragma unroll 1
         for (int ht = 0; ht < HT; ++ht) {
@@ -139,18 +143,24 @@ __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
 #pragma unroll
         for (int et = 0; et < ET; ++et)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int e = et * 32 + acc_feature(r, g);
-                const float val = gacc[et][r] + b2s[e];
-                v[et * 16 + r] = e < E ? val : -INFINITY;
-            }
+            for (int r = 0; r < 16; ++r) v[et * 16 + r] = gacc[et][r];
+        if (E != ET * 32) {   // padded experts never win
+#pragma unroll
+            for (int et = 0; et < ET; ++et)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (et * 32 + acc_feature(r, g) >= E) v[et * 16 + r] = -INFINITY;
+        }
         float m = v[0];
 #pragma unroll
         for (int i = 1; i < ET * 16; ++i) m = fmaxf(m, v[i]);
         m = fmaxf(m, __shfl_xor(m, 32));
+        // softmax denominator: exp(v - m) = exp2(v * log2(e) - m * log2(e)), one multiply-add and one exp2 per logit
+        constexpr float kLog2e = 1.4426950408889634f;
+        const float nm = -m * kLog2e;
         float den = 0.f;
 #pragma unroll
-        for (int i = 0; i < ET * 16; ++i) den += __expf(v[i] - m);
+        for (int i = 0; i < ET * 16; ++i) den += __builtin_amdgcn_exp2f(fmaf(v[i], kLog2e, nm));
         den += __shfl_xor(den, 32);
         const float rden = 1.0f / den;
 
@@ -178,7 +188,7 @@ __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
             }
             if (valid && g == 0) {
                 idx[n * k + jj] = be;
-                pk[n * k + jj] = __expf(bv - m) * rden;
+                pk[n * k + jj] = __builtin_amdgcn_exp2f(fmaf(bv, kLog2e, nm)) * rden;
             }
         }
 #pragma unroll
