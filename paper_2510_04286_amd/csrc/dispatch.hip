@@ -8,6 +8,8 @@
 //                  assignment inside its expert; totals -> counts_raw, counts, offsets
 //   3. scatter     stable rank of every assignment inside its chunk, final row, perm / inv;
 //                  one extra block computes the load statistics from the counts
+// When the table of step 1 is small (the headline has 512 chunks x 32 experts) step 2 is folded into
+// step 3: every scatter block sums the table itself, which is cheaper than a latency-bound launch.
 // Stability needs ranks in ascending a.  A block walks its chunk in rounds of 256 consecutive
 // ids; inside a wavefront the rank among equal experts comes from ballots (one per bit of the
 // expert id gives every lane the mask of lanes holding the same expert), across wavefronts and
@@ -187,18 +189,74 @@ __global__ __launch_bounds__(1024) void dispatch_scan_kernel(
     }
 }
 
+// FUSED = false: `table` holds the exclusive per-expert prefixes written by dispatch_scan_kernel and the
+// per-expert offsets come from `offsets`.
+// FUSED = true (small tables, E a power of two >= 4): there is no scan kernel.  `table` holds the raw
+// per-chunk counts; every block sums the whole table (coalesced 16-byte loads, all in flight at once) into
+// the per-expert totals and into the prefix of its own chunk, derives counts and offsets itself, and block 0
+// writes counts_raw / counts / offsets for the stages that follow.  Reading nchunks * E ints per block is
+// cheaper than a separate latency-bound launch as long as the table is small.
+template <bool FUSED>
 __global__ __launch_bounds__(kDispThreads) void dispatch_scatter_kernel(
     const int32_t *__restrict__ idx, int Na, int E, int nbits, long long capacity,
-    const int32_t *__restrict__ block_base, const int32_t *__restrict__ offsets,
-    int32_t *__restrict__ perm, int32_t *__restrict__ inv, int nchunks, const int32_t *__restrict__ counts_raw,
-    const int32_t *__restrict__ counts, float *__restrict__ stats /* may be null */)
+    const int32_t *__restrict__ table, int32_t *__restrict__ offsets,
+    int32_t *__restrict__ perm, int32_t *__restrict__ inv, int nchunks, int32_t *__restrict__ counts_raw,
+    int32_t *__restrict__ counts, float *__restrict__ stats /* may be null */)
 {
     constexpr int kWaves = kDispThreads / 64;
     __shared__ int wcnt[kDispItems][kWaves][64];
+    __shared__ int s_pre[64];      // FUSED: rank of this chunk's first assignment inside each expert
+    __shared__ int s_off[65];      // FUSED: per-expert offsets
     const int tid = threadIdx.x;
-    if ((int)blockIdx.x == nchunks) {   // one extra block: the load statistics, off everyone's critical path
-        if (stats && tid < 64) load_stats_wave(tid < E ? counts_raw[tid] : 0, tid < E ? counts[tid] : 0, tid < E, E, stats);
-        return;
+    const bool stats_block = (int)blockIdx.x == nchunks;   // one extra block: the load statistics, off everyone's critical path
+    if constexpr (FUSED) {
+        __shared__ int part[2][kDispThreads][4];
+        const int n_entries = nchunks * E;              // a multiple of 4, and 4 * kDispThreads is a multiple of E:
+        int tot[4] = {0, 0, 0, 0}, pre[4] = {0, 0, 0, 0};   // a thread always sees the same four experts
+        for (int flat = tid * 4; flat < n_entries; flat += kDispThreads * 4) {
+            const int4 v = *(const int4 *)(table + flat);
+            const bool before = (flat >> nbits) < (int)blockIdx.x;   // chunk index of this piece
+            tot[0] += v.x; tot[1] += v.y; tot[2] += v.z; tot[3] += v.w;
+            if (before) { pre[0] += v.x; pre[1] += v.y; pre[2] += v.z; pre[3] += v.w; }
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            part[0][tid][q] = tot[q];
+            part[1][tid][q] = pre[q];
+        }
+        __syncthreads();
+        int raw = 0, mine = 0;
+        if (tid < E) {   // the threads t with (4 t) % E == 4 (tid / 4) hold expert tid in component tid % 4
+            const int step = E / 4;
+            for (int t = tid / 4; t < kDispThreads; t += step) {
+                raw += part[0][t][tid & 3];
+                mine += part[1][t][tid & 3];
+            }
+        }
+        if (tid < 64) {   // one wavefront: lane x owns expert x
+            const int c = (capacity >= 0 && raw > capacity) ? (int)capacity : raw;
+            const int incl = group_inclusive_scan(tid < E ? c : 0, tid, 64);
+            if (tid < E) {
+                s_pre[tid] = mine;
+                s_off[tid] = incl - c;
+                if (blockIdx.x == 0) {
+                    counts_raw[tid] = raw;
+                    counts[tid] = c;
+                    offsets[tid] = incl - c;
+                }
+            }
+            if (tid == E - 1) {
+                s_off[E] = incl;
+                if (blockIdx.x == 0) offsets[E] = incl;
+            }
+            if (stats_block && stats) load_stats_wave(raw, c, tid < E, E, stats);
+        }
+        if (stats_block) return;
+    } else {
+        if (stats_block) {
+            if (stats && tid < 64) load_stats_wave(tid < E ? counts_raw[tid] : 0, tid < E ? counts[tid] : 0, tid < E, E, stats);
+            return;
+        }
     }
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -224,7 +282,7 @@ __global__ __launch_bounds__(kDispThreads) void dispatch_scatter_kernel(
     }
     __syncthreads();
     if (tid < E) {
-        int run = block_base[(size_t)blockIdx.x * E + tid];
+        int run = FUSED ? s_pre[tid] : table[(size_t)blockIdx.x * E + tid];
         for (int i = 0; i < kDispItems; ++i)
             for (int w = 0; w < kWaves; ++w) {
                 const int t = wcnt[i][w][tid];
@@ -240,7 +298,7 @@ __global__ __launch_bounds__(kDispThreads) void dispatch_scatter_kernel(
         const int a = base + i * kDispThreads + tid;
         const int rank = wcnt[i][wave][e] + rk[i];
         if (capacity < 0 || rank < capacity) {
-            const int row = offsets[e] + rank;
+            const int row = (FUSED ? s_off[e] : offsets[e]) + rank;
             perm[row] = a;
             inv[a] = row;
         } else {
@@ -260,6 +318,13 @@ hipError_t launch_dispatch(const slicemoe_config &c, const int32_t *idx, int32_t
     const int Epow2 = 1 << nbits;
     const long long cap = slicemoe_capacity(&c);
     if (nblocks > 0) dispatch_hist_kernel<<<nblocks, kDispThreads, 0, s>>>(idx, (int)Na, c.E, nbits, block_counts);
+    // small table and a power-of-two expert count: every scatter block scans the table itself
+    const bool fused = nblocks > 0 && c.E >= 4 && Epow2 == c.E && (long long)nblocks * c.E <= 32768;
+    if (fused) {
+        dispatch_scatter_kernel<true><<<nblocks + (stats ? 1 : 0), kDispThreads, 0, s>>>(
+            idx, (int)Na, c.E, nbits, cap, block_counts, offsets, perm, inv, nblocks, counts_raw, counts, stats);
+        return hipGetLastError();
+    }
     {
         long long want = (long long)nblocks * c.E;
         int tile_entries = (int)(want < 1024 ? 1024 : (want > kScanTileMax ? kScanTileMax : (want + 3) / 4 * 4));
@@ -273,7 +338,7 @@ hipError_t launch_dispatch(const slicemoe_config &c, const int32_t *idx, int32_t
                                                                      counts, offsets, tile_entries);
     }
     if (nblocks > 0 || stats)
-        dispatch_scatter_kernel<<<nblocks + (stats ? 1 : 0), kDispThreads, 0, s>>>(
+        dispatch_scatter_kernel<false><<<nblocks + (stats ? 1 : 0), kDispThreads, 0, s>>>(
             idx, (int)Na, c.E, nbits, cap, block_counts, offsets, perm, inv, nblocks, counts_raw, counts, stats);
     return hipGetLastError();
 }
