@@ -463,7 +463,7 @@ static hipError_t run_resident(const slicemoe_config &c, const PackedLayout &L, 
 {
     const long long Na = (long long)c.T * c.S * c.k;
     const long long max_units = (Na + kResU - 1) / kResU;
-    long long blocks = (max_units + kResWaves - 1) / kResWaves;
+    long long blocks = max_units;   // small inputs: spread the units over all CUs rather than fill few blocks
     if (blocks > num_compute_units()) blocks = num_compute_units();
     auto kern = ffn_resident_kernel<HT>;
     hipError_t err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds);

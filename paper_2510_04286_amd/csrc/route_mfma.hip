@@ -59,7 +59,7 @@ __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
         for (int ks = 0; ks < KS; ++ks) xb[ks] = __builtin_bit_cast(bf16x8, xp[ks * 2]);
     };
     bf16x8 xb[KS];
-    load_x((long long)blockIdx.x * kRouteWaves + wave, xb);
+    load_x((long long)wave * gridDim.x + blockIdx.x, xb);   // tiles go round the blocks first: small inputs still use every CU
     {
         // the whole router (W1 and W2 fragments are adjacent in the packed buffer) goes global -> registers -> LDS
         constexpr int kPieces = HT * KS * 64 + ET * HT * 2 * 64;
@@ -73,7 +73,7 @@ __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
     }
     __syncthreads();
 
-    for (long long tile = (long long)blockIdx.x * kRouteWaves + wave; tile < ntiles; tile += tile_stride) {
+    for (long long tile = (long long)wave * gridDim.x + blockIdx.x; tile < ntiles; tile += tile_stride) {
         {   // fewer tiles left -> lower priority, so the wavefronts of a block finish together
             const long long left = (ntiles - 1 - tile) / tile_stride;
             if (left >= 3) __builtin_amdgcn_s_setprio(3);
@@ -206,7 +206,7 @@ static hipError_t run_route(const slicemoe_config &c, const void *h, const void 
     const size_t lds = (size_t)(kRouteHT * KS * 64 + ET * kRouteHT * 2 * 64) * 16 + (kRouteHr + ET * 32) * 4;
     const long long ntiles = (Ns + 31) / 32;
     constexpr int kRouteWaves = THREADS / 64;
-    long long blocks = (ntiles + kRouteWaves - 1) / kRouteWaves;
+    long long blocks = ntiles;   // one tile per block before a second wavefront of any block gets one
     const long long cap = (long long)num_compute_units();
     if (blocks > cap) blocks = cap;
     auto kern = route_mfma_kernel<DS, ET, THREADS>;
