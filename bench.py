@@ -7,7 +7,7 @@ weights pre-packed once outside the timed region as at model load).  Prints ONE 
 whole-layer tokens/s, the per-stage breakdown, the roofline of the dominant kernel (the
 grouped expert FFN, matrix-core bound) and the CPU oracle timed on this machine's host cores.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload headline|lm|skewed|large]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload headline|lm|skewed|large|paper]
 """
 import argparse
 import json
@@ -32,7 +32,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="headline", choices=["lm", "headline", "skewed", "large"])
+    ap.add_argument("--workload", default="headline", choices=["lm", "headline", "skewed", "large", "paper"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -154,7 +154,8 @@ def main():
 
     t_ffn = stage_ms["expert_ffn"] * 1e-3
     achieved = flops["expert_ffn"] / t_ffn / 1e12
-    roofline = {"kernel": "ffn_resident_kernel" if shape.ds == 64 else "ffn_streamed_kernel", "bound": "mfma", "achieved": round(achieved, 2),
+    resident = (shape.ds == 64 and shape.He in (64, 128, 256)) or (shape.ds == 96 and shape.He == 384)  # as the library plans
+    roofline = {"kernel": "ffn_resident_kernel" if resident else "ffn_streamed_kernel", "bound": "mfma", "achieved": round(achieved, 2),
                 "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_BF16_TFLOPS, 4),
                 "traffic": FFN_TRAFFIC_BYTES.get(args.workload), "launch_us": round(t_ffn * 1e6, 2),
                 "flops_per_launch": flops["expert_ffn"], "hbm_bytes_algorithmic": bytes_["expert_ffn"],

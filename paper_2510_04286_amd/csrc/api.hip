@@ -44,7 +44,7 @@ static slicemoe_status validate(const slicemoe_config *c)
     const int ds = c->d / c->S;
     // LDS staging of the generic kernels: 8 rows x (ds + max(Hr + E, He)) floats
     const long long generic_lds = 8ll * 4 * (ds + (c->Hr + c->E > c->He ? c->Hr + c->E : c->He));
-    const bool mfma_shape = c->dtype == SLICEMOE_BF16 && c->Hr == 256 && (ds == 64 || ds == 128) && c->He % 64 == 0;
+    const bool mfma_shape = c->dtype == SLICEMOE_BF16 && c->Hr == 256 && (ds == 64 || ds == 96 || ds == 128) && c->He % 64 == 0;
     const bool want_mfma = mfma_shape && !(c->flags & SLICEMOE_FLAG_FORCE_GENERIC);
     if (!want_mfma) {
         if (c->flags & SLICEMOE_FLAG_REQUIRE_MFMA) return SLICEMOE_ERR_UNSUPPORTED;
@@ -56,7 +56,7 @@ static slicemoe_status validate(const slicemoe_config *c)
 static bool use_mfma(const slicemoe_config &c)
 {
     const int ds = c.d / c.S;
-    return c.dtype == SLICEMOE_BF16 && c.Hr == 256 && (ds == 64 || ds == 128) && c.He % 64 == 0 &&
+    return c.dtype == SLICEMOE_BF16 && c.Hr == 256 && (ds == 64 || ds == 96 || ds == 128) && c.He % 64 == 0 &&
            !(c.flags & SLICEMOE_FLAG_FORCE_GENERIC);
 }
 

@@ -35,8 +35,9 @@
 //             expert boundaries; a block re-stages weights only when its range crosses into
 //             another expert.  Wavefront priority follows the number of units a wavefront still
 //             has to do, which keeps the 16 wavefronts finishing together.
-//   streamed  larger experts (ds = 128, He = 512: 256 KiB): a block walks tiles of one expert
-//             and streams the weights through LDS in chunks of hidden tiles, per row tile.
+//   streamed  larger experts (ds = 128, He = 512: 256 KiB; ds = 96, He = 384 of the paper's own shape:
+//             144 KiB): a block walks tiles of one expert and streams the weights through LDS in chunks
+//             of hidden tiles, per row tile.
 #include "mfma.h"
 
 namespace slicemoe {
@@ -246,23 +247,23 @@ __device__ __forceinline__ void set_p(RowUnit<DS, NSUB> &u, const float (&p)[NSU
 }
 
 // ------------------------------------------------------------------------------ resident
-constexpr int kResThreads = 1024;
-constexpr int kResWaves = kResThreads / 64;
 constexpr int kResU = 32;  // rows per wavefront unit (NSUB = 1)
 
 // One expert block in LDS exactly as it is packed in memory (W1 | W2 | b1 fp16 | b2 fp32, see pack.hip).
-template <int HT>
-__global__ __launch_bounds__(kResThreads) void ffn_resident_kernel(
+// THREADS = 1024 (16 wavefronts of <= 128 registers) for ds = 64; ds = 96 keeps 48 more accumulator and
+// row registers per lane and runs 12 wavefronts of <= 168.
+template <int DS, int HT, int THREADS>
+__global__ __launch_bounds__(THREADS) void ffn_resident_kernel(
     const bf16_t *__restrict__ x, const float *__restrict__ pk, const int32_t *__restrict__ offsets,
     const int32_t *__restrict__ perm, const char *__restrict__ experts, size_t e_stride, size_t off_w2,
     size_t off_b1, size_t off_b2, int E, int k, EpiConst K, half_t *__restrict__ y)
 {
-    constexpr int DS = 64;
+    constexpr int kResWaves = THREADS / 64;
     extern __shared__ __align__(16) char lds[];
-    const uint4 *w1s = (const uint4 *)lds;                  // [HT][4][64] fragments
-    const uint4 *w2s = (const uint4 *)(lds + off_w2);       // [HT][2][2][64] fragments
+    const uint4 *w1s = (const uint4 *)lds;                  // [HT][DS/16][64] fragments
+    const uint4 *w2s = (const uint4 *)(lds + off_w2);       // [HT][2][DS/32][64] fragments
     const uint4 *b1s = (const uint4 *)(lds + off_b1);       // [HT][2][16] fp16
-    const float *b2s = (const float *)(lds + off_b2);       // [64]
+    const float *b2s = (const float *)(lds + off_b2);       // [DS]
 
     const int tid = threadIdx.x, lane = tid & 63, j = lane & 31, g = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -284,7 +285,7 @@ __global__ __launch_bounds__(kResThreads) void ffn_resident_kernel(
         const int e = __builtin_amdgcn_readfirstlane(__popcll(__ballot(lane < E && off_hi <= r)));
         const int seg_end = min(__builtin_amdgcn_readfirstlane(__shfl(off_hi, e)), r_end);
         const char *ew = experts + (size_t)e * e_stride;
-        const int nunits = (seg_end - r + kResU - 1) / kResU;   // this wavefront takes units wave, wave + 16, ...
+        const int nunits = (seg_end - r + kResU - 1) / kResU;   // this wavefront takes units wave, wave + kResWaves, ...
 
         __syncthreads();  // everyone is done with the previous expert's weights
         int q_c = wave;
@@ -292,7 +293,7 @@ __global__ __launch_bounds__(kResThreads) void ffn_resident_kernel(
         float p_c[1], p_n[1];
         unit_rows<1>(r + q_c * kResU, seg_end, q_c < nunits, j, perm, row_c, a_c);   // index load rides along with the weights
         // stage the expert block (one linear copy: it is packed exactly as the kernel reads it)
-        stage_to_lds<kResThreads>(ew, lds, (int)(e_stride / 16), tid);
+        stage_to_lds<THREADS>(ew, lds, (int)(e_stride / 16), tid);
         RowUnit<DS, 1> cur, nxt;
         load_rows<DS, 1>(cur, a_c, row_c, x, pk, k, g, p_c);
         set_p<DS, 1>(cur, p_c);
@@ -309,7 +310,7 @@ __global__ __launch_bounds__(kResThreads) void ffn_resident_kernel(
             }
             unit_rows<1>(r + q_n * kResU, seg_end, q_n < nunits, j, perm, row_n, a_n);
 
-            f32x16 yacc[1][2];
+            f32x16 yacc[1][DS / 32];
             zero_acc<DS, 1>(yacc);
             f32x16 acc[2][1];
             uint4 hb[1][2];
@@ -427,7 +428,8 @@ struct FfnPlan {
     size_t lds;
 };
 
-// Whole expert resident in LDS for ds = 64 and He in {64, 128, 256}, else hidden tiles per chunk.
+// Whole expert resident in LDS for ds = 64 and He in {64, 128, 256} and for ds = 96, He = 384 (145 KiB), else hidden
+// tiles per chunk.
 static FfnPlan plan_ffn(const PackedLayout &L)
 {
     const int ds = L.ds, He = L.He, E = L.E;
@@ -435,7 +437,7 @@ static FfnPlan plan_ffn(const PackedLayout &L)
     const size_t frag_per_ht = (size_t)(KS + 2 * OT) * 1024;  // bytes of W1+W2 fragments per hidden tile
     const size_t dev_max = (size_t)max_lds_per_block();
     FfnPlan p;
-    if (ds == 64 && (He == 64 || He == 128 || He == 256) && L.e_stride <= dev_max) {
+    if (((ds == 64 && (He == 64 || He == 128 || He == 256)) || (ds == 96 && He == 384)) && L.e_stride <= dev_max) {
         p.resident = true;
         p.hc = HT;
         p.lds = L.e_stride;
@@ -456,7 +458,7 @@ static FfnPlan plan_ffn(const PackedLayout &L)
     return p;
 }
 
-template <int HT>
+template <int DS, int HT, int THREADS>
 static hipError_t run_resident(const slicemoe_config &c, const PackedLayout &L, const FfnPlan &pl, const void *h,
                                const float *p, const int32_t *offsets, const int32_t *perm, const char *experts,
                                void *y, hipStream_t s)
@@ -465,10 +467,10 @@ static hipError_t run_resident(const slicemoe_config &c, const PackedLayout &L, 
     const long long max_units = (Na + kResU - 1) / kResU;
     long long blocks = max_units;   // small inputs: spread the units over all CUs rather than fill few blocks
     if (blocks > num_compute_units()) blocks = num_compute_units();
-    auto kern = ffn_resident_kernel<HT>;
+    auto kern = ffn_resident_kernel<DS, HT, THREADS>;
     hipError_t err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds);
     if (err != hipSuccess) return err;
-    kern<<<(int)blocks, kResThreads, pl.lds, s>>>((const bf16_t *)h, p, offsets, perm, experts, L.e_stride, L.e_w2, L.e_b1,
+    kern<<<(int)blocks, THREADS, pl.lds, s>>>((const bf16_t *)h, p, offsets, perm, experts, L.e_stride, L.e_w2, L.e_b1,
                                                   L.e_b2, c.E, c.k, make_epi_const(), (half_t *)y);
     return hipGetLastError();
 }
@@ -501,11 +503,13 @@ hipError_t launch_ffn_mfma(const slicemoe_config &c, const void *h, const float 
     const FfnPlan pl = plan_ffn(L);
     const char *experts = (const char *)packed + L.experts;
     if (pl.resident) {
-        if (L.He == 256) return run_resident<8>(c, L, pl, h, p, offsets, perm, experts, y, s);
-        if (L.He == 128) return run_resident<4>(c, L, pl, h, p, offsets, perm, experts, y, s);
-        return run_resident<2>(c, L, pl, h, p, offsets, perm, experts, y, s);
+        if (L.ds == 96) return run_resident<96, 12, 768>(c, L, pl, h, p, offsets, perm, experts, y, s);
+        if (L.He == 256) return run_resident<64, 8, 1024>(c, L, pl, h, p, offsets, perm, experts, y, s);
+        if (L.He == 128) return run_resident<64, 4, 1024>(c, L, pl, h, p, offsets, perm, experts, y, s);
+        return run_resident<64, 2, 1024>(c, L, pl, h, p, offsets, perm, experts, y, s);
     }
     if (L.ds == 64) return run_streamed<64, 2>(c, L, pl, h, p, offsets, perm, experts, y, s);
+    if (L.ds == 96) return run_streamed<96, 2>(c, L, pl, h, p, offsets, perm, experts, y, s);
     return run_streamed<128, 2>(c, L, pl, h, p, offsets, perm, experts, y, s);
 }
 

@@ -81,6 +81,9 @@ CONFIGS = {
     "skewed": SliceMoEShape("skewed", T=16384, d=1024, S=16, E=32, k=2, He=256,
                             capacity_factor=1.25, zipf_s=1.2),
     "large": SliceMoEShape("large", T=65536, d=4096, S=32, E=64, k=2, He=512),
+    # the paper's own layer shape (Appendix A: d = 768, S = 8, E = 16, k = 2; expert hidden width 4 * d/S), not one of
+    # the five benchmark workloads
+    "paper": SliceMoEShape("paper", T=16384, d=768, S=8, E=16, k=2, He=384),
 }
 CONFIG_ORDER = ["tiny", "lm", "headline", "skewed", "large"]
 

@@ -141,6 +141,7 @@ def test_combine_matches_oracle(B, name, T):
 
 # ------------------------------------------------------------------ expert FFN
 FFN_CASES = [("tiny", 512, 0), ("lm", 1024, 0), ("headline", 2048, 0), ("skewed", 2048, 0), ("large", 512, 0),
+             ("paper", 1024, 0),  # slice width 96: three output tiles, six K-steps, two weight chunks
              ("headline", 1024, 1)]  # last: generic kernels on bf16 storage
 
 
@@ -194,7 +195,7 @@ def test_expert_ffn_empty_experts_and_ragged_tiles(B):
     assert err <= TOL_BF16, err
 
 
-@pytest.mark.parametrize("name,T", [("headline", 512), ("large", 128)])
+@pytest.mark.parametrize("name,T", [("headline", 512), ("large", 128), ("paper", 256)])
 def test_expert_ffn_large_preactivations(B, name, T):
     """Gates of 1 and first-layer weights scaled up: |z| reaches past 6, so the polynomial's whole fitted range and
     the saturation beyond it are exercised on the matrix-core kernels (resident and streamed)."""
@@ -220,6 +221,7 @@ def test_expert_ffn_large_preactivations(B, name, T):
 
 # ------------------------------------------------------------------ router
 ROUTE_CASES = [("tiny", 512, 0), ("lm", 4096, 0), ("headline", 4096, 0), ("skewed", 4096, 0), ("large", 1024, 0),
+               ("paper", 2048, 0),
                ("lm", 512, 1)]
 
 

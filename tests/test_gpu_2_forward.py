@@ -146,13 +146,19 @@ def test_forward_ragged_token_counts(B):
     check_against_full_oracle(B, shape, h, w)
 
 
-def test_forward_paper_native_shape_on_generic_kernels(B):
-    """d = 768, S = 8 (slice width 96), E = 16, k = 2 -- the shape of the paper's Appendix A."""
-    shape = wl.SliceMoEShape("paper768", T=256, d=768, S=8, E=16, k=2, He=384)
+def test_forward_paper_native_shape(B):
+    """d = 768, S = 8 (slice width 96), E = 16, k = 2 -- the shape of the paper's Appendix A, on the matrix-core
+    kernels (six K-steps, three output tiles) and on the generic ones."""
+    shape = wl.CONFIGS["paper"].scaled(256)
     w = wl.make_weights(shape)
     h = wl.make_h(shape)
-    assert B.slicemoe_uses_mfma(B.config_of(shape)) == 0
+    assert B.slicemoe_uses_mfma(B.config_of(shape)) == 1
     check_against_full_oracle(B, shape, h, w)
+    check_against_full_oracle(B, shape, h, w, flags=B.SLICEMOE_FLAG_FORCE_GENERIC)
+    # slice widths the matrix-core kernels do not take (S = 16 -> 48) stay on the generic kernels
+    shape48 = wl.SliceMoEShape("paper768_S16", T=96, d=768, S=16, E=16, k=2, He=192)
+    assert B.slicemoe_uses_mfma(B.config_of(shape48)) == 0
+    check_against_full_oracle(B, shape48, wl.make_h(shape48), wl.make_weights(shape48))
 
 
 def test_forward_other_k(B):
