@@ -32,6 +32,14 @@ int max_lds_per_block()
     return lds[dev];
 }
 
+// Shapes the matrix-core kernels are instantiated for: slice widths of 4, 6, 8 or 12 K-steps of 16 (64 and 128 are
+// the benchmark shapes; 96 and 192 are d = 768 cut into 8 and 4 slices), hidden tiles of 32 in pairs.
+static bool mfma_shape(const slicemoe_config &c)
+{
+    const int ds = c.d / c.S;
+    return c.dtype == SLICEMOE_BF16 && c.Hr == 256 && (ds == 64 || ds == 96 || ds == 128 || ds == 192) && c.He % 64 == 0;
+}
+
 static slicemoe_status validate(const slicemoe_config *c)
 {
     if (!c) return SLICEMOE_ERR_INVALID_ARG;
@@ -44,8 +52,7 @@ static slicemoe_status validate(const slicemoe_config *c)
     const int ds = c->d / c->S;
     // LDS staging of the generic kernels: 8 rows x (ds + max(Hr + E, He)) floats
     const long long generic_lds = 8ll * 4 * (ds + (c->Hr + c->E > c->He ? c->Hr + c->E : c->He));
-    const bool mfma_shape = c->dtype == SLICEMOE_BF16 && c->Hr == 256 && (ds == 64 || ds == 96 || ds == 128) && c->He % 64 == 0;
-    const bool want_mfma = mfma_shape && !(c->flags & SLICEMOE_FLAG_FORCE_GENERIC);
+    const bool want_mfma = mfma_shape(*c) && !(c->flags & SLICEMOE_FLAG_FORCE_GENERIC);
     if (!want_mfma) {
         if (c->flags & SLICEMOE_FLAG_REQUIRE_MFMA) return SLICEMOE_ERR_UNSUPPORTED;
         if (generic_lds > 60 * 1024) return SLICEMOE_ERR_UNSUPPORTED;
@@ -55,9 +62,7 @@ static slicemoe_status validate(const slicemoe_config *c)
 
 static bool use_mfma(const slicemoe_config &c)
 {
-    const int ds = c.d / c.S;
-    return c.dtype == SLICEMOE_BF16 && c.Hr == 256 && (ds == 64 || ds == 96 || ds == 128) && c.He % 64 == 0 &&
-           !(c.flags & SLICEMOE_FLAG_FORCE_GENERIC);
+    return mfma_shape(c) && !(c.flags & SLICEMOE_FLAG_FORCE_GENERIC);
 }
 
 PackedLayout packed_layout(const slicemoe_config &c)

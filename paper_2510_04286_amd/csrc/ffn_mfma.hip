@@ -510,6 +510,7 @@ hipError_t launch_ffn_mfma(const slicemoe_config &c, const void *h, const float 
     }
     if (L.ds == 64) return run_streamed<64, 2>(c, L, pl, h, p, offsets, perm, experts, y, s);
     if (L.ds == 96) return run_streamed<96, 2>(c, L, pl, h, p, offsets, perm, experts, y, s);
+    if (L.ds == 192) return run_streamed<192, 1>(c, L, pl, h, p, offsets, perm, experts, y, s);   // 96 output accumulators per row tile
     return run_streamed<128, 2>(c, L, pl, h, p, offsets, perm, experts, y, s);
 }
 

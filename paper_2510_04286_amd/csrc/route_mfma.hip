@@ -228,6 +228,8 @@ hipError_t launch_route_mfma(const slicemoe_config &c, const void *h, const void
         return et == 1 ? run_route<64, 1, 1024>(c, h, packed, idx, p, s) : run_route<64, 2, 512>(c, h, packed, idx, p, s);
     if (ds == 96)   // the slice width of the paper's own configuration (d = 768, S = 8): six K-steps
         return et == 1 ? run_route<96, 1, 512>(c, h, packed, idx, p, s) : run_route<96, 2, 512>(c, h, packed, idx, p, s);
+    if (ds == 192)
+        return et == 1 ? run_route<192, 1, 512>(c, h, packed, idx, p, s) : run_route<192, 2, 512>(c, h, packed, idx, p, s);
     return et == 1 ? run_route<128, 1, 512>(c, h, packed, idx, p, s) : run_route<128, 2, 512>(c, h, packed, idx, p, s);
 }
 

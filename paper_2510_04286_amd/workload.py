@@ -74,6 +74,14 @@ class SliceMoEShape:
         return replace(self, T=T, name=name or f"{self.name}@T{T}")
 
 
+def paper_shape(S: int = 8, k: int = 2, T: int = 16384) -> SliceMoEShape:
+    """The paper's own layer (Appendix A): d = 768, 16 experts, expert hidden width 4 * d/S; S = 8 and k = 2 are its
+    defaults, S in {2, 4, 8, 16, 32} its slice-count ablation (Table 2), k in {1, 2, 3} its top-k ablation
+    (Table 4).  Not one of the five benchmark workloads."""
+    name = "paper" if (S, k) == (8, 2) else f"paper_S{S}_k{k}"
+    return SliceMoEShape(name, T=T, d=768, S=S, E=16, k=k, He=4 * (768 // S))
+
+
 CONFIGS = {
     "tiny": SliceMoEShape("tiny", T=512, d=256, S=4, E=8, k=2, He=256, dtype="f32"),
     "lm": SliceMoEShape("lm", T=4096, d=512, S=8, E=16, k=2, He=256, layernorm=True),
@@ -81,9 +89,8 @@ CONFIGS = {
     "skewed": SliceMoEShape("skewed", T=16384, d=1024, S=16, E=32, k=2, He=256,
                             capacity_factor=1.25, zipf_s=1.2),
     "large": SliceMoEShape("large", T=65536, d=4096, S=32, E=64, k=2, He=512),
-    # the paper's own layer shape (Appendix A: d = 768, S = 8, E = 16, k = 2; expert hidden width 4 * d/S), not one of
-    # the five benchmark workloads
-    "paper": SliceMoEShape("paper", T=16384, d=768, S=8, E=16, k=2, He=384),
+    "paper": paper_shape(),
+    "paper_S4_k2": paper_shape(S=4),
 }
 CONFIG_ORDER = ["tiny", "lm", "headline", "skewed", "large"]
 

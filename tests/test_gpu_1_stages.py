@@ -141,7 +141,8 @@ def test_combine_matches_oracle(B, name, T):
 
 # ------------------------------------------------------------------ expert FFN
 FFN_CASES = [("tiny", 512, 0), ("lm", 1024, 0), ("headline", 2048, 0), ("skewed", 2048, 0), ("large", 512, 0),
-             ("paper", 1024, 0),  # slice width 96: three output tiles, six K-steps, two weight chunks
+             ("paper", 1024, 0),       # slice width 96: three output tiles, six K-steps
+             ("paper_S4_k2", 700, 0),  # slice width 192: six output tiles, weights streamed in chunks, ragged row tiles
              ("headline", 1024, 1)]  # last: generic kernels on bf16 storage
 
 
@@ -221,7 +222,7 @@ def test_expert_ffn_large_preactivations(B, name, T):
 
 # ------------------------------------------------------------------ router
 ROUTE_CASES = [("tiny", 512, 0), ("lm", 4096, 0), ("headline", 4096, 0), ("skewed", 4096, 0), ("large", 1024, 0),
-               ("paper", 2048, 0),
+               ("paper", 2048, 0), ("paper_S4_k2", 1000, 0),
                ("lm", 512, 1)]
 
 

@@ -161,6 +161,17 @@ def test_forward_paper_native_shape(B):
     check_against_full_oracle(B, shape48, wl.make_h(shape48), wl.make_weights(shape48))
 
 
+@pytest.mark.parametrize("S,k,T,mfma", [(2, 2, 64, 0), (4, 2, 320, 1), (16, 2, 96, 0), (32, 2, 64, 0), (8, 1, 200, 1), (8, 3, 200, 1),
+                                        (4, 3, 130, 1)])
+def test_forward_paper_slice_count_and_topk_sweeps(B, S, k, T, mfma):
+    """The paper's ablation shapes: d = 768 cut into S in {2, 4, 8, 16, 32} slices (Table 2) and k in {1, 2, 3}
+    experts per slice (Table 4), 16 experts of hidden width 4 d/S.  Slice widths 96 and 192 run on the matrix-core
+    kernels, 24, 48 and 384 on the generic ones."""
+    shape = wl.paper_shape(S, k, T)
+    assert B.slicemoe_uses_mfma(B.config_of(shape)) == mfma
+    check_against_full_oracle(B, shape, wl.make_h(shape), wl.make_weights(shape))
+
+
 def test_forward_other_k(B):
     for k in (1, 3):
         shape = wl.SliceMoEShape(f"k{k}", T=300, d=512, S=8, E=16, k=k, He=256)
