@@ -159,7 +159,7 @@ def main():
 
     t_ffn = stage_ms["expert_ffn"] * 1e-3
     achieved = flops["expert_ffn"] / t_ffn / 1e12
-    resident = (shape.ds == 64 and shape.He in (64, 128, 256)) or (shape.ds == 96 and shape.He == 384)  # as the library plans
+    resident = (shape.ds, shape.He) in ((64, 64), (64, 128), (64, 256), (96, 384), (48, 192), (24, 96))  # as the library plans
     kernel = "ffn_generic_kernel" if not B.slicemoe_uses_mfma(cfg) else "ffn_resident_kernel" if resident else "ffn_streamed_kernel"
     roofline = {"kernel": kernel, "bound": "mfma", "achieved": round(achieved, 2),
                 "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_BF16_TFLOPS, 4),

@@ -32,12 +32,14 @@ int max_lds_per_block()
     return lds[dev];
 }
 
-// Shapes the matrix-core kernels are instantiated for: slice widths of 4, 6, 8 or 12 K-steps of 16 (64 and 128 are
-// the benchmark shapes; 96 and 192 are d = 768 cut into 8 and 4 slices), hidden tiles of 32 in pairs.
+// Shapes the matrix-core kernels are instantiated for: 64 and 128 are the benchmark slice widths; 24, 48, 96 and 192
+// are d = 768 cut into 32, 16, 8 and 4 slices (24 and 48 zero-padded to whole K-steps and output tiles).  The expert
+// hidden width is a whole number of 32-wide tiles.
 static bool mfma_shape(const slicemoe_config &c)
 {
     const int ds = c.d / c.S;
-    return c.dtype == SLICEMOE_BF16 && c.Hr == 256 && (ds == 64 || ds == 96 || ds == 128 || ds == 192) && c.He % 64 == 0;
+    const bool width = ds == 24 || ds == 48 || ds == 64 || ds == 96 || ds == 128 || ds == 192;
+    return c.dtype == SLICEMOE_BF16 && c.Hr == 256 && width && c.He % 32 == 0;
 }
 
 static slicemoe_status validate(const slicemoe_config *c)
@@ -73,17 +75,19 @@ PackedLayout packed_layout(const slicemoe_config &c)
     L.He = c.He;
     L.E = c.E;
     L.Epad = (c.E + 31) / 32 * 32;
+    L.dsK = (L.ds + 15) / 16 * 16;
+    L.dsN = (L.ds + 31) / 32 * 32;
     size_t at = 0;
-    L.r_w1 = at;  at = align_up(at + (size_t)L.ds * L.Hr * 2, 256);
+    L.r_w1 = at;  at = align_up(at + (size_t)L.dsK * L.Hr * 2, 256);
     L.r_w2 = at;  at = align_up(at + (size_t)L.Hr * L.Epad * 2, 256);
     L.r_b1 = at;  at = align_up(at + (size_t)L.Hr * 4, 256);
     L.r_b2 = at;  at = align_up(at + (size_t)L.Epad * 4, 256);
     L.experts = at;
     size_t e = 0;
-    L.e_w1 = e;  e = align_up(e + (size_t)L.ds * L.He * 2, 256);
-    L.e_w2 = e;  e = align_up(e + (size_t)L.He * L.ds * 2, 256);
+    L.e_w1 = e;  e = align_up(e + (size_t)L.dsK * L.He * 2, 256);
+    L.e_w2 = e;  e = align_up(e + (size_t)L.He * L.dsN * 2, 256);
     L.e_b1 = e;  e = align_up(e + (size_t)L.He * 2, 256);
-    L.e_b2 = e;  e = align_up(e + (size_t)L.ds * 4, 256);
+    L.e_b2 = e;  e = align_up(e + (size_t)L.dsN * 4, 256);
     L.e_stride = e;
     L.total = L.experts + L.e_stride * (size_t)L.E;
     return L;

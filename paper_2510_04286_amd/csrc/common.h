@@ -69,6 +69,7 @@ __device__ __forceinline__ void stage_to_lds(const void *__restrict__ src, void 
 // All offsets in bytes from the start of the packed buffer; every region 256-byte aligned.
 struct PackedLayout {
     int ds, Hr, He, E, Epad;     // Epad = E rounded up to a multiple of 32
+    int dsK, dsN;                // ds rounded up to whole K-steps (16) and whole output tiles (32); padding is zeros
     size_t r_w1, r_w2, r_b1, r_b2;  // router: Wr1 frags, Wr2 frags, br1 (f32), br2 (f32, Epad)
     size_t experts;                 // start of expert 0
     size_t e_w1, e_w2, e_b1, e_b2;  // offsets inside one expert block: W1 frags (bf16), W2 frags (fp16, times 1/kappa),

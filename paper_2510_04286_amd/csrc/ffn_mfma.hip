@@ -101,7 +101,7 @@ __device__ __forceinline__ void activation_tile(const f32x16 &acc, h2 p2, const 
 }
 
 template <int DS, int NSUB> struct RowUnit {
-    bf16x8 xb[NSUB][DS / 16];
+    bf16x8 xb[NSUB][SliceTiles<DS>::KS];
     h2 p2[NSUB];   // (kappa p, kappa p), zero for a lane without a row
     int row[NSUB]; // -1: no row
 };
@@ -118,7 +118,7 @@ template <int DS, int NSUB>
 __device__ __forceinline__ void gemm1_tile(const RowUnit<DS, NSUB> &u, const uint4 *__restrict__ w1s, int hl, int lane,
                                            f32x16 (&acc)[NSUB])
 {
-    constexpr int KS = DS / 16;
+    constexpr int KS = SliceTiles<DS>::KS;
 #pragma unroll
     for (int sub = 0; sub < NSUB; ++sub)
 #pragma unroll
@@ -133,9 +133,9 @@ __device__ __forceinline__ void gemm1_tile(const RowUnit<DS, NSUB> &u, const uin
 
 template <int DS, int NSUB>
 __device__ __forceinline__ void gemm2_tile(const uint4 (&hb)[NSUB][2], const uint4 *__restrict__ w2s, int hl, int lane,
-                                           f32x16 (&yacc)[NSUB][DS / 32])
+                                           f32x16 (&yacc)[NSUB][SliceTiles<DS>::OT])
 {
-    constexpr int OT = DS / 32;
+    constexpr int OT = SliceTiles<DS>::OT;
 #pragma unroll
     for (int s = 0; s < 2; ++s)
 #pragma unroll
@@ -156,16 +156,17 @@ __device__ __forceinline__ uint32_t pack_half2(float a, float b)
 // of each 16-byte piece; lanes j and j + 32 trade halves (v_permlane32_swap) so that lane (j, g)
 // ends up with the whole pieces q = 2*qp + g and stores them with one 16-byte write each.
 template <int DS, int NSUB>
-__device__ __forceinline__ void store_rows(const RowUnit<DS, NSUB> &u, const f32x16 (&yacc)[NSUB][DS / 32],
+__device__ __forceinline__ void store_rows(const RowUnit<DS, NSUB> &u, const f32x16 (&yacc)[NSUB][SliceTiles<DS>::OT],
                                            const float *__restrict__ b2s, half_t *__restrict__ y, int g)
 {
 #pragma unroll
     for (int sub = 0; sub < NSUB; ++sub) {
         half_t *yr = y + (size_t)(u.row[sub] < 0 ? 0 : u.row[sub]) * DS;
 #pragma unroll
-        for (int ot = 0; ot < DS / 32; ++ot)
+        for (int ot = 0; ot < SliceTiles<DS>::OT; ++ot)
 #pragma unroll
             for (int qp = 0; qp < 2; ++qp) {
+                if (ot * 4 + 2 * qp >= SliceTiles<DS>::P) continue;   // padding columns of the last tile
                 uint32_t lo[2], hi[2];  // lo: piece q = 2qp, hi: piece q = 2qp + 1 (this lane's half of each)
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
@@ -185,7 +186,7 @@ __device__ __forceinline__ void store_rows(const RowUnit<DS, NSUB> &u, const f32
                 // (partner's hi, own hi) = piece 2qp + 1, both in feature order
                 const auto s0 = __builtin_amdgcn_permlane32_swap(lo[0], hi[0], false, false);
                 const auto s1 = __builtin_amdgcn_permlane32_swap(lo[1], hi[1], false, false);
-                if (u.row[sub] >= 0) {
+                if (u.row[sub] >= 0 && ot * 4 + 2 * qp + g < SliceTiles<DS>::P) {
                     const uint4 v = make_uint4(s0[0], s1[0], s0[1], s1[1]);
                     *(uint4 *)(yr + ot * 32 + 8 * (2 * qp + g)) = v;
                 }
@@ -194,12 +195,12 @@ __device__ __forceinline__ void store_rows(const RowUnit<DS, NSUB> &u, const f32
 }
 
 template <int DS, int NSUB>
-__device__ __forceinline__ void zero_acc(f32x16 (&yacc)[NSUB][DS / 32])
+__device__ __forceinline__ void zero_acc(f32x16 (&yacc)[NSUB][SliceTiles<DS>::OT])
 {
 #pragma unroll
     for (int sub = 0; sub < NSUB; ++sub)
 #pragma unroll
-        for (int ot = 0; ot < DS / 32; ++ot)
+        for (int ot = 0; ot < SliceTiles<DS>::OT; ++ot)
 #pragma unroll
             for (int r = 0; r < 16; ++r) yacc[sub][ot][r] = 0.f;
 }
@@ -229,9 +230,9 @@ __device__ __forceinline__ void load_rows(RowUnit<DS, NSUB> &u, const int (&a)[N
     for (int sub = 0; sub < NSUB; ++sub) {
         u.row[sub] = row[sub];
         const long long n = a[sub] / k;
-        const uint4 *xp = (const uint4 *)(x + n * DS) + g;
+        const uint4 *xr = (const uint4 *)(x + n * DS);
 #pragma unroll
-        for (int ks = 0; ks < DS / 16; ++ks) u.xb[sub][ks] = __builtin_bit_cast(bf16x8, xp[ks * 2]);
+        for (int ks = 0; ks < SliceTiles<DS>::KS; ++ks) u.xb[sub][ks] = load_row_piece<DS>(xr, ks, g);
         p[sub] = pk[a[sub]];
     }
 }
@@ -310,7 +311,7 @@ __global__ __launch_bounds__(THREADS) void ffn_resident_kernel(
             }
             unit_rows<1>(r + q_n * kResU, seg_end, q_n < nunits, j, perm, row_n, a_n);
 
-            f32x16 yacc[1][DS / 32];
+            f32x16 yacc[1][SliceTiles<DS>::OT];
             zero_acc<DS, 1>(yacc);
             f32x16 acc[2][1];
             uint4 hb[1][2];
@@ -343,8 +344,8 @@ __global__ __launch_bounds__(kFfnThreads) void ffn_streamed_kernel(
     const int32_t *__restrict__ perm, const char *__restrict__ experts, size_t e_stride, size_t off_w1,
     size_t off_w2, size_t off_b1, size_t off_b2, int He, int E, int k, int hc, EpiConst K, half_t *__restrict__ y)
 {
-    constexpr int KS = DS / 16;
-    constexpr int OT = DS / 32;
+    constexpr int KS = SliceTiles<DS>::KS;
+    constexpr int OT = SliceTiles<DS>::OT;
     constexpr int TM = kFfnWaves * NSUB * 32;
     constexpr int kRound = DS <= 64 ? 8 : 4;   // pieces in flight per thread while staging (register budget)
     const int HT = He / 32;
@@ -354,8 +355,8 @@ __global__ __launch_bounds__(kFfnThreads) void ffn_streamed_kernel(
     uint4 *w1s = (uint4 *)lds;                                     // [hc][KS][64] fragments
     uint4 *w2s = w1s + (size_t)hc * KS * 64;                       // [hc][2][OT][64] fragments
     uint4 *b1s = w2s + (size_t)hc * 2 * OT * 64;                   // [HT][2][16] fp16 = He * 2 bytes
-    float *b2s = (float *)(b1s + He / 8);                          // [DS]
-    int *tile_prefix = (int *)(b2s + DS);                          // [E+1]
+    float *b2s = (float *)(b1s + He / 8);                          // [OT*32]
+    int *tile_prefix = (int *)(b2s + OT * 32);                     // [E+1]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -403,7 +404,7 @@ __global__ __launch_bounds__(kFfnThreads) void ffn_streamed_kernel(
                 const uint4 *gb1 = (const uint4 *)(ew + off_b1);
                 const float *gb2 = (const float *)(ew + off_b2);
                 for (int i = tid; i < He / 8; i += kFfnThreads) b1s[i] = gb1[i];
-                for (int i = tid; i < DS; i += kFfnThreads) b2s[i] = gb2[i];
+                for (int i = tid; i < OT * 32; i += kFfnThreads) b2s[i] = gb2[i];   // padded with zeros by the packer
             }
             __syncthreads();
             for (int hl = 0; hl < hc; ++hl) {
@@ -428,23 +429,30 @@ struct FfnPlan {
     size_t lds;
 };
 
-// Whole expert resident in LDS for ds = 64 and He in {64, 128, 256} and for ds = 96, He = 384 (145 KiB), else hidden
-// tiles per chunk.
+// Shapes the resident kernel is instantiated for: the benchmark shapes and He = 4 ds of the paper's slice widths.
+static bool resident_shape(int ds, int He)
+{
+    return (ds == 64 && (He == 64 || He == 128 || He == 256)) || (ds == 96 && He == 384) || (ds == 48 && He == 192) ||
+           (ds == 24 && He == 96);
+}
+
+// Whole expert resident in LDS where an instantiation exists (ds = 96, He = 384 takes 145 KiB), else hidden tiles per
+// chunk.
 static FfnPlan plan_ffn(const PackedLayout &L)
 {
     const int ds = L.ds, He = L.He, E = L.E;
-    const int HT = He / 32, KS = ds / 16, OT = ds / 32;
+    const int HT = He / 32, KS = L.dsK / 16, OT = L.dsN / 32;
     const size_t frag_per_ht = (size_t)(KS + 2 * OT) * 1024;  // bytes of W1+W2 fragments per hidden tile
     const size_t dev_max = (size_t)max_lds_per_block();
     FfnPlan p;
-    if (((ds == 64 && (He == 64 || He == 128 || He == 256)) || (ds == 96 && He == 384)) && L.e_stride <= dev_max) {
+    if (resident_shape(ds, He) && L.e_stride <= dev_max) {
         p.resident = true;
         p.hc = HT;
         p.lds = L.e_stride;
         return p;
     }
     // a streamed block needs the whole register file of its CU anyway, so chunks may take most of the LDS
-    const size_t fixed = (size_t)He * 2 + (size_t)(ds + E + 1) * 4 + 64;
+    const size_t fixed = (size_t)He * 2 + (size_t)(L.dsN + E + 1) * 4 + 64;
     const size_t want = 140 * 1024;
     const size_t budget = dev_max < want ? dev_max : want;
     p.resident = false;
@@ -503,11 +511,15 @@ hipError_t launch_ffn_mfma(const slicemoe_config &c, const void *h, const float 
     const FfnPlan pl = plan_ffn(L);
     const char *experts = (const char *)packed + L.experts;
     if (pl.resident) {
+        if (L.ds == 24) return run_resident<24, 3, 1024>(c, L, pl, h, p, offsets, perm, experts, y, s);
+        if (L.ds == 48) return run_resident<48, 6, 1024>(c, L, pl, h, p, offsets, perm, experts, y, s);
         if (L.ds == 96) return run_resident<96, 12, 768>(c, L, pl, h, p, offsets, perm, experts, y, s);
         if (L.He == 256) return run_resident<64, 8, 1024>(c, L, pl, h, p, offsets, perm, experts, y, s);
         if (L.He == 128) return run_resident<64, 4, 1024>(c, L, pl, h, p, offsets, perm, experts, y, s);
         return run_resident<64, 2, 1024>(c, L, pl, h, p, offsets, perm, experts, y, s);
     }
+    if (L.ds == 24) return run_streamed<24, 2>(c, L, pl, h, p, offsets, perm, experts, y, s);
+    if (L.ds == 48) return run_streamed<48, 2>(c, L, pl, h, p, offsets, perm, experts, y, s);
     if (L.ds == 64) return run_streamed<64, 2>(c, L, pl, h, p, offsets, perm, experts, y, s);
     if (L.ds == 96) return run_streamed<96, 2>(c, L, pl, h, p, offsets, perm, experts, y, s);
     if (L.ds == 192) return run_streamed<192, 1>(c, L, pl, h, p, offsets, perm, experts, y, s);   // 96 output accumulators per row tile

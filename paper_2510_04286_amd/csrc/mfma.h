@@ -32,4 +32,27 @@ __host__ __device__ __forceinline__ int acc_feature(int r, int g) { return 8 * (
 // feature index inside a 32-wide tile that sits in contraction slot m of K-step s for lane group g
 __host__ __device__ __forceinline__ int chain_feature(int s, int g, int m) { return 16 * s + 8 * (m >> 2) + 4 * g + (m & 3); }
 
+// A slice of DS bf16 values (DS a multiple of 8: whole 16-byte pieces) as matrix-core operand: K-steps of 16 for the
+// GEMM that contracts over it, output tiles of 32 for the GEMM that produces it.  Widths that are not multiples of
+// 16 / 32 (24, 48) are padded with zeros: in the packed weights, and here for the activation operand.
+template <int DS> struct SliceTiles {
+    static_assert(DS % 8 == 0, "slice rows are whole 16-byte pieces");
+    static constexpr int KS = (DS + 15) / 16;
+    static constexpr int OT = (DS + 31) / 32;
+    static constexpr int P = DS / 8;   // 16-byte pieces per row
+};
+
+// Piece 2*ks + g of a slice row (the B operand of K-step ks for lane group g); zeros past the end of the row, and
+// then the address read stays inside the row.
+template <int DS>
+__device__ __forceinline__ bf16x8 load_row_piece(const uint4 *__restrict__ row, int ks, int g)
+{
+    constexpr int P = SliceTiles<DS>::P;
+    if (2 * ks + 1 < P) return __builtin_bit_cast(bf16x8, row[2 * ks + g]);
+    const int piece = 2 * ks + g;
+    uint4 v = row[piece < P ? piece : 0];
+    if (piece >= P) v = make_uint4(0, 0, 0, 0);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
 }  // namespace slicemoe

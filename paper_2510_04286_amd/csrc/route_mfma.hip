@@ -33,7 +33,7 @@ __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
     size_t off_w1, size_t off_b1, size_t off_b2, int32_t *__restrict__ idx,
     float *__restrict__ pk)
 {
-    constexpr int KS = DS / 16;
+    constexpr int KS = SliceTiles<DS>::KS;
     constexpr int HT = kRouteHT;
     constexpr int kRouteWaves = THREADS / 64;
     extern __shared__ __align__(16) char lds[];
@@ -54,9 +54,9 @@ __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
     auto load_x = [&](long long tile, bf16x8 (&xb)[KS]) {
         const long long n = tile * 32 + j;
         const bool valid = tile < ntiles && n < Ns;
-        const uint4 *xp = (const uint4 *)(x + (valid ? n : 0) * DS) + g;   // a lane without a slice reads slice 0
+        const uint4 *xr = (const uint4 *)(x + (valid ? n : 0) * DS);   // a lane without a slice reads slice 0
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) xb[ks] = __builtin_bit_cast(bf16x8, xp[ks * 2]);
+        for (int ks = 0; ks < KS; ++ks) xb[ks] = load_row_piece<DS>(xr, ks, g);
     };
     bf16x8 xb[KS];
     load_x((long long)wave * gridDim.x + blockIdx.x, xb);   // tiles go round the blocks first: small inputs still use every CU
@@ -202,7 +202,7 @@ static hipError_t run_route(const slicemoe_config &c, const void *h, const void 
 {
     const PackedLayout L = packed_layout(c);
     const long long Ns = (long long)c.T * c.S;
-    constexpr int KS = DS / 16;
+    constexpr int KS = SliceTiles<DS>::KS;
     const size_t lds = (size_t)(kRouteHT * KS * 64 + ET * kRouteHT * 2 * 64) * 16 + (kRouteHr + ET * 32) * 4;
     const long long ntiles = (Ns + 31) / 32;
     constexpr int kRouteWaves = THREADS / 64;
@@ -224,6 +224,10 @@ hipError_t launch_route_mfma(const slicemoe_config &c, const void *h, const void
     if ((long long)c.T * c.S == 0) return hipSuccess;
     const int ds = c.d / c.S;
     const int et = (c.E + 31) / 32;
+    if (ds == 24)   // two K-steps, the second half zeros
+        return et == 1 ? run_route<24, 1, 1024>(c, h, packed, idx, p, s) : run_route<24, 2, 512>(c, h, packed, idx, p, s);
+    if (ds == 48)
+        return et == 1 ? run_route<48, 1, 1024>(c, h, packed, idx, p, s) : run_route<48, 2, 512>(c, h, packed, idx, p, s);
     if (ds == 64)
         return et == 1 ? run_route<64, 1, 1024>(c, h, packed, idx, p, s) : run_route<64, 2, 512>(c, h, packed, idx, p, s);
     if (ds == 96)   // the slice width of the paper's own configuration (d = 768, S = 8): six K-steps

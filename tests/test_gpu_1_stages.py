@@ -143,6 +143,7 @@ def test_combine_matches_oracle(B, name, T):
 FFN_CASES = [("tiny", 512, 0), ("lm", 1024, 0), ("headline", 2048, 0), ("skewed", 2048, 0), ("large", 512, 0),
              ("paper", 1024, 0),       # slice width 96: three output tiles, six K-steps
              ("paper_S4_k2", 700, 0),  # slice width 192: six output tiles, weights streamed in chunks, ragged row tiles
+             ("paper_S16_k2", 300, 0), ("paper_S32_k2", 150, 0),  # slice widths 48 and 24: padded K-steps and output tiles
              ("headline", 1024, 1)]  # last: generic kernels on bf16 storage
 
 
@@ -196,7 +197,7 @@ def test_expert_ffn_empty_experts_and_ragged_tiles(B):
     assert err <= TOL_BF16, err
 
 
-@pytest.mark.parametrize("name,T", [("headline", 512), ("large", 128), ("paper", 256)])
+@pytest.mark.parametrize("name,T", [("headline", 512), ("large", 128), ("paper", 256), ("paper_S32_k2", 100)])
 def test_expert_ffn_large_preactivations(B, name, T):
     """Gates of 1 and first-layer weights scaled up: |z| reaches past 6, so the polynomial's whole fitted range and
     the saturation beyond it are exercised on the matrix-core kernels (resident and streamed)."""
@@ -222,7 +223,7 @@ def test_expert_ffn_large_preactivations(B, name, T):
 
 # ------------------------------------------------------------------ router
 ROUTE_CASES = [("tiny", 512, 0), ("lm", 4096, 0), ("headline", 4096, 0), ("skewed", 4096, 0), ("large", 1024, 0),
-               ("paper", 2048, 0), ("paper_S4_k2", 1000, 0),
+               ("paper", 2048, 0), ("paper_S4_k2", 1000, 0), ("paper_S16_k2", 500, 0), ("paper_S32_k2", 250, 0),
                ("lm", 512, 1)]
 
 

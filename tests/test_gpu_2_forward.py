@@ -155,20 +155,29 @@ def test_forward_paper_native_shape(B):
     assert B.slicemoe_uses_mfma(B.config_of(shape)) == 1
     check_against_full_oracle(B, shape, h, w)
     check_against_full_oracle(B, shape, h, w, flags=B.SLICEMOE_FLAG_FORCE_GENERIC)
-    # slice widths the matrix-core kernels do not take (S = 16 -> 48) stay on the generic kernels
-    shape48 = wl.SliceMoEShape("paper768_S16", T=96, d=768, S=16, E=16, k=2, He=192)
-    assert B.slicemoe_uses_mfma(B.config_of(shape48)) == 0
-    check_against_full_oracle(B, shape48, wl.make_h(shape48), wl.make_weights(shape48))
+    # slice widths the matrix-core kernels do not take (here 40) stay on the generic kernels
+    shape40 = wl.SliceMoEShape("d640_S16", T=96, d=640, S=16, E=16, k=2, He=160)
+    assert B.slicemoe_uses_mfma(B.config_of(shape40)) == 0
+    check_against_full_oracle(B, shape40, wl.make_h(shape40), wl.make_weights(shape40))
 
 
-@pytest.mark.parametrize("S,k,T,mfma", [(2, 2, 64, 0), (4, 2, 320, 1), (16, 2, 96, 0), (32, 2, 64, 0), (8, 1, 200, 1), (8, 3, 200, 1),
-                                        (4, 3, 130, 1)])
+@pytest.mark.parametrize("S,k,T,mfma", [(2, 2, 64, 0), (4, 2, 320, 1), (16, 2, 96, 1), (32, 2, 67, 1), (8, 1, 200, 1), (8, 3, 200, 1),
+                                        (4, 3, 130, 1), (16, 3, 257, 1), (32, 1, 129, 1)])
 def test_forward_paper_slice_count_and_topk_sweeps(B, S, k, T, mfma):
     """The paper's ablation shapes: d = 768 cut into S in {2, 4, 8, 16, 32} slices (Table 2) and k in {1, 2, 3}
-    experts per slice (Table 4), 16 experts of hidden width 4 d/S.  Slice widths 96 and 192 run on the matrix-core
-    kernels, 24, 48 and 384 on the generic ones."""
+    experts per slice (Table 4), 16 experts of hidden width 4 d/S.  Slice widths 24 to 192 run on the matrix-core
+    kernels (24 and 48 zero-padded to whole K-steps and output tiles), 384 on the generic ones."""
     shape = wl.paper_shape(S, k, T)
     assert B.slicemoe_uses_mfma(B.config_of(shape)) == mfma
+    check_against_full_oracle(B, shape, wl.make_h(shape), wl.make_weights(shape))
+
+
+@pytest.mark.parametrize("d,S,E,He,T", [(384, 8, 8, 256, 300), (96, 4, 40, 160, 500), (768, 8, 16, 160, 200), (256, 4, 8, 96, 333)])
+def test_forward_streamed_expert_kernel_on_other_hidden_widths(B, d, S, E, He, T):
+    """Hidden widths without a resident instantiation (any multiple of 32, odd tile counts included) take the
+    streamed expert kernel at every slice width, padded ones too; E = 40 uses two expert tiles in the router."""
+    shape = wl.SliceMoEShape(f"d{d}_S{S}_He{He}", T=T, d=d, S=S, E=E, k=2, He=He)
+    assert B.slicemoe_uses_mfma(B.config_of(shape)) == 1
     check_against_full_oracle(B, shape, wl.make_h(shape), wl.make_weights(shape))
 
 
