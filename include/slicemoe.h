@@ -24,7 +24,7 @@
  *     mantissa bits than bf16, so the one rounding of h' after the k-sum stays the only
  *     significant one; |y| beyond 65504 would overflow).
  *   - Limits: 1 <= k <= min(E, 8), E <= 64, d % S == 0, T*S*k < 2^31.  The matrix-core
- *     (MFMA) kernels need dtype = bf16, Hr = 256, ds in {24, 48, 64, 96, 128, 192}, He % 32 == 0; any
+ *     (MFMA) kernels need dtype = bf16, Hr = 256, ds in {24, 48, 64, 96, 128, 192, 384}, He % 32 == 0; any
  *     other shape runs on slower generic kernels unless SLICEMOE_FLAG_REQUIRE_MFMA is set.
  *   - Errors are return codes; nothing aborts or throws across this boundary.
  */

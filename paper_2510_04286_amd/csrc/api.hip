@@ -33,12 +33,12 @@ int max_lds_per_block()
 }
 
 // Shapes the matrix-core kernels are instantiated for: 64 and 128 are the benchmark slice widths; 24, 48, 96 and 192
-// are d = 768 cut into 32, 16, 8 and 4 slices (24 and 48 zero-padded to whole K-steps and output tiles).  The expert
+// are d = 768 cut into 32, 16, 8 and 4 slices (24 and 48 zero-padded to whole K-steps and output tiles), 384 into 2.  The expert
 // hidden width is a whole number of 32-wide tiles.
 static bool mfma_shape(const slicemoe_config &c)
 {
     const int ds = c.d / c.S;
-    const bool width = ds == 24 || ds == 48 || ds == 64 || ds == 96 || ds == 128 || ds == 192;
+    const bool width = ds == 24 || ds == 48 || ds == 64 || ds == 96 || ds == 128 || ds == 192 || ds == 384;
     return c.dtype == SLICEMOE_BF16 && c.Hr == 256 && width && c.He % 32 == 0;
 }
 

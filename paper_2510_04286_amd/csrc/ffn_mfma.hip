@@ -335,17 +335,18 @@ __global__ __launch_bounds__(THREADS) void ffn_resident_kernel(
 }
 
 // ------------------------------------------------------------------------------ streamed
-constexpr int kFfnThreads = 512;   // two wavefronts per SIMD: one's matrix work overlaps the other's vector work
-constexpr int kFfnWaves = kFfnThreads / 64;
+// THREADS = 512: two wavefronts per SIMD, one's matrix work overlaps the other's vector work.  Slice width 384 needs
+// 192 output accumulators and 96 row registers per lane, more than half a SIMD's register file: 256 threads there.
 
-template <int DS, int NSUB>
-__global__ __launch_bounds__(kFfnThreads) void ffn_streamed_kernel(
+template <int DS, int NSUB, int THREADS>
+__global__ __launch_bounds__(THREADS) void ffn_streamed_kernel(
     const bf16_t *__restrict__ x, const float *__restrict__ pk, const int32_t *__restrict__ offsets,
     const int32_t *__restrict__ perm, const char *__restrict__ experts, size_t e_stride, size_t off_w1,
     size_t off_w2, size_t off_b1, size_t off_b2, int He, int E, int k, int hc, EpiConst K, half_t *__restrict__ y)
 {
     constexpr int KS = SliceTiles<DS>::KS;
     constexpr int OT = SliceTiles<DS>::OT;
+    constexpr int kFfnWaves = THREADS / 64;
     constexpr int TM = kFfnWaves * NSUB * 32;
     constexpr int kRound = DS <= 64 ? 8 : 4;   // pieces in flight per thread while staging (register budget)
     const int HT = He / 32;
@@ -398,13 +399,13 @@ __global__ __launch_bounds__(kFfnThreads) void ffn_streamed_kernel(
         zero_acc<DS, NSUB>(yacc);
         for (int ch = 0; ch < nchunks; ++ch) {
             __syncthreads();  // everyone is done with the previous contents
-            stage_to_lds<kFfnThreads, kRound>((const uint4 *)(ew + off_w1) + (size_t)ch * hc * KS * 64, w1s, hc * KS * 64, tid);
-            stage_to_lds<kFfnThreads, kRound>((const uint4 *)(ew + off_w2) + (size_t)ch * hc * 2 * OT * 64, w2s, hc * 2 * OT * 64, tid);
+            stage_to_lds<THREADS, kRound>((const uint4 *)(ew + off_w1) + (size_t)ch * hc * KS * 64, w1s, hc * KS * 64, tid);
+            stage_to_lds<THREADS, kRound>((const uint4 *)(ew + off_w2) + (size_t)ch * hc * 2 * OT * 64, w2s, hc * 2 * OT * 64, tid);
             if (new_expert && ch == 0) {
                 const uint4 *gb1 = (const uint4 *)(ew + off_b1);
                 const float *gb2 = (const float *)(ew + off_b2);
-                for (int i = tid; i < He / 8; i += kFfnThreads) b1s[i] = gb1[i];
-                for (int i = tid; i < OT * 32; i += kFfnThreads) b2s[i] = gb2[i];   // padded with zeros by the packer
+                for (int i = tid; i < He / 8; i += THREADS) b1s[i] = gb1[i];
+                for (int i = tid; i < OT * 32; i += THREADS) b2s[i] = gb2[i];   // padded with zeros by the packer
             }
             __syncthreads();
             for (int hl = 0; hl < hc; ++hl) {
@@ -483,20 +484,20 @@ static hipError_t run_resident(const slicemoe_config &c, const PackedLayout &L, 
     return hipGetLastError();
 }
 
-template <int DS, int NSUB>
+template <int DS, int NSUB, int THREADS = 512>
 static hipError_t run_streamed(const slicemoe_config &c, const PackedLayout &L, const FfnPlan &pl, const void *h,
                                const float *p, const int32_t *offsets, const int32_t *perm, const char *experts,
                                void *y, hipStream_t s)
 {
     const long long Na = (long long)c.T * c.S * c.k;
-    constexpr int TM = kFfnWaves * NSUB * 32;
+    constexpr int TM = THREADS / 64 * NSUB * 32;
     const long long max_tiles = (Na + TM - 1) / TM + c.E;
     long long blocks = (long long)num_compute_units() * (pl.lds <= 78 * 1024 ? 2 : 1);
     if (blocks > max_tiles) blocks = max_tiles;
-    auto kern = ffn_streamed_kernel<DS, NSUB>;
+    auto kern = ffn_streamed_kernel<DS, NSUB, THREADS>;
     hipError_t err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds);
     if (err != hipSuccess) return err;
-    kern<<<(int)blocks, kFfnThreads, pl.lds, s>>>((const bf16_t *)h, p, offsets, perm, experts, L.e_stride, L.e_w1, L.e_w2,
+    kern<<<(int)blocks, THREADS, pl.lds, s>>>((const bf16_t *)h, p, offsets, perm, experts, L.e_stride, L.e_w1, L.e_w2,
                                                   L.e_b1, L.e_b2, c.He, c.E, c.k, pl.hc, make_epi_const(), (half_t *)y);
     return hipGetLastError();
 }
@@ -523,6 +524,7 @@ hipError_t launch_ffn_mfma(const slicemoe_config &c, const void *h, const float 
     if (L.ds == 64) return run_streamed<64, 2>(c, L, pl, h, p, offsets, perm, experts, y, s);
     if (L.ds == 96) return run_streamed<96, 2>(c, L, pl, h, p, offsets, perm, experts, y, s);
     if (L.ds == 192) return run_streamed<192, 1>(c, L, pl, h, p, offsets, perm, experts, y, s);   // 96 output accumulators per row tile
+    if (L.ds == 384) return run_streamed<384, 1, 256>(c, L, pl, h, p, offsets, perm, experts, y, s);
     return run_streamed<128, 2>(c, L, pl, h, p, offsets, perm, experts, y, s);
 }
 

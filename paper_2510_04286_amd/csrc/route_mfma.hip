@@ -27,7 +27,9 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 // One block per CU shares one LDS copy of the router: THREADS = 1024 (16 wavefronts, <= 128 VGPRs)
 // for the small shapes, 512 where the accumulators of two expert tiles or K = 128 need more registers.
-template <int DS, int ET, int THREADS>
+// W1_LDS = false (slice width 384, whose first layer of 192 KiB exceeds the LDS): the first-layer fragments are read
+// from memory as they are used; only the second layer and the biases are staged.
+template <int DS, int ET, int THREADS, bool W1_LDS>
 __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
     const bf16_t *__restrict__ x, long long Ns, int E, int k, const char *__restrict__ packed,
     size_t off_w1, size_t off_b1, size_t off_b2, int32_t *__restrict__ idx,
@@ -37,8 +39,8 @@ __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
     constexpr int HT = kRouteHT;
     constexpr int kRouteWaves = THREADS / 64;
     extern __shared__ __align__(16) char lds[];
-    uint4 *w1s = (uint4 *)lds;                         // [HT][KS][64]
-    uint4 *w2s = w1s + HT * KS * 64;                   // [ET][HT][2][64]
+    const uint4 *w1s = W1_LDS ? (const uint4 *)lds : (const uint4 *)(packed + off_w1);   // [HT][KS][64]
+    uint4 *w2s = (uint4 *)lds + (W1_LDS ? HT * KS * 64 : 0);                             // [ET][HT][2][64]
     float *b1s = (float *)(w2s + ET * HT * 2 * 64);    // [Hr]
     float *b2s = b1s + kRouteHr;                       // [ET*32]
 
@@ -62,12 +64,13 @@ __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
     load_x((long long)wave * gridDim.x + blockIdx.x, xb);   // tiles go round the blocks first: small inputs still use every CU
     {
         // the whole router (W1 and W2 fragments are adjacent in the packed buffer) goes global -> registers -> LDS
-        constexpr int kPieces = HT * KS * 64 + ET * HT * 2 * 64;
+        constexpr int kW1Pieces = HT * KS * 64;
+        constexpr int kPieces = (W1_LDS ? kW1Pieces : 0) + ET * HT * 2 * 64;
         const float *gb1 = (const float *)(packed + off_b1);
         const float *gb2 = (const float *)(packed + off_b2);
         const float bv1 = gb1[tid < kRouteHr ? tid : 0];
         const float bv2 = gb2[tid < ET * 32 ? tid : 0];
-        stage_to_lds<THREADS>(packed + off_w1, w1s, kPieces, tid);
+        stage_to_lds<THREADS>(packed + off_w1 + (W1_LDS ? 0 : (size_t)kW1Pieces * 16), lds, kPieces, tid);
         if (tid < kRouteHr) b1s[tid] = bv1;
         if (tid < ET * 32) b2s[tid] = bv2;
     }
@@ -196,20 +199,20 @@ __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
     }
 }
 
-template <int DS, int ET, int THREADS>
+template <int DS, int ET, int THREADS, bool W1_LDS = true>
 static hipError_t run_route(const slicemoe_config &c, const void *h, const void *packed, int32_t *idx, float *p,
                             hipStream_t s)
 {
     const PackedLayout L = packed_layout(c);
     const long long Ns = (long long)c.T * c.S;
     constexpr int KS = SliceTiles<DS>::KS;
-    const size_t lds = (size_t)(kRouteHT * KS * 64 + ET * kRouteHT * 2 * 64) * 16 + (kRouteHr + ET * 32) * 4;
+    const size_t lds = (size_t)((W1_LDS ? kRouteHT * KS * 64 : 0) + ET * kRouteHT * 2 * 64) * 16 + (kRouteHr + ET * 32) * 4;
     const long long ntiles = (Ns + 31) / 32;
     constexpr int kRouteWaves = THREADS / 64;
     long long blocks = ntiles;   // one tile per block before a second wavefront of any block gets one
     const long long cap = (long long)num_compute_units();
     if (blocks > cap) blocks = cap;
-    auto kern = route_mfma_kernel<DS, ET, THREADS>;
+    auto kern = route_mfma_kernel<DS, ET, THREADS, W1_LDS>;
     hipError_t err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (err != hipSuccess) return err;
     if (L.r_w2 != L.r_w1 + (size_t)kRouteHT * KS * 64 * 16) return hipErrorInvalidValue;   // the kernel copies W1 | W2 as one run
@@ -234,6 +237,8 @@ hipError_t launch_route_mfma(const slicemoe_config &c, const void *h, const void
         return et == 1 ? run_route<96, 1, 512>(c, h, packed, idx, p, s) : run_route<96, 2, 512>(c, h, packed, idx, p, s);
     if (ds == 192)
         return et == 1 ? run_route<192, 1, 512>(c, h, packed, idx, p, s) : run_route<192, 2, 512>(c, h, packed, idx, p, s);
+    if (ds == 384)
+        return et == 1 ? run_route<384, 1, 256, false>(c, h, packed, idx, p, s) : run_route<384, 2, 256, false>(c, h, packed, idx, p, s);
     return et == 1 ? run_route<128, 1, 512>(c, h, packed, idx, p, s) : run_route<128, 2, 512>(c, h, packed, idx, p, s);
 }
 

@@ -90,6 +90,7 @@ CONFIGS = {
                             capacity_factor=1.25, zipf_s=1.2),
     "large": SliceMoEShape("large", T=65536, d=4096, S=32, E=64, k=2, He=512),
     "paper": paper_shape(),
+    "paper_S2_k2": paper_shape(S=2),
     "paper_S4_k2": paper_shape(S=4),
     "paper_S16_k2": paper_shape(S=16),
     "paper_S32_k2": paper_shape(S=32),

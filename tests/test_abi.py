@@ -45,7 +45,8 @@ def test_config_validation_and_kernel_choice(B):
     assert B.slicemoe_uses_mfma(B.make_config(512, 256, 4, 2, 8, 256, dtype="f32")) == 0
     assert B.slicemoe_uses_mfma(B.make_config(64, 768, 8, 2, 16, 384)) == 1  # ds = 96, the paper's own shape
     assert B.slicemoe_uses_mfma(B.make_config(64, 768, 16, 2, 16, 192)) == 1  # ds = 48: zero-padded K-steps and tiles
-    assert B.slicemoe_uses_mfma(B.make_config(64, 768, 2, 2, 16, 1536)) == 0  # ds = 384: generic kernels
+    assert B.slicemoe_uses_mfma(B.make_config(64, 768, 2, 2, 16, 1536)) == 1  # ds = 384: first router layer read from memory
+    assert B.slicemoe_uses_mfma(B.make_config(64, 640, 16, 2, 16, 160)) == 0  # ds = 40: generic kernels
     assert B.slicemoe_uses_mfma(B.make_config(64, 1024, 16, 2, 32, 256, flags=B.SLICEMOE_FLAG_FORCE_GENERIC)) == 0
     for bad in [B.make_config(8, 100, 3, 2, 4, 16),      # d % S != 0
                 B.make_config(8, 64, 4, 5, 4, 16),       # k > E
@@ -53,7 +54,7 @@ def test_config_validation_and_kernel_choice(B):
                 B.make_config(8, 64, 4, 0, 4, 16),
                 B.make_config(8, 64, 4, 2, 65, 16),      # E > 64
                 B.make_config(8, 64, 4, 9, 16, 16),      # k > 8
-                B.make_config(8, 768, 2, 2, 16, 1536, flags=B.SLICEMOE_FLAG_REQUIRE_MFMA)]:
+                B.make_config(8, 640, 16, 2, 16, 160, flags=B.SLICEMOE_FLAG_REQUIRE_MFMA)]:
         assert B.slicemoe_uses_mfma(bad) == -1
         assert B.slicemoe_workspace_bytes(bad) == 0 and B.slicemoe_packed_bytes(bad) == 0
     L = B.lib()

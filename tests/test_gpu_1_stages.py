@@ -144,6 +144,7 @@ FFN_CASES = [("tiny", 512, 0), ("lm", 1024, 0), ("headline", 2048, 0), ("skewed"
              ("paper", 1024, 0),       # slice width 96: three output tiles, six K-steps
              ("paper_S4_k2", 700, 0),  # slice width 192: six output tiles, weights streamed in chunks, ragged row tiles
              ("paper_S16_k2", 300, 0), ("paper_S32_k2", 150, 0),  # slice widths 48 and 24: padded K-steps and output tiles
+             ("paper_S2_k2", 1100, 0),  # slice width 384: four wavefronts per block, 24 weight chunks per row tile
              ("headline", 1024, 1)]  # last: generic kernels on bf16 storage
 
 
@@ -223,7 +224,7 @@ def test_expert_ffn_large_preactivations(B, name, T):
 
 # ------------------------------------------------------------------ router
 ROUTE_CASES = [("tiny", 512, 0), ("lm", 4096, 0), ("headline", 4096, 0), ("skewed", 4096, 0), ("large", 1024, 0),
-               ("paper", 2048, 0), ("paper_S4_k2", 1000, 0), ("paper_S16_k2", 500, 0), ("paper_S32_k2", 250, 0),
+               ("paper", 2048, 0), ("paper_S4_k2", 1000, 0), ("paper_S16_k2", 500, 0), ("paper_S32_k2", 250, 0), ("paper_S2_k2", 3000, 0),
                ("lm", 512, 1)]
 
 

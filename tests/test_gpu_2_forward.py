@@ -161,12 +161,12 @@ def test_forward_paper_native_shape(B):
     check_against_full_oracle(B, shape40, wl.make_h(shape40), wl.make_weights(shape40))
 
 
-@pytest.mark.parametrize("S,k,T,mfma", [(2, 2, 64, 0), (4, 2, 320, 1), (16, 2, 96, 1), (32, 2, 67, 1), (8, 1, 200, 1), (8, 3, 200, 1),
-                                        (4, 3, 130, 1), (16, 3, 257, 1), (32, 1, 129, 1)])
+@pytest.mark.parametrize("S,k,T,mfma", [(2, 2, 700, 1), (4, 2, 320, 1), (16, 2, 96, 1), (32, 2, 67, 1), (8, 1, 200, 1), (8, 3, 200, 1),
+                                        (4, 3, 130, 1), (16, 3, 257, 1), (32, 1, 129, 1), (2, 3, 33, 1)])
 def test_forward_paper_slice_count_and_topk_sweeps(B, S, k, T, mfma):
     """The paper's ablation shapes: d = 768 cut into S in {2, 4, 8, 16, 32} slices (Table 2) and k in {1, 2, 3}
-    experts per slice (Table 4), 16 experts of hidden width 4 d/S.  Slice widths 24 to 192 run on the matrix-core
-    kernels (24 and 48 zero-padded to whole K-steps and output tiles), 384 on the generic ones."""
+    experts per slice (Table 4), 16 experts of hidden width 4 d/S.  All of these slice widths, 24 to 384, run on the
+    matrix-core kernels (24 and 48 zero-padded to whole K-steps and output tiles)."""
     shape = wl.paper_shape(S, k, T)
     assert B.slicemoe_uses_mfma(B.config_of(shape)) == mfma
     check_against_full_oracle(B, shape, wl.make_h(shape), wl.make_weights(shape))
