@@ -92,6 +92,33 @@ def route(x, Wr1, br1, Wr2, br2, k: int, want_logits: bool = False):
     return out
 
 
+def route_train(x, Wr1, br1, Wr2, br2, k: int, tau: float = 1.0, sigma: float = 0.0, noise=None,
+                rate: float = 0.0, drop_u=None, want_logits: bool = False):
+    """Training-time router (temperature: Appendix B; logit noise: Section 5; cross-slice dropout: Section 3.3).
+    noise[Ns, E] standard-normal draws and drop_u[Ns, k] uniform draws are inputs.  Output as route()."""
+    x = _f64(x)
+    Ns, ds = x.shape
+    Wr1, br1, Wr2, br2 = _f64(Wr1), _f64(br1), _f64(Wr2), _f64(br2)
+    Hr, E = Wr2.shape
+    assert Wr1.shape == (ds, Hr) and br1.shape == (Hr,) and br2.shape == (E,)
+    noise = None if noise is None else _f64(noise)
+    drop_u = None if drop_u is None else _f64(drop_u)
+    assert noise is None or noise.shape == (Ns, E)
+    assert drop_u is None or drop_u.shape == (Ns, k)
+    idx = np.empty((Ns, k), dtype=np.int32)
+    pk = np.empty((Ns, k), dtype=np.float64)
+    margin = np.empty((Ns,), dtype=np.float64)
+    logits = np.empty((Ns, E), dtype=np.float64) if want_logits else None
+    rc = lib().oracle_route_train(_p(x), ctypes.c_int64(Ns), ds, Hr, E, k, _p(Wr1), _p(br1), _p(Wr2), _p(br2),
+                                  ctypes.c_double(tau), ctypes.c_double(sigma), _p(noise), ctypes.c_double(rate),
+                                  _p(drop_u), _p(idx), _p(pk), _p(logits), _p(margin))
+    _check(rc, "oracle_route_train")
+    out = {"idx": idx, "pk": pk, "margin": margin}
+    if want_logits:
+        out["logits"] = logits
+    return out
+
+
 def dispatch(idx, E: int, capacity: int = -1):
     """idx[Ns,k] -> dict(counts_raw[E], counts[E], offsets[E+1], perm[Ns*k], inv[Ns*k])."""
     idx = _i32(idx)
@@ -179,6 +206,22 @@ def forward(h, S: int, k: int, weights: dict, capacity: int = -1, act: int = ACT
                               _p(out["perm"]), _p(out["inv"]))
     _check(rc, "oracle_forward")
     return out
+
+
+def forward_train(h, S: int, k: int, weights: dict, tau: float = 1.0, sigma: float = 0.0, noise=None,
+                  rate: float = 0.0, drop_u=None, capacity: int = -1):
+    """Whole layer with the training-time router: route_train, then dispatch, experts and combine as in forward()."""
+    h = _f64(h)
+    T, d = h.shape
+    x = h.reshape(T * S, d // S)
+    r = route_train(x, weights["Wr1"], weights["br1"], weights["Wr2"], weights["br2"], k, tau, sigma, noise, rate,
+                    drop_u, want_logits=True)
+    E = np.asarray(weights["Wr2"]).shape[1]
+    dsp = dispatch(r["idx"], E, capacity)
+    out = slices(x, r["idx"], r["pk"], dsp["inv"], weights["W1"], weights["b1"], weights["W2"], weights["b2"])
+    res = {"h_out": out.reshape(T, d), "idx": r["idx"], "pk": r["pk"], "margin": r["margin"], "logits": r["logits"]}
+    res.update(dsp)
+    return res
 
 
 def load_stats(counts):

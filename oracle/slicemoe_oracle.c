@@ -27,7 +27,9 @@
  *
  * Pins (tests/test_oracle_*.py): brute-force stable sort for top-k and dispatch, count sum,
  * bijection, E=1/k=1 dense-FFN reduction against library matmul+erf, S=1 token-level MoE,
- * W2=0 and identity-activation closed forms, load-statistic closed forms.
+ * W2=0 and identity-activation closed forms, load-statistic closed forms; for the training-time
+ * router: reduction to oracle_route, the power law of the temperature, shift invariance and
+ * planted bumps for the noise, hand-worked dropout cases.
  */
 #include <math.h>
 #include <stdint.h>
@@ -117,6 +119,94 @@ int oracle_route(const double *x, int64_t Ns, int ds, int Hr, int E, int k,
             }
         }
         free(u); free(g); free(p); free(gf); free(taken);
+    }
+    return fail ? -1 : 0;
+}
+
+/*
+ * Training-time routing of every slice: the router of Section 3.1 with the three variations
+ * the paper describes around it, in the order logits -> noise -> top-k and softmax -> dropout.
+ *   - Gaussian logit noise (Section 5, robustness to router noise): g <- g + sigma * noise[n, e],
+ *     added before the softmax, hence also before the selection.  The standard-normal draws
+ *     are an INPUT (noise[Ns, E], may be NULL when sigma == 0).
+ *   - softmax temperature (Appendix B): p = softmax(g / tau) over all E experts.  The selection
+ *     is taken on g itself (dividing by tau > 0 does not change the order), rounded to fp32 as
+ *     in oracle_route.
+ *   - cross-slice dropout (Section 3.3; Appendix A gives the rate 0.2): each of the k selected
+ *     assignments of a slice is dropped independently when its uniform draw drop_u[n, j] is
+ *     below `rate` (draws are an INPUT, compared as fp32 values); the remaining probabilities of
+ *     the slice are renormalised to sum to 1 and the dropped ones are 0.  A slice whose k draws
+ *     would all drop keeps slot 0, its largest, so every slice still reaches an expert.  With
+ *     rate > 0 the renormalisation applies to every slice, dropped from or not.  idx keeps all
+ *     k experts: a dropped assignment stays assigned with probability 0 (by Eq. 1 its expert
+ *     then sees the zero vector).
+ * With tau = 1, sigma = 0 and rate = 0 this is oracle_route.  Outputs as oracle_route; `logits`
+ * receives the noisy logits, `margin` is taken on them.
+ */
+int oracle_route_train(const double *x, int64_t Ns, int ds, int Hr, int E, int k,
+                       const double *Wr1, const double *br1, const double *Wr2, const double *br2,
+                       double tau, double sigma, const double *noise, double rate, const double *drop_u,
+                       int32_t *idx, double *pk, double *logits, double *margin)
+{
+    if (!x || !idx || !pk || Ns < 0 || ds < 1 || Hr < 1 || E < 1 || k < 1 || k > E) return -1;
+    if (!(tau > 0.0) || !(sigma >= 0.0) || !(rate >= 0.0) || !(rate < 1.0)) return -1;
+    if ((sigma > 0.0 && !noise) || (rate > 0.0 && !drop_u)) return -1;
+    int fail = 0;
+#pragma omp parallel
+    {
+        double *u = (double *)malloc(sizeof(double) * (size_t)Hr);
+        double *g = (double *)malloc(sizeof(double) * (size_t)E);
+        double *p = (double *)malloc(sizeof(double) * (size_t)E);
+        float *gf = (float *)malloc(sizeof(float) * (size_t)E);
+        char *taken = (char *)malloc((size_t)E);
+        char *keep = (char *)malloc((size_t)k);
+        if (!u || !g || !p || !gf || !taken || !keep) {
+#pragma omp atomic write
+            fail = 1;
+        } else {
+#pragma omp for schedule(static)
+            for (int64_t n = 0; n < Ns; ++n) {
+                router_logits(x + n * ds, ds, Hr, E, Wr1, br1, Wr2, br2, u, g);
+                if (sigma > 0.0)
+                    for (int e = 0; e < E; ++e) g[e] += sigma * noise[n * E + e];
+                if (logits) memcpy(logits + n * E, g, sizeof(double) * (size_t)E);
+                /* softmax of g / tau over all E experts */
+                double m = g[0];
+                for (int e = 1; e < E; ++e) m = g[e] > m ? g[e] : m;
+                double den = 0.0;
+                for (int e = 0; e < E; ++e) { p[e] = exp((g[e] - m) / tau); den += p[e]; }
+                for (int e = 0; e < E; ++e) p[e] /= den;
+                /* top-k on the fp32-rounded (noisy) logits, lowest index on ties */
+                for (int e = 0; e < E; ++e) { gf[e] = (float)g[e]; taken[e] = 0; }
+                for (int j = 0; j < k; ++j) {
+                    int best = -1;
+                    for (int e = 0; e < E; ++e)
+                        if (!taken[e] && (best < 0 || gf[e] > gf[best])) best = e;
+                    taken[best] = 1;
+                    idx[n * k + j] = best;
+                    pk[n * k + j] = p[best];
+                }
+                if (margin) {
+                    int rest = -1;
+                    for (int e = 0; e < E; ++e)
+                        if (!taken[e] && (rest < 0 || gf[e] > gf[rest])) rest = e;
+                    margin[n] = rest < 0 ? INFINITY
+                                         : (double)gf[idx[n * k + k - 1]] - (double)gf[rest];
+                }
+                if (rate > 0.0) {
+                    int kept = 0;
+                    for (int j = 0; j < k; ++j) {
+                        keep[j] = !((float)drop_u[n * k + j] < (float)rate);
+                        kept += keep[j];
+                    }
+                    if (kept == 0) keep[0] = 1;
+                    double sum = 0.0;
+                    for (int j = 0; j < k; ++j) if (keep[j]) sum += pk[n * k + j];
+                    for (int j = 0; j < k; ++j) pk[n * k + j] = keep[j] ? pk[n * k + j] / sum : 0.0;
+                }
+            }
+        }
+        free(u); free(g); free(p); free(gf); free(taken); free(keep);
     }
     return fail ? -1 : 0;
 }

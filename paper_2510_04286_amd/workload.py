@@ -1,7 +1,7 @@
 """Seeded synthetic inputs for the SliceMoE layer forward pass.
 
 This module only *draws inputs* (hidden states, router and expert weights, random
-top-k index tables).  It contains none of the layer's arithmetic (no router, no
+top-k index tables, and the random draws a training-time router consumes).  It contains none of the layer's arithmetic (no router, no
 softmax, no expert FFN, no dispatch), so the CPU oracle and the HIP path can both be
 fed from it without sharing any code of the method.
 
@@ -31,7 +31,7 @@ _M2 = np.uint64(0x94D049BB133111EB)
 H_R = 256  # router hidden width (Section 3.1, Appendix A)
 
 # tensor ids (streams) of the generator
-TID_H, TID_WR1, TID_BR1, TID_WR2, TID_BR2, TID_W1, TID_B1, TID_W2, TID_B2, TID_IDX = range(10)
+TID_H, TID_WR1, TID_BR1, TID_WR2, TID_BR2, TID_W1, TID_B1, TID_W2, TID_B2, TID_IDX, TID_NOISE, TID_DROP = range(12)
 
 
 @dataclass(frozen=True)
@@ -219,3 +219,12 @@ def make_topk_idx(Ns: int, k: int, E: int, seed: int = 2, zipf_s: float = 0.0) -
         key = np.log(w)[None, :] - np.log(-np.log(np.clip(u, 1e-300, 1 - 1e-16)))
         out[a:b] = np.argsort(-key, axis=1, kind="stable")[:, :k].astype(np.int32)
     return out
+
+
+def make_router_draws(cfg: SliceMoEShape, seed: int = 2) -> tuple:
+    """The random numbers a training-time router consumes, as inputs: standard normals noise[Ns, E] for the logit noise
+    (Section 5) and uniforms drop_u[Ns, k] in [0, 1) for the cross-slice dropout (Section 3.3), both fp32."""
+    noise = normal(seed, TID_NOISE, 0, cfg.Ns * cfg.E).astype(np.float32).reshape(cfg.Ns, cfg.E)
+    drop_u = uniform01(seed, TID_DROP, 0, cfg.Na).astype(np.float32).reshape(cfg.Ns, cfg.k)
+    drop_u = np.minimum(drop_u, np.float32(1.0 - 2.0 ** -24))   # rounding to fp32 must not reach 1
+    return noise, drop_u
