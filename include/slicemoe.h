@@ -140,6 +140,33 @@ slicemoe_status slicemoe_route(const slicemoe_config *cfg, const void *h, const 
                                void *workspace, size_t workspace_bytes, slicemoe_stream_t stream);
 
 /*
+ * Training-time router: slicemoe_route with the variations the paper describes around it, applied in the order
+ * logits -> noise -> top-k and softmax -> dropout.
+ *   temperature  tau > 0 (Appendix B; default 1): p = softmax(g / tau).  The selection does not depend on it.
+ *   noise_std    sigma >= 0 (Section 5, robustness to router noise): g <- g + sigma * noise[n, e] before the
+ *                softmax, hence also before the selection.
+ *   dropout_rate r in [0, 1) (Section 3.3, cross-slice dropout; Appendix A uses 0.2): selected assignment j of slice
+ *                n is dropped when drop_u[n, j] < r; the slice's remaining probabilities are renormalised to sum to 1
+ *                and the dropped ones become 0; if all k would drop, slot 0 is kept.  With r > 0 every slice is
+ *                renormalised.  topk_idx keeps all k experts: a dropped assignment stays assigned with probability
+ *                0, so by Eq. 1 its expert sees the zero vector.
+ * The random draws are INPUTS, so a run is reproducible from its arguments alone:
+ *   noise  [T*S, E] float, standard-normal draws, 16-byte aligned; read only when noise_std > 0 (may be NULL otherwise)
+ *   drop_u [T*S, k] float, uniform draws in [0, 1); read only when dropout_rate > 0 (may be NULL otherwise)
+ * Other arguments, layouts and workspace as slicemoe_route.  INVALID_ARG for params == NULL, a parameter outside its
+ * range (or NaN / infinite), or a table the parameters need that is NULL or misaligned.
+ */
+typedef struct {
+    float temperature;
+    float noise_std;
+    float dropout_rate;
+} slicemoe_route_train_params;
+slicemoe_status slicemoe_route_train(const slicemoe_config *cfg, const void *h, const slicemoe_weights *w,
+                                     const slicemoe_route_train_params *params, const float *noise,
+                                     const float *drop_u, int32_t *topk_idx, float *topk_p,
+                                     void *workspace, size_t workspace_bytes, slicemoe_stream_t stream);
+
+/*
  * Dispatch (the grouping of Section 3.4): stable counting sort of assignments by expert.
  *   topk_idx   [T*S, k] in, values in [0, E) (out-of-range values are clamped, never faulted on)
  *   counts_raw [E]      out: assignments per expert (the counts of Eq. 2)
@@ -197,6 +224,16 @@ slicemoe_status slicemoe_load_stats(const slicemoe_config *cfg, const int32_t *c
 slicemoe_status slicemoe_forward(const slicemoe_config *cfg, const void *h, const slicemoe_weights *w,
                                  void *h_out, void *workspace, size_t workspace_bytes,
                                  slicemoe_stream_t stream);
+
+/*
+ * Whole layer with the training-time router: slicemoe_forward with slicemoe_route_train in place of slicemoe_route
+ * (same parameters and tables of draws); dispatch, expert FFN (Eq. 1 with the dropped-and-renormalised probabilities)
+ * and combine are unchanged.
+ */
+slicemoe_status slicemoe_forward_train(const slicemoe_config *cfg, const void *h, const slicemoe_weights *w,
+                                       const slicemoe_route_train_params *params, const float *noise,
+                                       const float *drop_u, void *h_out, void *workspace, size_t workspace_bytes,
+                                       slicemoe_stream_t stream);
 
 /*
  * Measurement aid (not a step of the layer): runs `nblocks` blocks of 256 threads, each doing `iters`

@@ -29,6 +29,7 @@ EXPORTS = [
     "slicemoe_dispatch_workspace_bytes", "slicemoe_get_workspace_layout", "slicemoe_packed_bytes",
     "slicemoe_pack_weights", "slicemoe_route", "slicemoe_dispatch", "slicemoe_expert_ffn",
     "slicemoe_combine", "slicemoe_load_stats", "slicemoe_forward", "slicemoe_probe_clock",
+    "slicemoe_route_train", "slicemoe_forward_train",
 ]
 
 
@@ -46,6 +47,10 @@ class slicemoe_config(ctypes.Structure):
 
 class slicemoe_weights(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in ("Wr1", "br1", "Wr2", "br2", "W1", "b1", "W2", "b2", "packed")]
+
+
+class slicemoe_route_train_params(ctypes.Structure):
+    _fields_ = [("temperature", ctypes.c_float), ("noise_std", ctypes.c_float), ("dropout_rate", ctypes.c_float)]
 
 
 class slicemoe_workspace_layout(ctypes.Structure):
@@ -91,6 +96,11 @@ def lib() -> ctypes.CDLL:
         L.slicemoe_forward.argtypes = [cfgp, vp, wp, vp, vp, st, vp]
         L.slicemoe_probe_clock.restype = ctypes.c_int
         L.slicemoe_probe_clock.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, vp]
+        tpp = ctypes.POINTER(slicemoe_route_train_params)
+        L.slicemoe_route_train.restype = ctypes.c_int
+        L.slicemoe_route_train.argtypes = [cfgp, vp, wp, tpp, vp, vp, vp, vp, vp, st, vp]
+        L.slicemoe_forward_train.restype = ctypes.c_int
+        L.slicemoe_forward_train.argtypes = [cfgp, vp, wp, tpp, vp, vp, vp, vp, st, vp]
         _lib = L
     return _lib
 
@@ -251,6 +261,36 @@ def slicemoe_forward(cfg, h, w, h_out, workspace, stream=None):
     _check(lib().slicemoe_forward(ctypes.byref(cfg), _ptr(h, _tdtype(cfg), cfg.T * cfg.d, "h"), ctypes.byref(ws),
                                   _ptr(h_out, _tdtype(cfg), cfg.T * cfg.d, "h_out"), wsp, wsb, _stream(stream)),
            "slicemoe_forward")
+
+
+def _train_args(cfg, temperature, noise_std, dropout_rate, noise, drop_u):
+    tp = slicemoe_route_train_params(temperature, noise_std, dropout_rate)
+    Ns = cfg.T * cfg.S
+    npt = None if noise is None else _ptr(noise, torch.float32, Ns * cfg.E, "noise")
+    upt = None if drop_u is None else _ptr(drop_u, torch.float32, Ns * cfg.k, "drop_u")
+    return tp, npt, upt
+
+
+def slicemoe_route_train(cfg, h, w, topk_idx, topk_p, temperature=1.0, noise_std=0.0, dropout_rate=0.0, noise=None,
+                         drop_u=None, workspace=None, stream=None):
+    Ns = cfg.T * cfg.S
+    wsp, wsb = _ws(workspace)
+    ws = _weights(cfg, w)
+    tp, npt, upt = _train_args(cfg, temperature, noise_std, dropout_rate, noise, drop_u)
+    _check(lib().slicemoe_route_train(ctypes.byref(cfg), _ptr(h, _tdtype(cfg), cfg.T * cfg.d, "h"), ctypes.byref(ws),
+                                      ctypes.byref(tp), npt, upt, _ptr(topk_idx, torch.int32, Ns * cfg.k, "topk_idx"),
+                                      _ptr(topk_p, torch.float32, Ns * cfg.k, "topk_p"), wsp, wsb, _stream(stream)),
+           "slicemoe_route_train")
+
+
+def slicemoe_forward_train(cfg, h, w, h_out, workspace, temperature=1.0, noise_std=0.0, dropout_rate=0.0, noise=None,
+                           drop_u=None, stream=None):
+    wsp, wsb = _ws(workspace)
+    ws = _weights(cfg, w)
+    tp, npt, upt = _train_args(cfg, temperature, noise_std, dropout_rate, noise, drop_u)
+    _check(lib().slicemoe_forward_train(ctypes.byref(cfg), _ptr(h, _tdtype(cfg), cfg.T * cfg.d, "h"), ctypes.byref(ws),
+                                        ctypes.byref(tp), npt, upt, _ptr(h_out, _tdtype(cfg), cfg.T * cfg.d, "h_out"),
+                                        wsp, wsb, _stream(stream)), "slicemoe_forward_train")
 
 
 def slicemoe_probe_clock(cycles_and_ticks, nblocks: int, iters: int, stream=None):

@@ -220,23 +220,65 @@ slicemoe_status slicemoe_pack_weights(const slicemoe_config *cfg, const slicemoe
     return launch_pack(*cfg, *w, packed_out, (hipStream_t)stream) == hipSuccess ? SLICEMOE_OK : SLICEMOE_ERR_HIP;
 }
 
+// Router variant from the caller's training parameters; INVALID_ARG when a parameter is out of range or a table of
+// draws that the parameters ask for is missing or misaligned.
+static slicemoe_status make_route_variant(const slicemoe_route_train_params *tp, const float *noise, const float *drop_u,
+                                          RouteVariant *v)
+{
+    if (!tp) return SLICEMOE_ERR_INVALID_ARG;
+    if (!(tp->temperature > 0.f) || isinf(tp->temperature)) return SLICEMOE_ERR_INVALID_ARG;
+    if (!(tp->noise_std >= 0.f) || isinf(tp->noise_std)) return SLICEMOE_ERR_INVALID_ARG;
+    if (!(tp->dropout_rate >= 0.f) || !(tp->dropout_rate < 1.f)) return SLICEMOE_ERR_INVALID_ARG;
+    if (tp->noise_std > 0.f && (!noise || misaligned(noise, 16))) return SLICEMOE_ERR_INVALID_ARG;
+    if (tp->dropout_rate > 0.f && !drop_u) return SLICEMOE_ERR_INVALID_ARG;
+    v->inv_tau = 1.f / tp->temperature;
+    v->sigma = tp->noise_std;
+    v->noise = noise;
+    return SLICEMOE_OK;
+}
+
+static slicemoe_status route_common(const slicemoe_config *cfg, const void *h, const slicemoe_weights *w,
+                                    const RouteVariant &v, const float *drop_u, float rate, int32_t *topk_idx,
+                                    float *topk_p, void *workspace, size_t workspace_bytes, hipStream_t s)
+{
+    if (!w || !topk_idx || !topk_p || (!h && cfg->T > 0)) return SLICEMOE_ERR_INVALID_ARG;
+    if (misaligned(h, 16)) return SLICEMOE_ERR_INVALID_ARG;
+    hipError_t e;
+    if (use_mfma(*cfg)) {
+        const void *packed = nullptr;
+        const slicemoe_status ps = resolve_packed(*cfg, *w, workspace, workspace_bytes, s, &packed);
+        if (ps != SLICEMOE_OK) return ps;
+        e = launch_route_mfma(*cfg, h, packed, topk_idx, topk_p, s, v);
+    } else {
+        if (!logical_weights_ok(*w, true, false)) return SLICEMOE_ERR_INVALID_ARG;
+        e = launch_route_generic(*cfg, h, *w, topk_idx, topk_p, s, v);
+    }
+    if (e == hipSuccess && rate > 0.f) e = launch_route_dropout(*cfg, topk_p, drop_u, rate, s);
+    return e == hipSuccess ? SLICEMOE_OK : SLICEMOE_ERR_HIP;
+}
+
 slicemoe_status slicemoe_route(const slicemoe_config *cfg, const void *h, const slicemoe_weights *w,
                                int32_t *topk_idx, float *topk_p, void *workspace, size_t workspace_bytes,
                                slicemoe_stream_t stream)
 {
     const slicemoe_status st = validate(cfg);
     if (st != SLICEMOE_OK) return st;
-    if (!w || !topk_idx || !topk_p || (!h && cfg->T > 0)) return SLICEMOE_ERR_INVALID_ARG;
-    if (misaligned(h, 16)) return SLICEMOE_ERR_INVALID_ARG;
-    hipStream_t s = (hipStream_t)stream;
-    if (use_mfma(*cfg)) {
-        const void *packed = nullptr;
-        const slicemoe_status ps = resolve_packed(*cfg, *w, workspace, workspace_bytes, s, &packed);
-        if (ps != SLICEMOE_OK) return ps;
-        return launch_route_mfma(*cfg, h, packed, topk_idx, topk_p, s) == hipSuccess ? SLICEMOE_OK : SLICEMOE_ERR_HIP;
-    }
-    if (!logical_weights_ok(*w, true, false)) return SLICEMOE_ERR_INVALID_ARG;
-    return launch_route_generic(*cfg, h, *w, topk_idx, topk_p, s) == hipSuccess ? SLICEMOE_OK : SLICEMOE_ERR_HIP;
+    return route_common(cfg, h, w, RouteVariant(), nullptr, 0.f, topk_idx, topk_p, workspace, workspace_bytes,
+                        (hipStream_t)stream);
+}
+
+slicemoe_status slicemoe_route_train(const slicemoe_config *cfg, const void *h, const slicemoe_weights *w,
+                                     const slicemoe_route_train_params *params, const float *noise, const float *drop_u,
+                                     int32_t *topk_idx, float *topk_p, void *workspace, size_t workspace_bytes,
+                                     slicemoe_stream_t stream)
+{
+    const slicemoe_status st = validate(cfg);
+    if (st != SLICEMOE_OK) return st;
+    RouteVariant v;
+    const slicemoe_status vs = make_route_variant(params, noise, drop_u, &v);
+    if (vs != SLICEMOE_OK) return vs;
+    return route_common(cfg, h, w, v, drop_u, params->dropout_rate, topk_idx, topk_p, workspace, workspace_bytes,
+                        (hipStream_t)stream);
 }
 
 slicemoe_status slicemoe_dispatch(const slicemoe_config *cfg, const int32_t *topk_idx, int32_t *counts_raw,
@@ -294,11 +336,10 @@ slicemoe_status slicemoe_load_stats(const slicemoe_config *cfg, const int32_t *c
                                                                                                  : SLICEMOE_ERR_HIP;
 }
 
-slicemoe_status slicemoe_forward(const slicemoe_config *cfg, const void *h, const slicemoe_weights *w, void *h_out,
-                                 void *workspace, size_t workspace_bytes, slicemoe_stream_t stream)
+static slicemoe_status forward_common(const slicemoe_config *cfg, const void *h, const slicemoe_weights *w,
+                                      const RouteVariant &v, const float *drop_u, float rate, void *h_out,
+                                      void *workspace, size_t workspace_bytes, slicemoe_stream_t stream)
 {
-    const slicemoe_status st = validate(cfg);
-    if (st != SLICEMOE_OK) return st;
     if (!w || ((!h || !h_out) && cfg->T > 0)) return SLICEMOE_ERR_INVALID_ARG;
     if (misaligned(h, 16) || misaligned(h_out, 16)) return SLICEMOE_ERR_INVALID_ARG;
     slicemoe_workspace_layout L;
@@ -324,8 +365,12 @@ slicemoe_status slicemoe_forward(const slicemoe_config *cfg, const void *h, cons
         const slicemoe_status ps = resolve_packed(*cfg, *w, workspace, workspace_bytes, s, &packed);
         if (ps != SLICEMOE_OK) return ps;
     }
-    hipError_t e = mfma ? launch_route_mfma(*cfg, h, packed, idx, p, s) : launch_route_generic(*cfg, h, *w, idx, p, s);
+    hipError_t e = mfma ? launch_route_mfma(*cfg, h, packed, idx, p, s, v) : launch_route_generic(*cfg, h, *w, idx, p, s, v);
     if (e != hipSuccess) return SLICEMOE_ERR_HIP;
+    if (rate > 0.f) {
+        e = launch_route_dropout(*cfg, p, drop_u, rate, s);
+        if (e != hipSuccess) return SLICEMOE_ERR_HIP;
+    }
     // the load statistics ride along in the scan kernel of the dispatch
     e = launch_dispatch(*cfg, idx, counts_raw, counts, offsets, perm, inv, (int32_t *)(ws + L.scratch), stats, s);
     if (e != hipSuccess) return SLICEMOE_ERR_HIP;
@@ -334,6 +379,27 @@ slicemoe_status slicemoe_forward(const slicemoe_config *cfg, const void *h, cons
     if (e != hipSuccess) return SLICEMOE_ERR_HIP;
     e = launch_combine(*cfg, y, inv, h_out, s);
     return e == hipSuccess ? SLICEMOE_OK : SLICEMOE_ERR_HIP;
+}
+
+slicemoe_status slicemoe_forward(const slicemoe_config *cfg, const void *h, const slicemoe_weights *w, void *h_out,
+                                 void *workspace, size_t workspace_bytes, slicemoe_stream_t stream)
+{
+    const slicemoe_status st = validate(cfg);
+    if (st != SLICEMOE_OK) return st;
+    return forward_common(cfg, h, w, RouteVariant(), nullptr, 0.f, h_out, workspace, workspace_bytes, stream);
+}
+
+slicemoe_status slicemoe_forward_train(const slicemoe_config *cfg, const void *h, const slicemoe_weights *w,
+                                       const slicemoe_route_train_params *params, const float *noise,
+                                       const float *drop_u, void *h_out, void *workspace, size_t workspace_bytes,
+                                       slicemoe_stream_t stream)
+{
+    const slicemoe_status st = validate(cfg);
+    if (st != SLICEMOE_OK) return st;
+    RouteVariant v;
+    const slicemoe_status vs = make_route_variant(params, noise, drop_u, &v);
+    if (vs != SLICEMOE_OK) return vs;
+    return forward_common(cfg, h, w, v, drop_u, params->dropout_rate, h_out, workspace, workspace_bytes, stream);
 }
 
 slicemoe_status slicemoe_probe_clock(uint64_t *cycles_and_ticks, int32_t nblocks, int32_t iters, slicemoe_stream_t stream)

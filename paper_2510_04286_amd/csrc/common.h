@@ -85,10 +85,19 @@ constexpr int kDispItems = 4;
 constexpr int kDispChunk = kDispThreads * kDispItems;  // assignments per block
 
 // ---- kernel launchers (each only enqueues; returns hipGetLastError) --------------------
+// Training-time variations of the router (softmax temperature: Appendix B; Gaussian logit noise: Section 5); the
+// defaults are the inference router.
+struct RouteVariant {
+    float inv_tau = 1.f;             // softmax of g / tau
+    float sigma = 0.f;               // g += sigma * noise[n, e] before the selection and the softmax
+    const float *noise = nullptr;    // [Ns, E] standard-normal draws; read only when sigma > 0
+};
 hipError_t launch_route_generic(const slicemoe_config &c, const void *h, const slicemoe_weights &w,
-                                int32_t *idx, float *p, hipStream_t s);
+                                int32_t *idx, float *p, hipStream_t s, const RouteVariant &v = RouteVariant());
 hipError_t launch_route_mfma(const slicemoe_config &c, const void *h, const void *packed,
-                             int32_t *idx, float *p, hipStream_t s);
+                             int32_t *idx, float *p, hipStream_t s, const RouteVariant &v = RouteVariant());
+// Cross-slice dropout (Section 3.3) on the selected probabilities p[Ns, k], in place.
+hipError_t launch_route_dropout(const slicemoe_config &c, float *p, const float *drop_u, float rate, hipStream_t s);
 hipError_t launch_dispatch(const slicemoe_config &c, const int32_t *idx, int32_t *counts_raw,
                            int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv,
                            int32_t *block_counts, float *stats /* nullable */, hipStream_t s);

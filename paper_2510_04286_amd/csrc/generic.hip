@@ -15,7 +15,7 @@ template <typename T>
 __global__ __launch_bounds__(kGenThreads) void route_generic_kernel(
     const T *__restrict__ x, long long Ns, int ds, int Hr, int E, int k,
     const T *__restrict__ Wr1, const T *__restrict__ br1, const T *__restrict__ Wr2, const T *__restrict__ br2,
-    int32_t *__restrict__ idx, float *__restrict__ pk)
+    const float *__restrict__ noise, float sigma, float inv_tau, int32_t *__restrict__ idx, float *__restrict__ pk)
 {
     extern __shared__ float smem[];
     float *xs = smem;                 // [kRB][ds]
@@ -48,6 +48,8 @@ __global__ __launch_bounds__(kGenThreads) void route_generic_kernel(
         const int r = t / E, e = t - r * E;
         float acc = Storage<T>::load(br2 + e);
         for (int j = 0; j < Hr; ++j) acc = fmaf(us[r * Hr + j], Storage<T>::load(Wr2 + (size_t)j * E + e), acc);
+        // training-time logit noise (Section 5): before the selection and the softmax
+        if (noise != nullptr && r < rows) acc = fmaf(sigma, noise[(n0 + r) * E + e], acc);
         gs[t] = acc;
     }
     __syncthreads();
@@ -56,7 +58,7 @@ __global__ __launch_bounds__(kGenThreads) void route_generic_kernel(
         float m = g[0];
         for (int e = 1; e < E; ++e) m = fmaxf(m, g[e]);
         float den = 0.f;
-        for (int e = 0; e < E; ++e) den += expf(g[e] - m);
+        for (int e = 0; e < E; ++e) den += expf((g[e] - m) * inv_tau);   // softmax of g / tau (Appendix B)
         const long long n = n0 + tid;
         for (int j = 0; j < k; ++j) {
             int best = 0;
@@ -67,7 +69,7 @@ __global__ __launch_bounds__(kGenThreads) void route_generic_kernel(
                     best = e;
                 }
             idx[n * k + j] = best;
-            pk[n * k + j] = expf(bv - m) / den;
+            pk[n * k + j] = expf((bv - m) * inv_tau) / den;
             g[best] = -INFINITY;
         }
     }
@@ -132,21 +134,60 @@ __global__ __launch_bounds__(kGenThreads) void ffn_generic_kernel(
 }
 
 hipError_t launch_route_generic(const slicemoe_config &c, const void *h, const slicemoe_weights &w,
-                                int32_t *idx, float *p, hipStream_t s)
+                                int32_t *idx, float *p, hipStream_t s, const RouteVariant &v)
 {
     const long long Ns = (long long)c.T * c.S;
     if (Ns == 0) return hipSuccess;
     const int ds = c.d / c.S;
     const int blocks = (int)((Ns + kRB - 1) / kRB);
+    const float *noise = v.sigma > 0.f ? v.noise : nullptr;
     const size_t smem = sizeof(float) * (size_t)kRB * (ds + c.Hr + c.E);
     if (c.dtype == SLICEMOE_BF16)
         route_generic_kernel<bf16_t><<<blocks, kGenThreads, smem, s>>>(
             (const bf16_t *)h, Ns, ds, c.Hr, c.E, c.k, (const bf16_t *)w.Wr1, (const bf16_t *)w.br1,
-            (const bf16_t *)w.Wr2, (const bf16_t *)w.br2, idx, p);
+            (const bf16_t *)w.Wr2, (const bf16_t *)w.br2, noise, v.sigma, v.inv_tau, idx, p);
     else
         route_generic_kernel<float><<<blocks, kGenThreads, smem, s>>>(
             (const float *)h, Ns, ds, c.Hr, c.E, c.k, (const float *)w.Wr1, (const float *)w.br1,
-            (const float *)w.Wr2, (const float *)w.br2, idx, p);
+            (const float *)w.Wr2, (const float *)w.br2, noise, v.sigma, v.inv_tau, idx, p);
+    return hipGetLastError();
+}
+
+// Cross-slice dropout (Section 3.3): assignment j of a slice is dropped when its uniform draw is below the rate; the
+// remaining probabilities are renormalised to sum to 1, the dropped ones are 0.  A slice whose draws would drop all k
+// keeps slot 0.  One thread per slice; k <= 8.
+__global__ __launch_bounds__(256) void route_dropout_kernel(float *__restrict__ pk, const float *__restrict__ drop_u,
+                                                            long long Ns, int k, float rate)
+{
+    const long long n = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= Ns) return;
+    float p[8];
+    bool keep[8];
+    int kept = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        p[j] = 0.f;
+        keep[j] = false;
+        if (j < k) {
+            p[j] = pk[n * k + j];
+            keep[j] = !(drop_u[n * k + j] < rate);
+            kept += keep[j] ? 1 : 0;
+        }
+    }
+    if (kept == 0) keep[0] = true;
+    float sum = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) sum += keep[j] ? p[j] : 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+        if (j < k) pk[n * k + j] = keep[j] ? p[j] / sum : 0.f;
+}
+
+hipError_t launch_route_dropout(const slicemoe_config &c, float *p, const float *drop_u, float rate, hipStream_t s)
+{
+    const long long Ns = (long long)c.T * c.S;
+    if (Ns == 0 || !(rate > 0.f)) return hipSuccess;
+    route_dropout_kernel<<<(int)((Ns + 255) / 256), 256, 0, s>>>(p, drop_u, Ns, c.k, rate);
     return hipGetLastError();
 }
 

@@ -32,8 +32,8 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 template <int DS, int ET, int THREADS, bool W1_LDS>
 __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
     const bf16_t *__restrict__ x, long long Ns, int E, int k, const char *__restrict__ packed,
-    size_t off_w1, size_t off_b1, size_t off_b2, int32_t *__restrict__ idx,
-    float *__restrict__ pk)
+    size_t off_w1, size_t off_b1, size_t off_b2, const float *__restrict__ noise, float sigma, float exp_scale,
+    int32_t *__restrict__ idx, float *__restrict__ pk)
 {
     constexpr int KS = SliceTiles<DS>::KS;
     constexpr int HT = kRouteHT;
@@ -147,6 +147,30 @@ __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
         for (int et = 0; et < ET; ++et)
 #pragma unroll
             for (int r = 0; r < 16; ++r) v[et * 16 + r] = gacc[et][r];
+        if (noise != nullptr) {   // training-time logit noise: g += sigma * draw, before the selection and the softmax
+            const float *nr = noise + (valid ? n : 0) * E;
+            if ((E & 3) == 0) {   // rows of the table are 16-byte aligned: this lane's four consecutive experts at once
+#pragma unroll
+                for (int et = 0; et < ET; ++et)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int e0 = et * 32 + 8 * q + 4 * g;
+                        if (e0 < E) {
+                            const f32x4 z = *(const f32x4 *)(nr + e0);
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) v[et * 16 + 4 * q + c] = fmaf(sigma, z[c], v[et * 16 + 4 * q + c]);
+                        }
+                    }
+            } else {
+#pragma unroll
+                for (int et = 0; et < ET; ++et)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int e = et * 32 + acc_feature(r, g);
+                        if (e < E) v[et * 16 + r] = fmaf(sigma, nr[e], v[et * 16 + r]);
+                    }
+            }
+        }
         if (E != ET * 32) {   // padded experts never win
 #pragma unroll
             for (int et = 0; et < ET; ++et)
@@ -158,8 +182,9 @@ __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
 #pragma unroll
         for (int i = 1; i < ET * 16; ++i) m = fmaxf(m, v[i]);
         m = fmaxf(m, __shfl_xor(m, 32));
-        // softmax denominator: exp(v - m) = exp2(v * log2(e) - m * log2(e)), one multiply-add and one exp2 per logit
-        constexpr float kLog2e = 1.4426950408889634f;
+        // softmax denominator: exp((v - m) / tau) = exp2(v * c - m * c) with c = log2(e) / tau, one multiply-add and
+        // one exp2 per logit
+        const float kLog2e = exp_scale;
         const float nm = -m * kLog2e;
         float den = 0.f;
 #pragma unroll
@@ -201,7 +226,7 @@ __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
 
 template <int DS, int ET, int THREADS, bool W1_LDS = true>
 static hipError_t run_route(const slicemoe_config &c, const void *h, const void *packed, int32_t *idx, float *p,
-                            hipStream_t s)
+                            hipStream_t s, const RouteVariant &v)
 {
     const PackedLayout L = packed_layout(c);
     const long long Ns = (long long)c.T * c.S;
@@ -217,29 +242,29 @@ static hipError_t run_route(const slicemoe_config &c, const void *h, const void 
     if (err != hipSuccess) return err;
     if (L.r_w2 != L.r_w1 + (size_t)kRouteHT * KS * 64 * 16) return hipErrorInvalidValue;   // the kernel copies W1 | W2 as one run
     kern<<<(int)blocks, THREADS, lds, s>>>((const bf16_t *)h, Ns, c.E, c.k, (const char *)packed, L.r_w1, L.r_b1, L.r_b2,
-                                           idx, p);
+                                           v.sigma > 0.f ? v.noise : nullptr, v.sigma, 1.4426950408889634f * v.inv_tau, idx, p);
     return hipGetLastError();
 }
 
 hipError_t launch_route_mfma(const slicemoe_config &c, const void *h, const void *packed, int32_t *idx,
-                             float *p, hipStream_t s)
+                             float *p, hipStream_t s, const RouteVariant &v)
 {
     if ((long long)c.T * c.S == 0) return hipSuccess;
     const int ds = c.d / c.S;
     const int et = (c.E + 31) / 32;
     if (ds == 24)   // two K-steps, the second half zeros
-        return et == 1 ? run_route<24, 1, 1024>(c, h, packed, idx, p, s) : run_route<24, 2, 512>(c, h, packed, idx, p, s);
+        return et == 1 ? run_route<24, 1, 1024>(c, h, packed, idx, p, s, v) : run_route<24, 2, 512>(c, h, packed, idx, p, s, v);
     if (ds == 48)
-        return et == 1 ? run_route<48, 1, 1024>(c, h, packed, idx, p, s) : run_route<48, 2, 512>(c, h, packed, idx, p, s);
+        return et == 1 ? run_route<48, 1, 1024>(c, h, packed, idx, p, s, v) : run_route<48, 2, 512>(c, h, packed, idx, p, s, v);
     if (ds == 64)
-        return et == 1 ? run_route<64, 1, 1024>(c, h, packed, idx, p, s) : run_route<64, 2, 512>(c, h, packed, idx, p, s);
+        return et == 1 ? run_route<64, 1, 1024>(c, h, packed, idx, p, s, v) : run_route<64, 2, 512>(c, h, packed, idx, p, s, v);
     if (ds == 96)   // the slice width of the paper's own configuration (d = 768, S = 8): six K-steps
-        return et == 1 ? run_route<96, 1, 512>(c, h, packed, idx, p, s) : run_route<96, 2, 512>(c, h, packed, idx, p, s);
+        return et == 1 ? run_route<96, 1, 512>(c, h, packed, idx, p, s, v) : run_route<96, 2, 512>(c, h, packed, idx, p, s, v);
     if (ds == 192)
-        return et == 1 ? run_route<192, 1, 512>(c, h, packed, idx, p, s) : run_route<192, 2, 512>(c, h, packed, idx, p, s);
+        return et == 1 ? run_route<192, 1, 512>(c, h, packed, idx, p, s, v) : run_route<192, 2, 512>(c, h, packed, idx, p, s, v);
     if (ds == 384)
-        return et == 1 ? run_route<384, 1, 256, false>(c, h, packed, idx, p, s) : run_route<384, 2, 256, false>(c, h, packed, idx, p, s);
-    return et == 1 ? run_route<128, 1, 512>(c, h, packed, idx, p, s) : run_route<128, 2, 512>(c, h, packed, idx, p, s);
+        return et == 1 ? run_route<384, 1, 256, false>(c, h, packed, idx, p, s, v) : run_route<384, 2, 256, false>(c, h, packed, idx, p, s, v);
+    return et == 1 ? run_route<128, 1, 512>(c, h, packed, idx, p, s, v) : run_route<128, 2, 512>(c, h, packed, idx, p, s, v);
 }
 
 }  // namespace slicemoe

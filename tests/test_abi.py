@@ -71,6 +71,37 @@ def test_config_validation_and_kernel_choice(B):
     assert L.slicemoe_dispatch(ctypes.byref(ok), one, one, one, one, one, one, one, 16, None) == B.SLICEMOE_ERR_WORKSPACE
 
 
+def test_train_router_parameter_checks(B):
+    """Out-of-range parameters and missing tables of draws are INVALID_ARG before anything touches the GPU."""
+    L = B.lib()
+    ok = B.make_config(64, 1024, 16, 2, 32, 256)
+    w = B.slicemoe_weights()
+    one = ctypes.c_void_p(256)   # never dereferenced
+    odd = ctypes.c_void_p(260)   # not 16-byte aligned
+
+    def route(tp, noise, drop_u):
+        return L.slicemoe_route_train(ctypes.byref(ok), one, ctypes.byref(w), tp, noise, drop_u, one, one, None, 0, None)
+
+    def forward(tp, noise, drop_u):
+        return L.slicemoe_forward_train(ctypes.byref(ok), one, ctypes.byref(w), tp, noise, drop_u, one, one, 0, None)
+
+    P = B.slicemoe_route_train_params
+    for call in (route, forward):
+        assert call(None, None, None) == B.SLICEMOE_ERR_INVALID_ARG
+        for bad in (P(0.0, 0.0, 0.0), P(-1.0, 0.0, 0.0), P(float("nan"), 0.0, 0.0), P(float("inf"), 0.0, 0.0),
+                    P(1.0, -0.1, 0.0), P(1.0, float("nan"), 0.0), P(1.0, 0.0, 1.0), P(1.0, 0.0, -0.1),
+                    P(1.0, 0.0, float("nan"))):
+            assert call(ctypes.byref(bad), one, one) == B.SLICEMOE_ERR_INVALID_ARG
+        assert call(ctypes.byref(P(1.0, 0.5, 0.0)), None, None) == B.SLICEMOE_ERR_INVALID_ARG   # noise table missing
+        assert call(ctypes.byref(P(1.0, 0.5, 0.0)), odd, None) == B.SLICEMOE_ERR_INVALID_ARG    # misaligned
+        assert call(ctypes.byref(P(1.0, 0.0, 0.2)), None, None) == B.SLICEMOE_ERR_INVALID_ARG   # drop_u missing
+    # valid parameters get as far as the workspace check of the whole-layer call
+    assert forward(ctypes.byref(P(0.7, 0.5, 0.2)), one, one) == B.SLICEMOE_ERR_WORKSPACE
+    bad_cfg = B.make_config(8, 100, 3, 2, 4, 16)
+    assert L.slicemoe_route_train(ctypes.byref(bad_cfg), one, ctypes.byref(w), ctypes.byref(P(1.0, 0.0, 0.0)), None, None,
+                                  one, one, None, 0, None) == B.SLICEMOE_ERR_INVALID_ARG
+
+
 def test_capacity_and_sizes(B):
     from paper_2510_04286_amd import workload as wl
     for name, c in wl.CONFIGS.items():

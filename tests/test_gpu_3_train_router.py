@@ -1,0 +1,121 @@
+"""GPU parity of the training-time router (softmax temperature: Appendix B; Gaussian logit noise: Section 5;
+cross-slice dropout: Section 3.3) and of the layer run with it, against the fp64 CPU oracle.  The random draws are
+inputs from the seeded generator, identical on both sides.
+
+Bars: as for the inference router -- routing equal except near-ties of the (noisy) fp32 logits, which are counted
+and masked; selected probabilities to 5e-5 relative (they carry the fp32 logit error divided by the temperature);
+which assignments the dropout zeroes is an exact fp32 comparison of the same draws, so it must agree exactly.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2510_04286_amd import workload as wl
+from tests.common import NEAR_TIE, TOL_BF16, TOL_F32, make_inputs, rms, routing_agreement
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need an MI355X"
+    from paper_2510_04286_amd import binding
+    binding.lib()
+    return binding
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+SHAPES = {
+    "tiny": (wl.CONFIGS["tiny"], 300),                   # fp32 storage: generic kernels
+    "lm": (wl.CONFIGS["lm"], 1024),                      # E = 16
+    "headline": (wl.CONFIGS["headline"], 1027),          # E = 32, ragged last tile
+    "paper": (wl.CONFIGS["paper"], 700),                 # slice width 96
+    "E6": (wl.SliceMoEShape("E6", T=500, d=256, S=4, E=6, k=3, He=64), None),     # E not a multiple of 4
+    "E40": (wl.SliceMoEShape("E40", T=400, d=512, S=4, E=40, k=2, He=128), None),  # two expert tiles, 8 padded
+}
+VARIANTS = [(1.0, 0.0, 0.0), (0.5, 0.0, 0.0), (2.0, 0.3, 0.0), (1.0, 0.0, 0.2), (0.7, 0.5, 0.2), (1.0, 1.0, 0.5)]
+
+
+@pytest.mark.parametrize("name", list(SHAPES))
+@pytest.mark.parametrize("tau,sigma,rate", VARIANTS)
+def test_route_train_matches_oracle(B, name, tau, sigma, rate):
+    import torch
+    base, T = SHAPES[name]
+    shape, h, w = make_inputs(base, T)
+    cfg = B.config_of(shape)
+    noise, drop_u = wl.make_router_draws(shape)
+    x = h.reshape(-1, shape.ds)
+    ref = oracle.route_train(x, w["Wr1"], w["br1"], w["Wr2"], w["br2"], shape.k, tau=tau, sigma=sigma, noise=noise,
+                             rate=rate, drop_u=drop_u, want_logits=True)
+    wd = B.pack(cfg, B.weights_to_device(w, shape.dtype))
+    idx = torch.full((shape.Ns, shape.k), -1, dtype=torch.int32, device="cuda:0")
+    p = torch.full((shape.Ns, shape.k), -1.0, dtype=torch.float32, device="cuda:0")
+    B.slicemoe_route_train(cfg, B.to_device(h, shape.dtype), wd, idx, p, temperature=tau, noise_std=sigma,
+                           dropout_rate=rate, noise=dev(noise), drop_u=dev(drop_u))
+    gi, gp = idx.cpu().numpy(), p.cpu().numpy().astype(np.float64)
+    mism, n_tie = routing_agreement(gi, ref["idx"], ref["logits"])
+    near = int(np.count_nonzero(ref["margin"] < NEAR_TIE))
+    ok = ~mism
+    np.testing.assert_array_equal(gp[ok] == 0, ref["pk"][ok] == 0)
+    np.testing.assert_allclose(gp[ok], ref["pk"][ok], rtol=5e-5, atol=1e-9)
+    assert n_tie <= max(4, 4 * near)
+    if rate > 0:
+        np.testing.assert_allclose(gp.sum(axis=1), 1.0, rtol=1e-5)
+        assert 0 < np.count_nonzero(gp == 0) < gp.size
+    if sigma > 0:   # the noise did reach the selection
+        plain = oracle.route(x, w["Wr1"], w["br1"], w["Wr2"], w["br2"], shape.k)
+        assert np.any(plain["idx"] != gi)
+
+
+def test_route_train_with_plain_parameters_is_the_inference_router(B):
+    import torch
+    shape, h, w = make_inputs(wl.CONFIGS["headline"], 512)
+    cfg = B.config_of(shape)
+    wd = B.pack(cfg, B.weights_to_device(w, shape.dtype))
+    hd = B.to_device(h, shape.dtype)
+    out = []
+    for train in (False, True):
+        idx = torch.full((shape.Ns, shape.k), -1, dtype=torch.int32, device="cuda:0")
+        p = torch.full((shape.Ns, shape.k), -1.0, dtype=torch.float32, device="cuda:0")
+        if train:
+            B.slicemoe_route_train(cfg, hd, wd, idx, p)   # tau = 1, no noise, no dropout, no tables
+        else:
+            B.slicemoe_route(cfg, hd, wd, idx, p)
+        out.append((idx.cpu().numpy(), p.cpu().numpy()))
+    np.testing.assert_array_equal(out[0][0], out[1][0])
+    np.testing.assert_array_equal(out[0][1], out[1][1])
+
+
+@pytest.mark.parametrize("name,T", [("tiny", 128), ("headline", 200), ("paper", 150)])
+def test_forward_train_matches_oracle(B, name, T):
+    import torch
+    shape, h, w = make_inputs(wl.CONFIGS[name], T)
+    cfg = B.config_of(shape)
+    noise, drop_u = wl.make_router_draws(shape)
+    tau, sigma, rate = 0.8, 0.4, 0.2
+    ref = oracle.forward_train(h, shape.S, shape.k, w, tau=tau, sigma=sigma, noise=noise, rate=rate, drop_u=drop_u,
+                               capacity=shape.capacity())
+    wd = B.pack(cfg, B.weights_to_device(w, shape.dtype))
+    ws = B.alloc_workspace(cfg)
+    tdt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+    out = torch.full((shape.T, shape.d), 3.0, dtype=tdt, device="cuda:0")
+    B.slicemoe_forward_train(cfg, B.to_device(h, shape.dtype), wd, out, ws, temperature=tau, noise_std=sigma,
+                             dropout_rate=rate, noise=dev(noise), drop_u=dev(drop_u))
+    torch.cuda.synchronize()
+    views = {n: v.cpu().numpy() for n, v in B.workspace_views(cfg, ws).items() if n != "y"}
+    got = out.float().cpu().numpy().astype(np.float64)
+    mism, n_tie = routing_agreement(views["topk_idx"], ref["idx"], ref["logits"])
+    if n_tie == 0:
+        for n in ("counts_raw", "counts", "offsets", "inv"):
+            np.testing.assert_array_equal(views[n], ref[n], err_msg=n)
+    tol = TOL_F32 if shape.dtype == "f32" else TOL_BF16
+    diff = np.abs(got - ref["h_out"]).reshape(-1, shape.ds)
+    err = diff[~mism].max() / rms(ref["h_out"])
+    print(f"\n[forward_train {name}] slices={shape.Ns} near-tie mismatches={n_tie} max|err|/rms={err:.3e} (bar {tol:g})")
+    assert err <= tol
+    assert mism.sum() <= max(8, 1e-4 * shape.Ns)
