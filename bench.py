@@ -7,7 +7,8 @@ weights pre-packed once outside the timed region as at model load).  Prints ONE 
 whole-layer tokens/s, the per-stage breakdown, the roofline of the dominant kernel (the
 grouped expert FFN, matrix-core bound) and the CPU oracle timed on this machine's host cores.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload headline|lm|skewed|large|paper]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload headline|lm|skewed|large|paper [--slices S] [--topk k]]
+                  [--train-router TAU,SIGMA,RATE]
 """
 import argparse
 import json
@@ -35,6 +36,9 @@ def main():
     ap.add_argument("--workload", default="headline", choices=["lm", "headline", "skewed", "large", "paper"])
     ap.add_argument("--slices", type=int, default=8, help="S of the paper workload (its Table 2 sweep)")
     ap.add_argument("--topk", type=int, default=2, help="k of the paper workload (its Table 4 sweep)")
+    ap.add_argument("--train-router", default=None, metavar="TAU,SIGMA,RATE",
+                    help="run the layer with the training-time router: softmax temperature, logit-noise std, "
+                         "cross-slice dropout rate (e.g. 1.0,0.1,0.2); the draws are seeded inputs resident in HBM")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -77,9 +81,19 @@ def main():
                      torch.empty(ws_bytes, dtype=torch.uint8, device=dev)))
     del h_dev
 
+    train = None
+    if args.train_router:
+        tau, sigma, rate = (float(v) for v in args.train_router.split(","))
+        noise_h, drop_h = wl.make_router_draws(shape)
+        train = dict(temperature=tau, noise_std=sigma, dropout_rate=rate,
+                     noise=torch.from_numpy(noise_h).to(dev), drop_u=torch.from_numpy(drop_h).to(dev))
+
     def step(i):
         hh, oo, ws = sets[i % nsets]
-        B.slicemoe_forward(cfg, hh, wd, oo, ws)
+        if train:
+            B.slicemoe_forward_train(cfg, hh, wd, oo, ws, **train)
+        else:
+            B.slicemoe_forward(cfg, hh, wd, oo, ws)
 
     for i in range(args.warmup):
         step(i)
@@ -105,7 +119,10 @@ def main():
         v = views[i % nsets]
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
         ev[0].record()
-        B.slicemoe_route(cfg, hh, wd, v["topk_idx"], v["topk_p"])
+        if train:
+            B.slicemoe_route_train(cfg, hh, wd, v["topk_idx"], v["topk_p"], **train)
+        else:
+            B.slicemoe_route(cfg, hh, wd, v["topk_idx"], v["topk_p"])
         ev[1].record()
         B.slicemoe_dispatch(cfg, v["topk_idx"], v["counts_raw"], v["counts"], v["offsets"], v["perm"], v["inv"],
                             ws[L.scratch:L.packed])
@@ -180,7 +197,11 @@ def main():
             hc = h[:Tc]
         cap = -1 if shape.capacity_factor <= 0 else int(np.ceil(float(np.float32(shape.capacity_factor)) * Tc * shape.S * shape.k / shape.E))
         c0 = time.perf_counter()
-        oracle.forward(hc, shape.S, shape.k, w, capacity=cap)
+        if train:
+            oracle.forward_train(hc, shape.S, shape.k, w, tau=tau, sigma=sigma, noise=noise_h[:Tc * shape.S], rate=rate,
+                                 drop_u=drop_h[:Tc * shape.S], capacity=cap)
+        else:
+            oracle.forward(hc, shape.S, shape.k, w, capacity=cap)
         c1 = time.perf_counter()
         cpu = {"value": round(Tc / (c1 - c0), 1), "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
                "sample": sample, "seconds": round(c1 - c0, 2)}
@@ -191,6 +212,7 @@ def main():
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{shape.name}: T={shape.T} d={shape.d} S={shape.S} E={shape.E} k={shape.k} "
                                f"Hr={shape.Hr} He={shape.He} capacity_factor={shape.capacity_factor}",
+                   "router": f"training-time: temperature {tau}, noise std {sigma}, dropout {rate}" if train else "inference",
                    "rotating_sets": nsets, "prepacked_weights": True, "kept_rows": n_kept},
         "slices_per_s": round(Ns / (ms_per_step * 1e-3), 1),
         "stages": stages,
