@@ -224,6 +224,37 @@ def forward_train(h, S: int, k: int, weights: dict, tau: float = 1.0, sigma: flo
     return res
 
 
+def backward(h, S: int, k: int, weights: dict, d_out, idx, inv, tau: float = 1.0, sigma: float = 0.0, noise=None,
+             rate: float = 0.0, drop_u=None):
+    """Gradients of a loss with dL/dh' = d_out[T, d], given the forward pass's idx[Ns,k] and inv[Ns*k].
+    Returns dict(d_h[T,d], Wr1, br1, Wr2, br2, W1, b1, W2, b2) in the logical layouts, fp64."""
+    h = _f64(h)
+    T, d = h.shape
+    ds = d // S
+    Ns = T * S
+    w = {n: _f64(weights[n]) for n in ("Wr1", "br1", "Wr2", "br2", "W1", "b1", "W2", "b2")}
+    Hr, E = w["Wr2"].shape
+    He = w["W1"].shape[2]
+    G = _f64(d_out)
+    assert G.shape == (T, d)
+    idx, inv = _i32(idx), _i32(inv)
+    assert idx.shape == (Ns, k) and inv.shape == (Ns * k,)
+    noise = None if noise is None else _f64(noise)
+    drop_u = None if drop_u is None else _f64(drop_u)
+    out = {"d_h": np.empty((T, d), dtype=np.float64)}
+    for n in ("Wr1", "br1", "Wr2", "br2", "W1", "b1", "W2", "b2"):
+        out[n] = np.empty_like(w[n])
+    rc = lib().oracle_backward(_p(h), ctypes.c_int64(Ns), ds, Hr, E, k, He,
+                               _p(w["Wr1"]), _p(w["br1"]), _p(w["Wr2"]), _p(w["br2"]),
+                               _p(w["W1"]), _p(w["b1"]), _p(w["W2"]), _p(w["b2"]),
+                               ctypes.c_double(tau), ctypes.c_double(sigma), _p(noise), ctypes.c_double(rate),
+                               _p(drop_u), _p(idx), _p(inv), _p(G), _p(out["d_h"]),
+                               _p(out["Wr1"]), _p(out["br1"]), _p(out["Wr2"]), _p(out["br2"]),
+                               _p(out["W1"]), _p(out["b1"]), _p(out["W2"]), _p(out["b2"]))
+    _check(rc, "oracle_backward")
+    return out
+
+
 def load_stats(counts):
     """dict(cv_pop, cv_sample, ele) of per-expert counts (Eq. 2 statistic; ELE of Section 4)."""
     counts = _i32(counts)

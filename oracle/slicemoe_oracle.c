@@ -29,7 +29,8 @@
  * bijection, E=1/k=1 dense-FFN reduction against library matmul+erf, S=1 token-level MoE,
  * W2=0 and identity-activation closed forms, load-statistic closed forms; for the training-time
  * router: reduction to oracle_route, the power law of the temperature, shift invariance and
- * planted bumps for the noise, hand-worked dropout cases.
+ * planted bumps for the noise, hand-worked dropout cases; for the backward: central finite
+ * differences of the forward functions in this file, parameter by parameter.
  */
 #include <math.h>
 #include <stdint.h>
@@ -406,6 +407,181 @@ int oracle_forward(const double *h, int64_t T, int d, int S, int Hr, int E, int 
     }
     free(idx); free(pk); free(perm); free(inv); free(cr); free(cc); free(off);
     return rc;
+}
+
+/*
+ * Backward of the layer: gradients of a scalar loss that depends on h and on the weights only
+ * through h', given G = dL/dh' (slice view [Ns, ds]).  Chain rule through the definition, slice
+ * by slice: the k-sum, the expert FFN (Section 3.1), the input weighting of Eq. 1, and the router
+ * (Section 3.1; training-time variations as in oracle_route_train).
+ *
+ * Readings (the paper gives no backward):
+ *   - the routing DECISIONS are piecewise constant and held fixed: which experts a slice selects,
+ *     which assignments a capacity limit dropped (inv[a] < 0: no contribution, no gradient) and
+ *     which the cross-slice dropout zeroed.  The router receives gradient only through the
+ *     selected probabilities, which weight the expert inputs (Eq. 1: z = p (x W1) + b1, so
+ *     dL/dp = sum_hidden dL/dz * (x W1)).
+ *   - with dropout the renormalisation pk'_j = p_j / s (s = sum of the kept p) is differentiated:
+ *     dL/dp_j = (dL/dpk'_j - sum_i dL/dpk'_i pk'_i) / s for kept j, 0 for dropped j.
+ *   - softmax with temperature: dL/dg_e = (1/tau) sum_j dL/dp_j p_j ([e == e_j] - p_e); the noise
+ *     is an additive constant.
+ *   - the capacity loss of Eq. 2 is a function of integer counts and has zero gradient; it is
+ *     not part of this function.
+ * idx[Ns,k] and inv[Ns*k] are the forward pass's (oracle_route_train / oracle_dispatch); the
+ * probabilities are recomputed here.  Outputs (all overwritten): dx[Ns, ds] and one array per
+ * weight tensor in its logical layout.  Returns 0, or -1 on bad arguments / allocation failure.
+ */
+static double gelu_grad(double z)
+{
+    /* d/dz [z Phi(z)] = Phi(z) + z phi(z) */
+    return 0.5 * erfc(-z * 0.70710678118654752440) + z * exp(-0.5 * z * z) * 0.39894228040143267794;
+}
+
+int oracle_backward(const double *x, int64_t Ns, int ds, int Hr, int E, int k, int He,
+                    const double *Wr1, const double *br1, const double *Wr2, const double *br2,
+                    const double *W1, const double *b1, const double *W2, const double *b2,
+                    double tau, double sigma, const double *noise, double rate, const double *drop_u,
+                    const int32_t *idx, const int32_t *inv, const double *G,
+                    double *dx, double *dWr1, double *dbr1, double *dWr2, double *dbr2,
+                    double *dW1, double *db1, double *dW2, double *db2)
+{
+    if (!x || !idx || !inv || !G || !dx || !dWr1 || !dbr1 || !dWr2 || !dbr2 || !dW1 || !db1 || !dW2 || !db2) return -1;
+    if (Ns < 0 || ds < 1 || Hr < 1 || E < 1 || k < 1 || k > E || He < 1) return -1;
+    if (!(tau > 0.0) || !(sigma >= 0.0) || !(rate >= 0.0) || !(rate < 1.0)) return -1;
+    if ((sigma > 0.0 && !noise) || (rate > 0.0 && !drop_u)) return -1;
+    (void)b2; /* the output bias shifts h' and does not enter any derivative */
+    const size_t nWr1 = (size_t)ds * Hr, nWr2 = (size_t)Hr * E, nW = (size_t)E * ds * He;
+    const size_t nb1 = (size_t)E * He, nb2 = (size_t)E * ds;
+    memset(dWr1, 0, sizeof(double) * nWr1); memset(dbr1, 0, sizeof(double) * (size_t)Hr);
+    memset(dWr2, 0, sizeof(double) * nWr2); memset(dbr2, 0, sizeof(double) * (size_t)E);
+    memset(dW1, 0, sizeof(double) * nW); memset(db1, 0, sizeof(double) * nb1);
+    memset(dW2, 0, sizeof(double) * nW); memset(db2, 0, sizeof(double) * nb2);
+    int fail = 0;
+#pragma omp parallel
+    {
+        /* per-thread partial weight gradients, added up at the end */
+        const size_t total = nWr1 + (size_t)Hr + nWr2 + (size_t)E + 2 * nW + nb1 + nb2;
+        double *part = (double *)calloc(total, sizeof(double));
+        double *ur = (double *)malloc(sizeof(double) * (size_t)Hr);
+        double *dur = (double *)malloc(sizeof(double) * (size_t)Hr);
+        double *g = (double *)malloc(sizeof(double) * (size_t)E);
+        double *pa = (double *)malloc(sizeof(double) * (size_t)E);
+        double *dg = (double *)malloc(sizeof(double) * (size_t)E);
+        double *u = (double *)malloc(sizeof(double) * (size_t)He);
+        double *dz = (double *)malloc(sizeof(double) * (size_t)He);
+        double *pf = (double *)malloc(sizeof(double) * (size_t)k);   /* final probabilities */
+        double *dpf = (double *)malloc(sizeof(double) * (size_t)k);  /* dL/d(final probability) */
+        char *keep = (char *)malloc((size_t)k);
+        if (!part || !ur || !dur || !g || !pa || !dg || !u || !dz || !pf || !dpf || !keep) {
+#pragma omp atomic write
+            fail = 1;
+        } else {
+            double *qWr1 = part, *qbr1 = qWr1 + nWr1, *qWr2 = qbr1 + Hr, *qbr2 = qWr2 + nWr2;
+            double *qW1 = qbr2 + E, *qb1 = qW1 + nW, *qW2 = qb1 + nb1, *qb2 = qW2 + nW;
+#pragma omp for schedule(static)
+            for (int64_t n = 0; n < Ns; ++n) {
+                const double *xn = x + n * ds, *Gn = G + n * ds;
+                double *dxn = dx + n * ds;
+                for (int i = 0; i < ds; ++i) dxn[i] = 0.0;
+                /* forward quantities of the router, as in oracle_route_train */
+                router_logits(xn, ds, Hr, E, Wr1, br1, Wr2, br2, ur, g);
+                if (sigma > 0.0)
+                    for (int e = 0; e < E; ++e) g[e] += sigma * noise[n * E + e];
+                double m = g[0];
+                for (int e = 1; e < E; ++e) m = g[e] > m ? g[e] : m;
+                double den = 0.0;
+                for (int e = 0; e < E; ++e) { pa[e] = exp((g[e] - m) / tau); den += pa[e]; }
+                for (int e = 0; e < E; ++e) pa[e] /= den;
+                double ssum = 1.0;
+                for (int j = 0; j < k; ++j) { keep[j] = 1; pf[j] = pa[idx[n * k + j]]; }
+                if (rate > 0.0) {
+                    int kept = 0;
+                    for (int j = 0; j < k; ++j) { keep[j] = !((float)drop_u[n * k + j] < (float)rate); kept += keep[j]; }
+                    if (kept == 0) keep[0] = 1;
+                    ssum = 0.0;
+                    for (int j = 0; j < k; ++j) if (keep[j]) ssum += pf[j];
+                    for (int j = 0; j < k; ++j) pf[j] = keep[j] ? pf[j] / ssum : 0.0;
+                }
+                /* experts */
+                for (int j = 0; j < k; ++j) {
+                    dpf[j] = 0.0;
+                    int64_t a = n * k + j;
+                    if (inv[a] < 0) continue;
+                    int e = idx[a];
+                    const double *w1 = W1 + (size_t)e * ds * He, *w2 = W2 + (size_t)e * He * ds;
+                    double p = pf[j];
+                    for (int h = 0; h < He; ++h) u[h] = 0.0;
+                    for (int i = 0; i < ds; ++i)
+                        for (int h = 0; h < He; ++h) u[h] += xn[i] * w1[(size_t)i * He + h];
+                    for (int i = 0; i < ds; ++i) qb2[(size_t)e * ds + i] += Gn[i];
+                    for (int h = 0; h < He; ++h) {
+                        double z = p * u[h] + b1[(size_t)e * He + h];
+                        double a1 = act_fn(z, ORACLE_ACT_GELU);
+                        double da1 = 0.0;
+                        for (int i = 0; i < ds; ++i) {
+                            qW2[((size_t)e * He + h) * ds + i] += a1 * Gn[i];
+                            da1 += Gn[i] * w2[(size_t)h * ds + i];
+                        }
+                        dz[h] = da1 * gelu_grad(z);
+                        qb1[(size_t)e * He + h] += dz[h];
+                        dpf[j] += dz[h] * u[h];
+                    }
+                    for (int i = 0; i < ds; ++i) {
+                        double acc = 0.0;
+                        for (int h = 0; h < He; ++h) {
+                            qW1[((size_t)e * ds + i) * He + h] += xn[i] * p * dz[h];
+                            acc += dz[h] * w1[(size_t)i * He + h];
+                        }
+                        dxn[i] += p * acc;
+                    }
+                }
+                /* through the renormalisation of the dropout, then the softmax */
+                if (rate > 0.0) {
+                    double dot = 0.0;
+                    for (int j = 0; j < k; ++j) if (keep[j]) dot += dpf[j] * pf[j];
+                    for (int j = 0; j < k; ++j) dpf[j] = keep[j] ? (dpf[j] - dot) / ssum : 0.0;
+                }
+                for (int e = 0; e < E; ++e) dg[e] = 0.0;
+                for (int j = 0; j < k; ++j) {
+                    int ej = idx[n * k + j];
+                    double c = dpf[j] * pa[ej];
+                    for (int e = 0; e < E; ++e) dg[e] += c * ((e == ej ? 1.0 : 0.0) - pa[e]);
+                }
+                for (int e = 0; e < E; ++e) dg[e] /= tau;
+                /* router MLP */
+                for (int e = 0; e < E; ++e) qbr2[e] += dg[e];
+                for (int h = 0; h < Hr; ++h) {
+                    double acc = 0.0;
+                    for (int e = 0; e < E; ++e) {
+                        qWr2[(size_t)h * E + e] += ur[h] * dg[e];
+                        acc += dg[e] * Wr2[(size_t)h * E + e];
+                    }
+                    dur[h] = ur[h] > 0.0 ? acc : 0.0;
+                    qbr1[h] += dur[h];
+                }
+                for (int i = 0; i < ds; ++i) {
+                    double acc = 0.0;
+                    for (int h = 0; h < Hr; ++h) {
+                        qWr1[(size_t)i * Hr + h] += xn[i] * dur[h];
+                        acc += dur[h] * Wr1[(size_t)i * Hr + h];
+                    }
+                    dxn[i] += acc;
+                }
+            }
+#pragma omp critical
+            {
+                for (size_t t = 0; t < nWr1; ++t) dWr1[t] += qWr1[t];
+                for (int t = 0; t < Hr; ++t) dbr1[t] += qbr1[t];
+                for (size_t t = 0; t < nWr2; ++t) dWr2[t] += qWr2[t];
+                for (int t = 0; t < E; ++t) dbr2[t] += qbr2[t];
+                for (size_t t = 0; t < nW; ++t) { dW1[t] += qW1[t]; dW2[t] += qW2[t]; }
+                for (size_t t = 0; t < nb1; ++t) db1[t] += qb1[t];
+                for (size_t t = 0; t < nb2; ++t) db2[t] += qb2[t];
+            }
+        }
+        free(part); free(ur); free(dur); free(g); free(pa); free(dg); free(u); free(dz); free(pf); free(dpf); free(keep);
+    }
+    return fail ? -1 : 0;
 }
 
 /*
