@@ -236,6 +236,35 @@ slicemoe_status slicemoe_forward_train(const slicemoe_config *cfg, const void *h
                                        slicemoe_stream_t stream);
 
 /*
+ * Backward pass of the layer: gradients of a scalar loss that depends on h and on the weights only through h', by
+ * the chain rule through the sum over the k experts, the expert FFN and the Eq. 1 input weighting (Section 3.1) and
+ * the router (Section 3.1; temperature of Appendix B, logit noise of Section 5, cross-slice dropout of Section 3.3).
+ * The routing decisions -- which experts a slice selected, which assignments the capacity limit dropped, which the
+ * dropout zeroed -- are piecewise constant and held fixed.  The router receives gradient through the selected
+ * probabilities, which weight the expert inputs (z = p (x W1) + b1, so dL/dp = sum over the hidden units of
+ * dL/dz (x W1)); with dropout the renormalisation is differentiated; the noise is an additive constant.  The capacity
+ * loss of Eq. 2 is a function of integer counts, has zero gradient, and is not part of this call.
+ *   h, w                 as given to the forward call (w: the LOGICAL tensors are read, w->packed is ignored)
+ *   params, noise, drop_u as given to slicemoe_forward_train; params == NULL after slicemoe_forward
+ *   forward_workspace    the workspace that forward call filled (routing tables and probabilities are read from it)
+ *   d_out [T, d] in      dL/dh', storage dtype
+ *   d_h   [T, d] out     dL/dh, storage dtype (one rounding)
+ *   grads       out      one fp32 DEVICE array per weight tensor, logical layout, overwritten.  They are summed with
+ *                        fp32 atomic adds: the last bits vary from run to run.
+ *   workspace            >= slicemoe_backward_workspace_bytes(cfg), 256-byte aligned
+ * This version runs on vector-ALU kernels for every shape.  UNSUPPORTED for Hr > 256.
+ */
+typedef struct {
+    float *Wr1, *br1, *Wr2, *br2, *W1, *b1, *W2, *b2;
+} slicemoe_weight_grads;
+size_t slicemoe_backward_workspace_bytes(const slicemoe_config *cfg);
+slicemoe_status slicemoe_backward(const slicemoe_config *cfg, const void *h, const slicemoe_weights *w,
+                                  const slicemoe_route_train_params *params, const float *noise, const float *drop_u,
+                                  const void *forward_workspace, size_t forward_workspace_bytes,
+                                  const void *d_out, void *d_h, const slicemoe_weight_grads *grads,
+                                  void *workspace, size_t workspace_bytes, slicemoe_stream_t stream);
+
+/*
  * Measurement aid (not a step of the layer): runs `nblocks` blocks of 256 threads, each doing `iters`
  * rounds of a fixed register-only mix of bf16 matrix and packed-fp16 vector instructions, and writes
  * per block cycles_and_ticks[2*b] = elapsed shader cycles, [2*b+1] = elapsed ticks of the constant

@@ -29,7 +29,7 @@ EXPORTS = [
     "slicemoe_dispatch_workspace_bytes", "slicemoe_get_workspace_layout", "slicemoe_packed_bytes",
     "slicemoe_pack_weights", "slicemoe_route", "slicemoe_dispatch", "slicemoe_expert_ffn",
     "slicemoe_combine", "slicemoe_load_stats", "slicemoe_forward", "slicemoe_probe_clock",
-    "slicemoe_route_train", "slicemoe_forward_train",
+    "slicemoe_route_train", "slicemoe_forward_train", "slicemoe_backward_workspace_bytes", "slicemoe_backward",
 ]
 
 
@@ -51,6 +51,10 @@ class slicemoe_weights(ctypes.Structure):
 
 class slicemoe_route_train_params(ctypes.Structure):
     _fields_ = [("temperature", ctypes.c_float), ("noise_std", ctypes.c_float), ("dropout_rate", ctypes.c_float)]
+
+
+class slicemoe_weight_grads(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in ("Wr1", "br1", "Wr2", "br2", "W1", "b1", "W2", "b2")]
 
 
 class slicemoe_workspace_layout(ctypes.Structure):
@@ -101,6 +105,11 @@ def lib() -> ctypes.CDLL:
         L.slicemoe_route_train.argtypes = [cfgp, vp, wp, tpp, vp, vp, vp, vp, vp, st, vp]
         L.slicemoe_forward_train.restype = ctypes.c_int
         L.slicemoe_forward_train.argtypes = [cfgp, vp, wp, tpp, vp, vp, vp, vp, st, vp]
+        L.slicemoe_backward_workspace_bytes.restype = ctypes.c_size_t
+        L.slicemoe_backward_workspace_bytes.argtypes = [cfgp]
+        L.slicemoe_backward.restype = ctypes.c_int
+        L.slicemoe_backward.argtypes = [cfgp, vp, wp, tpp, vp, vp, vp, st, vp, vp, ctypes.POINTER(slicemoe_weight_grads),
+                                        vp, st, vp]
         _lib = L
     return _lib
 
@@ -291,6 +300,41 @@ def slicemoe_forward_train(cfg, h, w, h_out, workspace, temperature=1.0, noise_s
     _check(lib().slicemoe_forward_train(ctypes.byref(cfg), _ptr(h, _tdtype(cfg), cfg.T * cfg.d, "h"), ctypes.byref(ws),
                                         ctypes.byref(tp), npt, upt, _ptr(h_out, _tdtype(cfg), cfg.T * cfg.d, "h_out"),
                                         wsp, wsb, _stream(stream)), "slicemoe_forward_train")
+
+
+def slicemoe_backward_workspace_bytes(cfg) -> int:
+    return int(lib().slicemoe_backward_workspace_bytes(ctypes.byref(cfg)))
+
+
+def alloc_weight_grads(cfg, device="cuda:0") -> dict:
+    """fp32 device tensors in the logical layout of each weight tensor (contents undefined until slicemoe_backward)."""
+    ds = cfg.d // cfg.S
+    shapes = {"Wr1": (ds, cfg.Hr), "br1": (cfg.Hr,), "Wr2": (cfg.Hr, cfg.E), "br2": (cfg.E,),
+              "W1": (cfg.E, ds, cfg.He), "b1": (cfg.E, cfg.He), "W2": (cfg.E, cfg.He, ds), "b2": (cfg.E, ds)}
+    return {n: torch.empty(sh, dtype=torch.float32, device=device) for n, sh in shapes.items()}
+
+
+def slicemoe_backward(cfg, h, w, forward_workspace, d_out, d_h, grads: dict, workspace, train: dict | None = None,
+                      stream=None):
+    """train: None after slicemoe_forward, else the keyword arguments given to slicemoe_forward_train."""
+    fwp, fwb = _ws(forward_workspace)
+    wsp, wsb = _ws(workspace)
+    ws = _weights(cfg, w)
+    tpp, npt, upt = None, None, None
+    if train is not None:
+        tp, npt, upt = _train_args(cfg, train.get("temperature", 1.0), train.get("noise_std", 0.0),
+                                   train.get("dropout_rate", 0.0), train.get("noise"), train.get("drop_u"))
+        tpp = ctypes.byref(tp)
+    g = slicemoe_weight_grads()
+    ds = cfg.d // cfg.S
+    sizes = {"Wr1": ds * cfg.Hr, "br1": cfg.Hr, "Wr2": cfg.Hr * cfg.E, "br2": cfg.E, "W1": cfg.E * ds * cfg.He,
+             "b1": cfg.E * cfg.He, "W2": cfg.E * cfg.He * ds, "b2": cfg.E * ds}
+    for n, numel in sizes.items():
+        setattr(g, n, _ptr(grads[n], torch.float32, numel, "grads." + n).value)
+    _check(lib().slicemoe_backward(ctypes.byref(cfg), _ptr(h, _tdtype(cfg), cfg.T * cfg.d, "h"), ctypes.byref(ws), tpp,
+                                   npt, upt, fwp, fwb, _ptr(d_out, _tdtype(cfg), cfg.T * cfg.d, "d_out"),
+                                   _ptr(d_h, _tdtype(cfg), cfg.T * cfg.d, "d_h"), ctypes.byref(g), wsp, wsb,
+                                   _stream(stream)), "slicemoe_backward")
 
 
 def slicemoe_probe_clock(cycles_and_ticks, nblocks: int, iters: int, stream=None):

@@ -402,6 +402,51 @@ slicemoe_status slicemoe_forward_train(const slicemoe_config *cfg, const void *h
     return forward_common(cfg, h, w, v, drop_u, params->dropout_rate, h_out, workspace, workspace_bytes, stream);
 }
 
+size_t slicemoe_backward_workspace_bytes(const slicemoe_config *cfg)
+{
+    if (validate(cfg) != SLICEMOE_OK) return 0;
+    const size_t Na = (size_t)cfg->T * cfg->S * cfg->k;
+    const size_t ds = (size_t)(cfg->d / cfg->S);
+    return align_up(Na * ds * sizeof(float), 256) + align_up(Na * sizeof(float), 256) + 256;
+}
+
+slicemoe_status slicemoe_backward(const slicemoe_config *cfg, const void *h, const slicemoe_weights *w,
+                                  const slicemoe_route_train_params *params, const float *noise, const float *drop_u,
+                                  const void *forward_workspace, size_t forward_workspace_bytes, const void *d_out,
+                                  void *d_h, const slicemoe_weight_grads *grads, void *workspace, size_t workspace_bytes,
+                                  slicemoe_stream_t stream)
+{
+    const slicemoe_status st = validate(cfg);
+    if (st != SLICEMOE_OK) return st;
+    if (cfg->Hr > 256 || backward_lds_bytes(*cfg) > 60 * 1024) return SLICEMOE_ERR_UNSUPPORTED;
+    RouteVariant v;
+    float rate = 0.f;
+    if (params) {
+        const slicemoe_status vs = make_route_variant(params, noise, drop_u, &v);
+        if (vs != SLICEMOE_OK) return vs;
+        rate = params->dropout_rate;
+    }
+    if (!w || !grads || ((!h || !d_out || !d_h) && cfg->T > 0)) return SLICEMOE_ERR_INVALID_ARG;
+    if (!logical_weights_ok(*w, true, true)) return SLICEMOE_ERR_INVALID_ARG;
+    if (!grads->Wr1 || !grads->br1 || !grads->Wr2 || !grads->br2 || !grads->W1 || !grads->b1 || !grads->W2 || !grads->b2)
+        return SLICEMOE_ERR_INVALID_ARG;
+    slicemoe_workspace_layout L;
+    make_layout(*cfg, &L);
+    if (!forward_workspace || forward_workspace_bytes < L.total) return SLICEMOE_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes < slicemoe_backward_workspace_bytes(cfg)) return SLICEMOE_ERR_WORKSPACE;
+    if (misaligned(forward_workspace, 256) || misaligned(workspace, 256)) return SLICEMOE_ERR_INVALID_ARG;
+    const char *fw = (const char *)forward_workspace;
+    const size_t Na = (size_t)cfg->T * cfg->S * cfg->k;
+    const size_t ds = (size_t)(cfg->d / cfg->S);
+    float *dxrow = (float *)workspace;
+    float *dpk = (float *)((char *)workspace + align_up(Na * ds * sizeof(float), 256));
+    const hipError_t e = launch_backward(*cfg, h, *w, v, drop_u, rate, (const int32_t *)(fw + L.topk_idx),
+                                         (const float *)(fw + L.topk_p), (const int32_t *)(fw + L.offsets),
+                                         (const int32_t *)(fw + L.perm), (const int32_t *)(fw + L.inv), d_out, d_h, *grads,
+                                         dxrow, dpk, (hipStream_t)stream);
+    return e == hipSuccess ? SLICEMOE_OK : SLICEMOE_ERR_HIP;
+}
+
 slicemoe_status slicemoe_probe_clock(uint64_t *cycles_and_ticks, int32_t nblocks, int32_t iters, slicemoe_stream_t stream)
 {
     if (!cycles_and_ticks || nblocks < 1 || nblocks > 65536 || iters < 1 || iters > (1 << 24)) return SLICEMOE_ERR_INVALID_ARG;

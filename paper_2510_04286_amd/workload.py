@@ -31,7 +31,7 @@ _M2 = np.uint64(0x94D049BB133111EB)
 H_R = 256  # router hidden width (Section 3.1, Appendix A)
 
 # tensor ids (streams) of the generator
-TID_H, TID_WR1, TID_BR1, TID_WR2, TID_BR2, TID_W1, TID_B1, TID_W2, TID_B2, TID_IDX, TID_NOISE, TID_DROP = range(12)
+TID_H, TID_WR1, TID_BR1, TID_WR2, TID_BR2, TID_W1, TID_B1, TID_W2, TID_B2, TID_IDX, TID_NOISE, TID_DROP, TID_DOUT = range(13)
 
 
 @dataclass(frozen=True)
@@ -228,3 +228,9 @@ def make_router_draws(cfg: SliceMoEShape, seed: int = 2) -> tuple:
     drop_u = uniform01(seed, TID_DROP, 0, cfg.Na).astype(np.float32).reshape(cfg.Ns, cfg.k)
     drop_u = np.minimum(drop_u, np.float32(1.0 - 2.0 ** -24))   # rounding to fp32 must not reach 1
     return noise, drop_u
+
+
+def make_dout(cfg: SliceMoEShape, seed: int = 3) -> np.ndarray:
+    """Upstream gradient dL/dh'[T, d] ~ N(0,1) for the backward pass, storage-rounded."""
+    g = normal(seed, TID_DOUT, 0, cfg.T * cfg.d).reshape(cfg.T, cfg.d)
+    return to_storage(g, cfg.dtype)

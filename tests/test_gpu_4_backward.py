@@ -1,0 +1,125 @@
+"""GPU parity of slicemoe_backward against the fp64 CPU oracle's backward (itself pinned by finite differences).
+
+Each case runs the forward on the GPU (inference or training-time router), then the backward with a seeded upstream
+gradient.  The oracle runs its own forward and backward from the same inputs; the routing must agree exactly on these
+cases (no near-tie among them), because a weight gradient sums over every slice.
+Bars, derived from the arithmetic (fp32 throughout, exact GELU; the forward's tolerance is stated for h' only):
+dL/dh is computed in fp32 and rounded once to the storage type, so per element |err| <= 2^-8 |ref| + 2e-4 RMS for
+bf16 storage (half a unit in the last place of 8 significant bits is at most 2^-8 relative; the RMS term covers the
+fp32 error, measured 3e-6 RMS, also where it moves a value across a rounding boundary) and <= 1e-4 RMS for fp32 storage; a max-over-RMS bar does not fit here, because with the
+renormalised probabilities of the dropout a few slices carry gradients ten times the RMS.  The fp32 weight gradients:
+5e-4 of the tensor's RMS (fp32 sums of up to ~10^4 terms over fp32 recomputed activations; measured 1e-5).
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2510_04286_amd import workload as wl
+from tests.common import TOL_F32, make_inputs, rms, routing_agreement
+
+pytestmark = pytest.mark.gpu
+
+NAMES = ("Wr1", "br1", "Wr2", "br2", "W1", "b1", "W2", "b2")
+TOL_WGRAD = 5e-4
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need an MI355X"
+    from paper_2510_04286_amd import binding
+    binding.lib()
+    return binding
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+CASES = {
+    # name: (shape, T, training-time router parameters or None)
+    "tiny": (wl.CONFIGS["tiny"], 96, None),                                        # fp32 storage
+    "tiny_train": (wl.CONFIGS["tiny"], 61, dict(tau=0.8, sigma=0.3, rate=0.25)),
+    "lm": (wl.CONFIGS["lm"], 200, None),
+    "headline": (wl.CONFIGS["headline"], 130, None),                               # ragged batches of rows
+    "headline_train": (wl.CONFIGS["headline"], 96, dict(tau=1.5, sigma=0.2, rate=0.2)),
+    "skewed": (wl.CONFIGS["skewed"], 256, None),                                   # capacity drops
+    "paper": (wl.CONFIGS["paper"], 100, dict(tau=1.0, sigma=0.0, rate=0.2)),       # slice width 96: two feature chunks
+    "paper_S2": (wl.CONFIGS["paper_S2_k2"], 40, None),                             # He = 1536: six hidden groups (atomic rows)
+    "k3": (wl.SliceMoEShape("k3", T=150, d=256, S=4, E=8, k=3, He=96), None, dict(tau=0.7, sigma=0.0, rate=0.3)),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_backward_matches_oracle(B, name):
+    import torch
+    base, T, train = CASES[name]
+    shape, h, w = make_inputs(base, T)
+    cfg = B.config_of(shape)
+    dout = wl.make_dout(shape)
+    noise, drop_u = wl.make_router_draws(shape)
+    okw = dict(tau=1.0, sigma=0.0, rate=0.0)
+    if train:
+        okw.update(train)
+    ref_f = oracle.forward_train(h, shape.S, shape.k, w, noise=noise, drop_u=drop_u, capacity=shape.capacity(), **okw)
+    ref = oracle.backward(h, shape.S, shape.k, w, dout, ref_f["idx"], ref_f["inv"], noise=noise, drop_u=drop_u, **okw)
+
+    wd = B.pack(cfg, B.weights_to_device(w, shape.dtype))
+    ws = B.alloc_workspace(cfg)
+    tdt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+    hd = B.to_device(h, shape.dtype)
+    out = torch.empty((shape.T, shape.d), dtype=tdt, device="cuda:0")
+    tkw = None
+    if train:
+        tkw = dict(temperature=okw["tau"], noise_std=okw["sigma"], dropout_rate=okw["rate"], noise=dev(noise),
+                   drop_u=dev(drop_u))
+        B.slicemoe_forward_train(cfg, hd, wd, out, ws, **tkw)
+    else:
+        B.slicemoe_forward(cfg, hd, wd, out, ws)
+    grads = B.alloc_weight_grads(cfg)
+    for t in grads.values():
+        t.fill_(7.0)          # the call overwrites
+    d_h = torch.full((shape.T, shape.d), 5.0, dtype=tdt, device="cuda:0")
+    bws = torch.empty(B.slicemoe_backward_workspace_bytes(cfg), dtype=torch.uint8, device="cuda:0")
+    B.slicemoe_backward(cfg, hd, wd, ws, B.to_device(dout, shape.dtype), d_h, grads, bws, train=tkw)
+    torch.cuda.synchronize()
+
+    views = B.workspace_views(cfg, ws)
+    mism, n_tie = routing_agreement(views["topk_idx"].cpu().numpy(), ref_f["idx"], ref_f["logits"])
+    assert n_tie == 0, "this case was chosen to have no near-tie; pick another token count"
+    np.testing.assert_array_equal(views["inv"].cpu().numpy(), ref_f["inv"])
+
+    got_dh = d_h.float().cpu().numpy().astype(np.float64)
+    scale_dh = rms(ref["d_h"])
+    if shape.dtype == "f32":
+        bound = np.full_like(ref["d_h"], TOL_F32 * scale_dh)
+    else:
+        bound = 2.0 ** -8 * np.abs(ref["d_h"]) + 2e-4 * scale_dh
+    excess = np.abs(got_dh - ref["d_h"]) / bound
+    err_dh = np.abs(got_dh - ref["d_h"]).max() / scale_dh
+    report = [f"d_h {err_dh:.2e} (worst element at {excess.max():.2f} of its bound)"]
+    for n in NAMES:
+        got = grads[n].cpu().numpy().astype(np.float64)
+        assert got.shape == ref[n].shape
+        scale = rms(ref[n])
+        err = np.abs(got - ref[n]).max() / scale if scale > 0 else np.abs(got).max()
+        report.append(f"{n} {err:.1e}")
+        assert err <= TOL_WGRAD, (n, err)
+    print(f"\n[backward {name}] rows={int(ref_f['offsets'][-1])} max|err|/rms: " + " ".join(report))
+    assert excess.max() <= 1.0, excess.max()
+
+
+def test_backward_argument_checks_on_device(B):
+    """Too small a workspace is reported, nothing is launched."""
+    import torch
+    shape, h, w = make_inputs(wl.CONFIGS["tiny"], 16)
+    cfg = B.config_of(shape)
+    wd = B.weights_to_device(w, shape.dtype)
+    ws = B.alloc_workspace(cfg)
+    hd = B.to_device(h, shape.dtype)
+    grads = B.alloc_weight_grads(cfg)
+    small = torch.empty(256, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(B.SliceMoEError) as ei:
+        B.slicemoe_backward(cfg, hd, wd, ws, hd, torch.empty_like(hd), grads, small)
+    assert ei.value.status == B.SLICEMOE_ERR_WORKSPACE
