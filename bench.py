@@ -28,6 +28,10 @@ PEAK_HBM_GBS = 8000.0           # MI355X HBM3E
 FFN_TRAFFIC_BYTES = {"headline": 115647560}
 
 
+def n_kept_rows(B, cfg, ws):
+    return int(B.workspace_views(cfg, ws)["offsets"][-1].item())
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -39,6 +43,8 @@ def main():
     ap.add_argument("--train-router", default=None, metavar="TAU,SIGMA,RATE",
                     help="run the layer with the training-time router: softmax temperature, logit-noise std, "
                          "cross-slice dropout rate (e.g. 1.0,0.1,0.2); the draws are seeded inputs resident in HBM")
+    ap.add_argument("--backward", action="store_true",
+                    help="also time slicemoe_backward after the forward (reported under \"backward\"; the metric stays the forward)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -185,6 +191,31 @@ def main():
                 "sustained_clock_ghz": round(clock_ghz, 3),
                 "frac_of_peak_at_sustained_clock": round(achieved / (PEAK_MFMA_BF16_TFLOPS * clock_ghz / 2.4), 4)}
 
+    backward = None
+    if args.backward:
+        # one forward leaves the routing in sets[0]'s workspace; the backward is timed on it with events on the launch stream
+        hh, oo, ws = sets[0]
+        step(0)
+        grads = B.alloc_weight_grads(cfg)
+        bws = torch.empty(B.slicemoe_backward_workspace_bytes(cfg), dtype=torch.uint8, device=dev)
+        d_out = B.to_device(wl.make_dout(shape), shape.dtype, dev)
+        d_h = torch.empty_like(hh)
+        nb = max(3, min(args.steps, 10))
+        evs = []
+        for i in range(2 + nb):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            B.slicemoe_backward(cfg, hh, wd, ws, d_out, d_h, grads, bws, train=train)
+            e1.record()
+            evs.append((e0, e1))
+        torch.cuda.synchronize()
+        bms = sum(a.elapsed_time(b) for a, b in evs[2:]) / nb
+        # five contractions of 2 ds He flop per kept row (recomputed x W1, dy W2^T, dz W1^T, and the two weight
+        # gradients) plus the router's three passes forward-size each way
+        bflops = 10 * ds * He * n_kept_rows(B, cfg, ws) + 6 * Ns * (ds * Hr + Hr * E)
+        backward = {"ms": round(bms, 4), "calls": nb, "flops": bflops, "tflops": round(bflops / (bms * 1e-3) / 1e12, 2),
+                    "kernels": "vector-ALU fp32", "frac_of_fp32_vector_peak": round(bflops / (bms * 1e-3) / 1e12 / 157.3, 4)}
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -220,6 +251,7 @@ def main():
         "load": {"cv2": round(stats[0], 5), "ele": round(stats[1], 5), "drop_fraction": round(stats[2], 5)},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        **({"backward": backward} if backward else {}),
     }
     print(json.dumps(line))
 

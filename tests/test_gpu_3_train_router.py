@@ -5,13 +5,18 @@ inputs from the seeded generator, identical on both sides.
 Bars: as for the inference router -- routing equal except near-ties of the (noisy) fp32 logits, which are counted
 and masked; selected probabilities to 5e-5 relative (they carry the fp32 logit error divided by the temperature);
 which assignments the dropout zeroes is an exact fp32 comparison of the same draws, so it must agree exactly.
+The layer output under the training-time router: the 2e-2 RMS bar of the inference layer is a statement about that
+workload (outputs within 4 RMS); with the dropout's renormalised probabilities (0.5 instead of 0.04) a few outputs
+reach 7 RMS and their one bf16 rounding alone exceeds it.  The bar here is per element, from the arithmetic:
+|err| <= 2^-8 |ref| (half a unit in the last place of bf16) + 1e-2 RMS (expert stage: packed-fp16 activation,
+fp16 stacked outputs; measured 6e-3 RMS at full size); 1e-4 RMS for fp32 storage as before.
 """
 import numpy as np
 import pytest
 
 import oracle
 from paper_2510_04286_amd import workload as wl
-from tests.common import NEAR_TIE, TOL_BF16, TOL_F32, make_inputs, rms, routing_agreement
+from tests.common import NEAR_TIE, TOL_F32, make_inputs, rms, routing_agreement
 
 pytestmark = pytest.mark.gpu
 
@@ -72,6 +77,16 @@ def test_route_train_matches_oracle(B, name, tau, sigma, rate):
         assert np.any(plain["idx"] != gi)
 
 
+def output_excess(got, ref, dtype, mask=None):
+    """max over the elements of |err| / bound, and max |err| / RMS, for the layer output under the training router."""
+    scale = rms(ref)
+    err = np.abs(got - ref)
+    bound = np.full_like(ref, TOL_F32 * scale) if dtype == "f32" else 2.0 ** -8 * np.abs(ref) + 1e-2 * scale
+    if mask is not None:
+        err, bound = err[mask], bound[mask]
+    return float((err / bound).max()), float(err.max() / scale)
+
+
 def test_route_train_with_plain_parameters_is_the_inference_router(B):
     import torch
     shape, h, w = make_inputs(wl.CONFIGS["headline"], 512)
@@ -113,9 +128,41 @@ def test_forward_train_matches_oracle(B, name, T):
     if n_tie == 0:
         for n in ("counts_raw", "counts", "offsets", "inv"):
             np.testing.assert_array_equal(views[n], ref[n], err_msg=n)
-    tol = TOL_F32 if shape.dtype == "f32" else TOL_BF16
-    diff = np.abs(got - ref["h_out"]).reshape(-1, shape.ds)
-    err = diff[~mism].max() / rms(ref["h_out"])
-    print(f"\n[forward_train {name}] slices={shape.Ns} near-tie mismatches={n_tie} max|err|/rms={err:.3e} (bar {tol:g})")
-    assert err <= tol
+    keep = np.repeat(~mism, shape.ds).reshape(-1, shape.ds)
+    excess, err = output_excess(got.reshape(-1, shape.ds), ref["h_out"].reshape(-1, shape.ds), shape.dtype, keep)
+    print(f"\n[forward_train {name}] slices={shape.Ns} near-tie mismatches={n_tie} max|err|/rms={err:.3e}, worst "
+          f"element at {excess:.2f} of its bound")
+    assert excess <= 1.0
     assert mism.sum() <= max(8, 1e-4 * shape.Ns)
+
+
+def test_forward_train_headline_at_full_size(B):
+    """The headline workload with the training-time router at the size that is timed: whole-layer comparison with the
+    oracle on all 262 144 slices."""
+    import torch
+    shape, h, w = make_inputs(wl.CONFIGS["headline"])
+    cfg = B.config_of(shape)
+    noise, drop_u = wl.make_router_draws(shape)
+    tau, sigma, rate = 1.0, 0.1, 0.2
+    ref = oracle.forward_train(h, shape.S, shape.k, w, tau=tau, sigma=sigma, noise=noise, rate=rate, drop_u=drop_u)
+    wd = B.pack(cfg, B.weights_to_device(w, shape.dtype))
+    ws = B.alloc_workspace(cfg)
+    out = torch.empty((shape.T, shape.d), dtype=torch.bfloat16, device="cuda:0")
+    B.slicemoe_forward_train(cfg, B.to_device(h, shape.dtype), wd, out, ws, temperature=tau, noise_std=sigma,
+                             dropout_rate=rate, noise=dev(noise), drop_u=dev(drop_u))
+    torch.cuda.synchronize()
+    views = {n: v.cpu().numpy() for n, v in B.workspace_views(cfg, ws).items() if n != "y"}
+    got = out.float().cpu().numpy().astype(np.float64)
+    mism, n_tie = routing_agreement(views["topk_idx"], ref["idx"], ref["logits"])
+    bad = mism
+    if n_tie == 0:
+        for n in ("counts_raw", "counts", "offsets", "inv"):
+            np.testing.assert_array_equal(views[n], ref[n], err_msg=n)
+    keep = np.repeat(~bad, shape.ds).reshape(-1, shape.ds)
+    excess, err = output_excess(got.reshape(-1, shape.ds), ref["h_out"].reshape(-1, shape.ds), shape.dtype, keep)
+    zero = views["topk_p"] == 0
+    print(f"\n[forward_train headline full] near-tie mismatches={n_tie} max|err|/rms={err:.3e}, worst element at "
+          f"{excess:.2f} of its bound, dropped share={zero.mean():.4f}")
+    np.testing.assert_array_equal(zero[~bad], ref["pk"][~bad] == 0)
+    assert excess <= 1.0
+    assert bad.sum() <= max(8, 1e-4 * shape.Ns)

@@ -47,6 +47,7 @@ CASES = {
     "skewed": (wl.CONFIGS["skewed"], 256, None),                                   # capacity drops
     "paper": (wl.CONFIGS["paper"], 100, dict(tau=1.0, sigma=0.0, rate=0.2)),       # slice width 96: two feature chunks
     "paper_S2": (wl.CONFIGS["paper_S2_k2"], 40, None),                             # He = 1536: six hidden groups (atomic rows)
+    "headline_4k": (wl.CONFIGS["headline"], 4096, None),                           # 131 072 rows: many blocks per expert
     "k3": (wl.SliceMoEShape("k3", T=150, d=256, S=4, E=8, k=3, He=96), None, dict(tau=0.7, sigma=0.0, rate=0.3)),
 }
 
