@@ -25,7 +25,7 @@ PEAK_MFMA_BF16_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0           # MI355X HBM3E
 # HBM bytes per launch of the expert FFN kernel on the headline workload, from rocprofv3 --pmc
 # (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size); None until measured.
-FFN_TRAFFIC_BYTES = {"headline": 115647560}
+FFN_TRAFFIC_BYTES = {"headline": 115627759}
 
 
 def n_kept_rows(B, cfg, ws):
