@@ -249,8 +249,9 @@ slicemoe_status slicemoe_forward_train(const slicemoe_config *cfg, const void *h
  *   forward_workspace    the workspace that forward call filled (routing tables and probabilities are read from it)
  *   d_out [T, d] in      dL/dh', storage dtype
  *   d_h   [T, d] out     dL/dh, storage dtype (one rounding)
- *   grads       out      one fp32 DEVICE array per weight tensor, logical layout, overwritten.  They are summed with
- *                        fp32 atomic adds: the last bits vary from run to run.
+ *   grads       out      one fp32 DEVICE array per weight tensor, logical layout, overwritten.  Partial sums are
+ *                        added in a fixed order: same inputs, bit-identical weight gradients (and dL/dh, unless
+ *                        He > 256, where the hidden units are cut into groups whose parts of dL/dx are added atomically).
  *   workspace            >= slicemoe_backward_workspace_bytes(cfg), 256-byte aligned
  * This version runs on vector-ALU kernels for every shape.  UNSUPPORTED for Hr > 256.
  */

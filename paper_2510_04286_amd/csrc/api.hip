@@ -405,9 +405,7 @@ slicemoe_status slicemoe_forward_train(const slicemoe_config *cfg, const void *h
 size_t slicemoe_backward_workspace_bytes(const slicemoe_config *cfg)
 {
     if (validate(cfg) != SLICEMOE_OK) return 0;
-    const size_t Na = (size_t)cfg->T * cfg->S * cfg->k;
-    const size_t ds = (size_t)(cfg->d / cfg->S);
-    return align_up(Na * ds * sizeof(float), 256) + align_up(Na * sizeof(float), 256) + 256;
+    return backward_plan(*cfg).total;
 }
 
 slicemoe_status slicemoe_backward(const slicemoe_config *cfg, const void *h, const slicemoe_weights *w,
@@ -436,14 +434,10 @@ slicemoe_status slicemoe_backward(const slicemoe_config *cfg, const void *h, con
     if (!workspace || workspace_bytes < slicemoe_backward_workspace_bytes(cfg)) return SLICEMOE_ERR_WORKSPACE;
     if (misaligned(forward_workspace, 256) || misaligned(workspace, 256)) return SLICEMOE_ERR_INVALID_ARG;
     const char *fw = (const char *)forward_workspace;
-    const size_t Na = (size_t)cfg->T * cfg->S * cfg->k;
-    const size_t ds = (size_t)(cfg->d / cfg->S);
-    float *dxrow = (float *)workspace;
-    float *dpk = (float *)((char *)workspace + align_up(Na * ds * sizeof(float), 256));
     const hipError_t e = launch_backward(*cfg, h, *w, v, drop_u, rate, (const int32_t *)(fw + L.topk_idx),
                                          (const float *)(fw + L.topk_p), (const int32_t *)(fw + L.offsets),
                                          (const int32_t *)(fw + L.perm), (const int32_t *)(fw + L.inv), d_out, d_h, *grads,
-                                         dxrow, dpk, (hipStream_t)stream);
+                                         workspace, (hipStream_t)stream);
     return e == hipSuccess ? SLICEMOE_OK : SLICEMOE_ERR_HIP;
 }
 

@@ -8,7 +8,7 @@
 // Two kernels, both straightforward by design (any shape within the library limits, either storage type):
 //   bwd_expert_kernel  a block walks up to kBwdRows stacked rows of ONE expert in batches of kRB, one thread per
 //                      hidden unit: recomputes u = x W1 and z, forms dz = (dy W2^T) gelu'(z), accumulates its
-//                      column of dW1 and its row of dW2 in registers (adds them to memory once, at the end),
+//                      column of dW1 and its row of dW2 in registers (stores them once, at the end),
 //                      reduces dL/dp over the hidden units and writes the row's dL/dx.
 //   bwd_router_kernel  a block walks up to kBwdSlices slices in batches of kRB, one thread per router hidden unit:
 //                      recomputes the router, goes back through the dropout's renormalisation and the softmax to
@@ -17,17 +17,20 @@
 // Wide shapes are cut over the grid: hidden units in groups of 256 (grid.y of the expert kernel; partial dL/dx and
 // dL/dp are then added atomically) and slice features in chunks of kBwdCols (grid.z / grid.y; every chunk recomputes
 // the shared quantities and owns its slice of the weight gradients and of dL/dx).
-// Weight gradients are summed with fp32 atomic adds: their summation order, hence their last bits, vary from run to
-// run.
+// Weight gradients: every block stores its partial sums in its own slot of a scratch buffer, and a second pair of
+// kernels adds the slots up in a fixed order (device-wide atomic adds from a thousand blocks cost more than the
+// arithmetic, and their order varies from run to run; this way the result is reproducible bit for bit).
 #include "common.h"
 
 namespace slicemoe {
 
 constexpr int kBwdThreads = 256;
 constexpr int kBwdRB = 8;         // rows (slices) per batch
-constexpr int kBwdRows = 512;     // stacked rows per block of the expert kernel
-constexpr int kBwdSlices = 256;   // slices per block of the router kernel
+constexpr int kBwdSlices = 512;   // slices per block of the router kernel
 constexpr int kBwdCols = 64;      // slice features per grid chunk (register accumulators per thread)
+
+__host__ __device__ __forceinline__ size_t expert_slot_floats(int ds, int He) { return 2 * (size_t)ds * He + He + ds; }
+__host__ __device__ __forceinline__ size_t router_slot_floats(int ds, int Hr, int E) { return (size_t)ds * Hr + (size_t)Hr * E + Hr + E; }
 
 __global__ void fill_zero_kernel(float *__restrict__ p, size_t n)
 {
@@ -57,34 +60,43 @@ __device__ __forceinline__ float gelu_grad(float z, float *act)
     return cdf + z * expf(-0.5f * z * z) * 0.39894228040143267794f;
 }
 
-template <typename T>
+// Row stride padding (elements) of the weight slices kept in LDS: an odd number of 32-bit words per row, so that
+// threads reading down a column hit different banks.
+template <typename T> constexpr int kWPad = sizeof(T) == 2 ? 2 : 1;
+
+// WLDS: this block's slices of W1 (all features x its 256 hidden units) and W2 (its 256 hidden units x all features)
+// sit in LDS for the whole block (they fit up to ds = 128 with 16-bit storage); otherwise they are read from memory.
+template <typename T, bool WLDS>
 __global__ __launch_bounds__(kBwdThreads) void bwd_expert_kernel(
     const T *__restrict__ x, const T *__restrict__ dout, const float *__restrict__ pk,
     const int32_t *__restrict__ offsets, const int32_t *__restrict__ perm, int ds, int He, int E, int k,
     const T *__restrict__ W1, const T *__restrict__ b1, const T *__restrict__ W2,
-    float *__restrict__ dxrow, float *__restrict__ dpk,
-    float *__restrict__ dW1, float *__restrict__ db1, float *__restrict__ dW2, float *__restrict__ db2)
+    float *__restrict__ dxrow, float *__restrict__ dpk, int rows_per_chunk, float *__restrict__ part)
 {
     extern __shared__ float smem[];
-    float *xs = smem;                          // [kBwdRB][ds]   slice rows (not weighted)
-    float *gs = xs + kBwdRB * ds;              // [kBwdRB][ds]   dL/dh' of the rows' slices
-    float *dzs = gs + kBwdRB * ds;             // [kBwdRB][kBwdThreads] dL/dz of this hidden group
+    const int dsp = (ds + kBwdCols - 1) / kBwdCols * kBwdCols;   // LDS row stride: whole feature chunks, zero-padded
+    float *xs = smem;                          // [kBwdRB][dsp]  slice rows (not weighted)
+    float *gs = xs + kBwdRB * dsp;             // [kBwdRB][dsp]  dL/dh' of the rows' slices
+    float *dzs = gs + kBwdRB * dsp;            // [kBwdRB][kBwdThreads] dL/dz of this hidden group
+    const int w1st = kBwdThreads + kWPad<T>, w2st = ds + kWPad<T>;
+    T *w1s = (T *)(dzs + kBwdRB * kBwdThreads);   // [ds][w1st]          (WLDS only)
+    T *w2s = w1s + (size_t)ds * w1st;             // [kBwdThreads][w2st] (WLDS only)
     __shared__ float ps[kBwdRB];               // final probability of each row
-    __shared__ float dps[kBwdRB];              // dL/dp of each row (this hidden group's part)
+    __shared__ float dps[kBwdThreads / 64][kBwdRB];   // dL/dp of each row: one partial sum per wavefront
     __shared__ int as[kBwdRB];                 // assignment id of each row
     __shared__ int blk[3];                     // expert, first row, end row of this block
 
     const int tid = threadIdx.x;
     if (tid == 0) {
-        // chunks of kBwdRows rows, never across an expert boundary: find the chunk blockIdx.x names
+        // chunks of rows_per_chunk rows, never across an expert boundary: find the chunk blockIdx.x names
         int left = (int)blockIdx.x, e = 0, begin = 0, end = 0;
         bool found = false;
         for (e = 0; e < E; ++e) {
             const int lo = offsets[e], hi = offsets[e + 1];
-            const int nch = (hi - lo + kBwdRows - 1) / kBwdRows;
+            const int nch = (hi - lo + rows_per_chunk - 1) / rows_per_chunk;
             if (left < nch) {
-                begin = lo + left * kBwdRows;
-                end = min(hi, begin + kBwdRows);
+                begin = lo + left * rows_per_chunk;
+                end = min(hi, begin + rows_per_chunk);
                 found = true;
                 break;
             }
@@ -106,6 +118,24 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_expert_kernel(
     const T *w1 = W1 + (size_t)e * ds * He;
     const T *w2 = W2 + (size_t)e * He * ds;
     const float bias = jok ? Storage<T>::load(b1 + (size_t)e * He + j) : 0.f;
+    const int jg0 = (int)blockIdx.y * kBwdThreads;
+    const int ds4 = (ds + 3) & ~3;
+    if (WLDS) {   // ordered before the first read by the barriers at the top of the row loop
+        for (int t = tid; t < ds * kBwdThreads; t += kBwdThreads) {
+            const int i = t / kBwdThreads, jj = t - i * kBwdThreads;
+            w1s[i * w1st + jj] = jg0 + jj < He ? w1[(size_t)i * He + jg0 + jj] : (T)0;
+        }
+        for (int t = tid; t < kBwdThreads * ds; t += kBwdThreads) {
+            const int jj = t / ds, c = t - jj * ds;
+            w2s[jj * w2st + c] = jg0 + jj < He ? w2[(size_t)(jg0 + jj) * ds + c] : (T)0;
+        }
+    }
+    auto w1_at = [&](int i, int jj) -> float {   // W1[e][i][jg0 + jj]
+        return WLDS ? Storage<T>::load(w1s + i * w1st + jj) : Storage<T>::load(w1 + (size_t)i * He + jg0 + jj);
+    };
+    auto w2_at = [&](int jj, int c) -> float {   // W2[e][jg0 + jj][c]
+        return WLDS ? Storage<T>::load(w2s + jj * w2st + c) : Storage<T>::load(w2 + (size_t)(jg0 + jj) * ds + c);
+    };
 
     float aW1[kBwdCols], aW2[kBwdCols];
 #pragma unroll
@@ -118,13 +148,12 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_expert_kernel(
             const int a = tid < rows ? perm[r0 + tid] : 0;
             as[tid] = a;
             ps[tid] = tid < rows ? pk[a] : 0.f;
-            dps[tid] = 0.f;
         }
         __syncthreads();
-        for (int i = tid; i < kBwdRB * ds; i += kBwdThreads) {
-            const int r = i / ds, c = i - r * ds;
+        for (int i = tid; i < kBwdRB * dsp; i += kBwdThreads) {
+            const int r = i / dsp, c = i - r * dsp;
             float xv = 0.f, gv = 0.f;
-            if (r < rows) {
+            if (r < rows && c < ds) {
                 const long long n = as[r] / k;
                 xv = Storage<T>::load(x + n * ds + c);
                 gv = Storage<T>::load(dout + n * ds + c);
@@ -138,13 +167,26 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_expert_kernel(
 #pragma unroll
         for (int r = 0; r < kBwdRB; ++r) u[r] = da[r] = 0.f;
         if (jok) {
-            for (int i = 0; i < ds; ++i) {
-                const float wv = Storage<T>::load(w1 + (size_t)i * He + j);
-                const float vv = Storage<T>::load(w2 + (size_t)j * ds + i);
+            for (int i = 0; i < ds4; i += 4) {
+                float wv[4], vv[4];
+                if (i + 4 <= ds) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        wv[q] = w1_at(i + q, tid);
+                        vv[q] = w2_at(tid, i + q);
+                    }
+                } else {   // last, partial group of a width that is not a multiple of 4: the tiles hold zeros there
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        wv[q] = i + q < ds ? w1_at(i + q, tid) : 0.f;
+                        vv[q] = i + q < ds ? w2_at(tid, i + q) : 0.f;
+                    }
+                }
 #pragma unroll
                 for (int r = 0; r < kBwdRB; ++r) {
-                    u[r] = fmaf(xs[r * ds + i], wv, u[r]);
-                    da[r] = fmaf(gs[r * ds + i], vv, da[r]);
+                    const float4 xq = *(const float4 *)(xs + r * dsp + i), gq = *(const float4 *)(gs + r * dsp + i);
+                    u[r] = fmaf(xq.x, wv[0], fmaf(xq.y, wv[1], fmaf(xq.z, wv[2], fmaf(xq.w, wv[3], u[r]))));
+                    da[r] = fmaf(gq.x, vv[0], fmaf(gq.y, vv[1], fmaf(gq.z, vv[2], fmaf(gq.w, vv[3], da[r]))));
                 }
             }
         }
@@ -157,60 +199,95 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_expert_kernel(
                 dz = da[r] * gelu_grad(z, &act);
                 pdz = p * dz;
                 ab1 += dz;
+                // the whole chunk of kBwdCols features: past the slice width the tiles hold zeros
 #pragma unroll
-                for (int c = 0; c < kBwdCols; ++c)
-                    if (c < ncols) {
-                        aW2[c] = fmaf(act, gs[r * ds + c0 + c], aW2[c]);
-                        aW1[c] = fmaf(xs[r * ds + c0 + c], pdz, aW1[c]);
-                    }
+                for (int c = 0; c < kBwdCols; c += 4) {
+                    const float4 gq = *(const float4 *)(gs + r * dsp + c0 + c), xq = *(const float4 *)(xs + r * dsp + c0 + c);
+                    aW2[c] = fmaf(act, gq.x, aW2[c]);
+                    aW2[c + 1] = fmaf(act, gq.y, aW2[c + 1]);
+                    aW2[c + 2] = fmaf(act, gq.z, aW2[c + 2]);
+                    aW2[c + 3] = fmaf(act, gq.w, aW2[c + 3]);
+                    aW1[c] = fmaf(xq.x, pdz, aW1[c]);
+                    aW1[c + 1] = fmaf(xq.y, pdz, aW1[c + 1]);
+                    aW1[c + 2] = fmaf(xq.z, pdz, aW1[c + 2]);
+                    aW1[c + 3] = fmaf(xq.w, pdz, aW1[c + 3]);
+                }
             }
             dzs[r * kBwdThreads + tid] = dz;
             const float part = wave_sum(dz * u[r]);   // dL/dp = sum over hidden units of dL/dz (x W1)
-            if ((tid & 63) == 0 && r < rows) atomicAdd(&dps[r], part);
+            if ((tid & 63) == 0) dps[tid >> 6][r] = part;   // added up below in a fixed order
         }
         if (blockIdx.y == 0 && tid < ncols)
-            for (int r = 0; r < rows; ++r) ab2 += gs[r * ds + c0 + tid];
+            for (int r = 0; r < rows; ++r) ab2 += gs[r * dsp + c0 + tid];
         __syncthreads();
 
         // dL/dx of the rows, this chunk's features: p * sum over this hidden group of dL/dz W1[i, j]
         const int jcount = min(kBwdThreads, He - (int)blockIdx.y * kBwdThreads);
         for (int t = tid; t < rows * ncols; t += kBwdThreads) {
             const int r = t / ncols, i = c0 + (t - r * ncols);
-            const T *wr = w1 + (size_t)i * He + (size_t)blockIdx.y * kBwdThreads;
             float acc = 0.f;
-            for (int jj = 0; jj < jcount; ++jj) acc = fmaf(dzs[r * kBwdThreads + jj], Storage<T>::load(wr + jj), acc);
+#pragma unroll 8
+            for (int jj = 0; jj < jcount; ++jj) acc = fmaf(dzs[r * kBwdThreads + jj], w1_at(i, jj), acc);
             float *dst = dxrow + (size_t)(r0 + r) * ds + i;
             if (atomic_rows) atomicAdd(dst, ps[r] * acc);
             else *dst = ps[r] * acc;
         }
         if (blockIdx.z == 0 && tid < rows) {
-            if (atomic_rows) atomicAdd(dpk + as[tid], dps[tid]);
-            else dpk[as[tid]] = dps[tid];
+            float dp = 0.f;
+#pragma unroll
+            for (int wv = 0; wv < kBwdThreads / 64; ++wv) dp += dps[wv][tid];
+            if (atomic_rows) atomicAdd(dpk + as[tid], dp);
+            else dpk[as[tid]] = dp;
         }
         __syncthreads();
     }
 
+    // this chunk's slot: dW1 [ds][He] | dW2 [He][ds] | db1 [He] | db2 [ds]; the blocks of the chunk (hidden groups x
+    // feature chunks) write disjoint parts of it, every element exactly once
+    float *slot = part + (size_t)blockIdx.x * expert_slot_floats(ds, He);
+    float *pW1 = slot, *pW2 = pW1 + (size_t)ds * He, *pb1 = pW2 + (size_t)He * ds, *pb2 = pb1 + He;
     if (jok) {
 #pragma unroll
         for (int c = 0; c < kBwdCols; ++c)   // constant trip count: the accumulators stay in registers
             if (c < ncols) {
-                atomicAdd(dW1 + ((size_t)e * ds + c0 + c) * He + j, aW1[c]);
-                atomicAdd(dW2 + ((size_t)e * He + j) * ds + c0 + c, aW2[c]);
+                pW1[(size_t)(c0 + c) * He + j] = aW1[c];
+                pW2[(size_t)j * ds + c0 + c] = aW2[c];
             }
-        if (blockIdx.z == 0) atomicAdd(db1 + (size_t)e * He + j, ab1);
+        if (blockIdx.z == 0) pb1[j] = ab1;
     }
-    if (blockIdx.y == 0 && tid < ncols) atomicAdd(db2 + (size_t)e * ds + c0 + tid, ab2);
+    if (blockIdx.y == 0 && tid < ncols) pb2[c0 + tid] = ab2;
+}
+
+// Sum of the chunk slots of each expert, in chunk order: grid (E, pieces of the slot), one thread per slot element.
+__global__ __launch_bounds__(256) void bwd_reduce_expert_kernel(
+    const float *__restrict__ part, const int32_t *__restrict__ offsets, int ds, int He, int E, int rows_per_chunk,
+    float *__restrict__ dW1, float *__restrict__ db1, float *__restrict__ dW2, float *__restrict__ db2)
+{
+    const int e = blockIdx.x;
+    const size_t slot = expert_slot_floats(ds, He);
+    const size_t t = (size_t)blockIdx.y * blockDim.x + threadIdx.x;
+    if (t >= slot) return;
+    int first = 0;   // chunks are numbered expert by expert, as the expert kernel finds them
+    for (int q = 0; q < e; ++q) first += (offsets[q + 1] - offsets[q] + rows_per_chunk - 1) / rows_per_chunk;
+    const int nch = (offsets[e + 1] - offsets[e] + rows_per_chunk - 1) / rows_per_chunk;
+    float acc = 0.f;
+    for (int c = 0; c < nch; ++c) acc += part[(size_t)(first + c) * slot + t];
+    const size_t nW = (size_t)ds * He;
+    if (t < nW) dW1[(size_t)e * nW + t] = acc;
+    else if (t < 2 * nW) dW2[(size_t)e * nW + (t - nW)] = acc;
+    else if (t < 2 * nW + He) db1[(size_t)e * He + (t - 2 * nW)] = acc;
+    else db2[(size_t)e * ds + (t - 2 * nW - He)] = acc;
 }
 
 // Router backward and the assembly of dL/dh.  Hr <= kBwdThreads (one thread per router hidden unit), E <= 64.
-template <typename T>
+// WLDS: both router matrices sit in LDS for the whole block (they fit up to ds = 128 with 16-bit storage).
+template <typename T, bool WLDS>
 __global__ __launch_bounds__(kBwdThreads) void bwd_router_kernel(
     const T *__restrict__ x, long long Ns, int ds, int Hr, int E, int k,
     const T *__restrict__ Wr1, const T *__restrict__ br1, const T *__restrict__ Wr2, const T *__restrict__ br2,
     const float *__restrict__ noise, float sigma, float inv_tau, const float *__restrict__ drop_u, float rate,
     const int32_t *__restrict__ idx, const int32_t *__restrict__ inv, const float *__restrict__ dpk,
-    const float *__restrict__ dxrow, T *__restrict__ dh,
-    float *__restrict__ dWr1, float *__restrict__ dbr1, float *__restrict__ dWr2, float *__restrict__ dbr2)
+    const float *__restrict__ dxrow, T *__restrict__ dh, float *__restrict__ part)
 {
     extern __shared__ float smem[];
     float *xs = smem;                      // [kBwdRB][ds]
@@ -218,6 +295,9 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_router_kernel(
     float *gs = us + kBwdRB * Hr;          // [kBwdRB][E]   logits, then softmax probabilities
     float *dgs = gs + kBwdRB * E;          // [kBwdRB][E]   dL/dg
     float *dus = dgs + kBwdRB * E;         // [kBwdRB][Hr]  dL/d(pre-activation of the hidden layer)
+    const int w1st = Hr + kWPad<T>, w2st = E + kWPad<T>;
+    T *w1s = (T *)(dus + kBwdRB * Hr);     // [ds][w1st]  (WLDS only)
+    T *w2s = w1s + (size_t)ds * w1st;      // [Hr][w2st]  (WLDS only)
 
     const int tid = threadIdx.x;
     const int c0 = (int)blockIdx.y * kBwdCols;
@@ -234,6 +314,23 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_router_kernel(
     for (int e = 0; e < 64; ++e) aWr2[e] = 0.f;
     float abr1 = 0.f, abr2 = 0.f;
     const float hbias = hok ? Storage<T>::load(br1 + tid) : 0.f;
+    const bool vec4 = (ds & 3) == 0;
+    if (WLDS) {   // ordered before the first read by the barrier after the slice loads
+        for (int t = tid; t < ds * Hr; t += kBwdThreads) {
+            const int i = t / Hr, jh = t - i * Hr;
+            w1s[i * w1st + jh] = Wr1[t];
+        }
+        for (int t = tid; t < Hr * E; t += kBwdThreads) {
+            const int jh = t / E, e = t - jh * E;
+            w2s[jh * w2st + e] = Wr2[t];
+        }
+    }
+    auto w1_at = [&](int i, int jh) -> float {   // Wr1[i][jh]
+        return WLDS ? Storage<T>::load(w1s + i * w1st + jh) : Storage<T>::load(Wr1 + (size_t)i * Hr + jh);
+    };
+    auto w2_at = [&](int jh, int e) -> float {   // Wr2[jh][e]
+        return WLDS ? Storage<T>::load(w2s + jh * w2st + e) : Storage<T>::load(Wr2 + (size_t)jh * E + e);
+    };
 
     for (long long n0 = n_begin; n0 < n_end; n0 += kBwdRB) {
         const int rows = (int)min((long long)kBwdRB, n_end - n0);
@@ -247,10 +344,21 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_router_kernel(
             float acc[kBwdRB];
 #pragma unroll
             for (int r = 0; r < kBwdRB; ++r) acc[r] = hbias;
-            for (int i = 0; i < ds; ++i) {
-                const float wv = Storage<T>::load(Wr1 + (size_t)i * Hr + tid);
+            if (vec4) {
+                for (int i = 0; i < ds; i += 4) {
+                    const float w0 = w1_at(i, tid), w1v = w1_at(i + 1, tid), w2v = w1_at(i + 2, tid), w3 = w1_at(i + 3, tid);
 #pragma unroll
-                for (int r = 0; r < kBwdRB; ++r) acc[r] = fmaf(xs[r * ds + i], wv, acc[r]);
+                    for (int r = 0; r < kBwdRB; ++r) {
+                        const float4 xq = *(const float4 *)(xs + r * ds + i);
+                        acc[r] = fmaf(xq.x, w0, fmaf(xq.y, w1v, fmaf(xq.z, w2v, fmaf(xq.w, w3, acc[r]))));
+                    }
+                }
+            } else {
+                for (int i = 0; i < ds; ++i) {
+                    const float wv = w1_at(i, tid);
+#pragma unroll
+                    for (int r = 0; r < kBwdRB; ++r) acc[r] = fmaf(xs[r * ds + i], wv, acc[r]);
+                }
             }
 #pragma unroll
             for (int r = 0; r < kBwdRB; ++r) us[r * Hr + tid] = fmaxf(acc[r], 0.f);
@@ -260,7 +368,8 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_router_kernel(
         for (int t = tid; t < kBwdRB * E; t += kBwdThreads) {
             const int r = t / E, e = t - r * E;
             float acc = Storage<T>::load(br2 + e);
-            for (int jh = 0; jh < Hr; ++jh) acc = fmaf(us[r * Hr + jh], Storage<T>::load(Wr2 + (size_t)jh * E + e), acc);
+#pragma unroll 8
+            for (int jh = 0; jh < Hr; ++jh) acc = fmaf(us[r * Hr + jh], w2_at(jh, e), acc);
             if (noise != nullptr && r < rows) acc = fmaf(sigma, noise[(n0 + r) * E + e], acc);
             gs[t] = acc;
         }
@@ -327,7 +436,7 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_router_kernel(
                 float acc = 0.f;
                 for (int e = 0; e < E; ++e) {
                     const float d = dgs[r * E + e];
-                    acc = fmaf(d, Storage<T>::load(Wr2 + (size_t)tid * E + e), acc);
+                    acc = fmaf(d, w2_at(tid, e), acc);
                 }
                 const float du = uv > 0.f ? acc : 0.f;
                 dus[r * Hr + tid] = du;
@@ -349,9 +458,9 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_router_kernel(
         for (int t = tid; t < rows * ncols; t += kBwdThreads) {
             const int r = t / ncols, i = c0 + (t - r * ncols);
             const long long n = n0 + r;
-            const T *wr = Wr1 + (size_t)i * Hr;
             float acc = 0.f;
-            for (int jh = 0; jh < Hr; ++jh) acc = fmaf(dus[r * Hr + jh], Storage<T>::load(wr + jh), acc);
+#pragma unroll 8
+            for (int jh = 0; jh < Hr; ++jh) acc = fmaf(dus[r * Hr + jh], w1_at(i, jh), acc);
             for (int jj = 0; jj < k; ++jj) {
                 const int row = inv[n * k + jj];
                 if (row >= 0) acc += dxrow[(size_t)row * ds + i];
@@ -361,47 +470,95 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_router_kernel(
         __syncthreads();
     }
 
+    // this block's slot: dWr1 [ds][Hr] | dWr2 [Hr][E] | dbr1 [Hr] | dbr2 [E]; the feature chunks of one range of slices
+    // (grid.y) share a slot and write disjoint parts of it
+    float *slot = part + (size_t)blockIdx.x * router_slot_floats(ds, Hr, E);
+    float *pWr1 = slot, *pWr2 = pWr1 + (size_t)ds * Hr, *pbr1 = pWr2 + (size_t)Hr * E, *pbr2 = pbr1 + Hr;
     if (hok) {
 #pragma unroll
         for (int c = 0; c < kBwdCols; ++c)
-            if (c < ncols) atomicAdd(dWr1 + (size_t)(c0 + c) * Hr + tid, aWr1[c]);
+            if (c < ncols) pWr1[(size_t)(c0 + c) * Hr + tid] = aWr1[c];
         if (first_chunk) {
-            atomicAdd(dbr1 + tid, abr1);
+            pbr1[tid] = abr1;
 #pragma unroll
             for (int e = 0; e < 64; ++e)
-                if (e < E) atomicAdd(dWr2 + (size_t)tid * E + e, aWr2[e]);
+                if (e < E) pWr2[(size_t)tid * E + e] = aWr2[e];
         }
     }
-    if (first_chunk && tid < E) atomicAdd(dbr2 + tid, abr2);
+    if (first_chunk && tid < E) pbr2[tid] = abr2;
+}
+
+// Sum of the router slots of all blocks, in block order: one thread per slot element.
+__global__ __launch_bounds__(256) void bwd_reduce_router_kernel(
+    const float *__restrict__ part, int nslots, int ds, int Hr, int E,
+    float *__restrict__ dWr1, float *__restrict__ dbr1, float *__restrict__ dWr2, float *__restrict__ dbr2)
+{
+    const size_t slot = router_slot_floats(ds, Hr, E);
+    const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= slot) return;
+    float acc = 0.f;
+    for (int b = 0; b < nslots; ++b) acc += part[(size_t)b * slot + t];
+    const size_t n1 = (size_t)ds * Hr, n2 = (size_t)Hr * E;
+    if (t < n1) dWr1[t] = acc;
+    else if (t < n1 + n2) dWr2[t - n1] = acc;
+    else if (t < n1 + n2 + Hr) dbr1[t - n1 - n2] = acc;
+    else dbr2[t - n1 - n2 - Hr] = acc;
 }
 
 size_t backward_lds_bytes(const slicemoe_config &c)
 {
     const size_t ds = (size_t)(c.d / c.S);
-    const size_t expert = sizeof(float) * (2 * kBwdRB * ds + (size_t)kBwdRB * kBwdThreads);
+    const size_t dsp = (ds + kBwdCols - 1) / kBwdCols * kBwdCols;
+    const size_t expert = sizeof(float) * (2 * kBwdRB * dsp + (size_t)kBwdRB * kBwdThreads);
     const size_t router = sizeof(float) * kBwdRB * (ds + 2 * (size_t)c.Hr + 2 * (size_t)c.E);
     return expert > router ? expert : router;
+}
+
+BackwardPlan backward_plan(const slicemoe_config &c)
+{
+    BackwardPlan p;
+    const size_t Ns = (size_t)c.T * c.S, Na = Ns * c.k;
+    const size_t ds = (size_t)(c.d / c.S);
+    // about a thousand chunks of stacked rows however large the batch (each has a slot of partial weight gradients),
+    // at least 512 rows each, whole batches of rows
+    size_t rows = (Na + 1023) / 1024;
+    rows = (rows + kBwdRB - 1) / kBwdRB * kBwdRB;
+    p.rows_per_chunk = (int)(rows < 512 ? 512 : rows);
+    p.chunks = (long long)((Na + p.rows_per_chunk - 1) / p.rows_per_chunk) + c.E;   // worst case: every expert ends on a partial chunk
+    p.slice_blocks = (long long)((Ns + kBwdSlices - 1) / kBwdSlices);
+    size_t at = 0;
+    p.dxrow = at;  at = align_up(at + Na * ds * sizeof(float), 256);
+    p.dpk = at;    at = align_up(at + Na * sizeof(float), 256);
+    p.expert_part = at;  at = align_up(at + (size_t)p.chunks * expert_slot_floats((int)ds, c.He) * sizeof(float), 256);
+    p.router_part = at;  at = align_up(at + (size_t)p.slice_blocks * router_slot_floats((int)ds, c.Hr, c.E) * sizeof(float), 256);
+    p.total = at + 256;
+    return p;
 }
 
 template <typename T>
 static hipError_t run_backward(const slicemoe_config &c, const void *h, const slicemoe_weights &w, const RouteVariant &v,
                                const float *drop_u, float rate, const int32_t *idx, const float *pk,
                                const int32_t *offsets, const int32_t *perm, const int32_t *inv, const void *d_out,
-                               void *d_h, const slicemoe_weight_grads &g, float *dxrow, float *dpk, hipStream_t s)
+                               void *d_h, const slicemoe_weight_grads &g, void *workspace, hipStream_t s)
 {
     const long long Ns = (long long)c.T * c.S, Na = Ns * c.k;
     const int ds = c.d / c.S;
     const size_t nW = (size_t)c.E * ds * c.He;
     hipError_t e;
-    if ((e = zero_fill(g.Wr1, (size_t)ds * c.Hr, s)) != hipSuccess) return e;
-    if ((e = zero_fill(g.br1, (size_t)c.Hr, s)) != hipSuccess) return e;
-    if ((e = zero_fill(g.Wr2, (size_t)c.Hr * c.E, s)) != hipSuccess) return e;
-    if ((e = zero_fill(g.br2, (size_t)c.E, s)) != hipSuccess) return e;
-    if ((e = zero_fill(g.W1, nW, s)) != hipSuccess) return e;
-    if ((e = zero_fill(g.b1, (size_t)c.E * c.He, s)) != hipSuccess) return e;
-    if ((e = zero_fill(g.W2, nW, s)) != hipSuccess) return e;
-    if ((e = zero_fill(g.b2, (size_t)c.E * ds, s)) != hipSuccess) return e;
-    if (Ns == 0) return hipSuccess;
+    if (Ns == 0) {   // nothing to sum: the gradients are zero
+        if ((e = zero_fill(g.Wr1, (size_t)ds * c.Hr, s)) != hipSuccess) return e;
+        if ((e = zero_fill(g.br1, (size_t)c.Hr, s)) != hipSuccess) return e;
+        if ((e = zero_fill(g.Wr2, (size_t)c.Hr * c.E, s)) != hipSuccess) return e;
+        if ((e = zero_fill(g.br2, (size_t)c.E, s)) != hipSuccess) return e;
+        if ((e = zero_fill(g.W1, nW, s)) != hipSuccess) return e;
+        if ((e = zero_fill(g.b1, (size_t)c.E * c.He, s)) != hipSuccess) return e;
+        if ((e = zero_fill(g.W2, nW, s)) != hipSuccess) return e;
+        return zero_fill(g.b2, (size_t)c.E * ds, s);
+    }
+    const BackwardPlan P = backward_plan(c);
+    char *ws = (char *)workspace;
+    float *dxrow = (float *)(ws + P.dxrow), *dpk = (float *)(ws + P.dpk);
+    float *epart = (float *)(ws + P.expert_part), *rpart = (float *)(ws + P.router_part);
 
     const int hidden_groups = (c.He + kBwdThreads - 1) / kBwdThreads;
     const int col_chunks = (ds + kBwdCols - 1) / kBwdCols;
@@ -409,30 +566,59 @@ static hipError_t run_backward(const slicemoe_config &c, const void *h, const sl
         if ((e = zero_fill(dxrow, (size_t)Na * ds, s)) != hipSuccess) return e;
         if ((e = zero_fill(dpk, (size_t)Na, s)) != hipSuccess) return e;
     }
-    const long long chunks = (Na + kBwdRows - 1) / kBwdRows + c.E;   // worst case: every expert ends on a partial chunk
-    const size_t lds_e = sizeof(float) * (2 * (size_t)kBwdRB * ds + (size_t)kBwdRB * kBwdThreads);
-    bwd_expert_kernel<T><<<dim3((unsigned)chunks, hidden_groups, col_chunks), kBwdThreads, lds_e, s>>>(
-        (const T *)h, (const T *)d_out, pk, offsets, perm, ds, c.He, c.E, c.k, (const T *)w.W1, (const T *)w.b1,
-        (const T *)w.W2, dxrow, dpk, g.W1, g.b1, g.W2, g.b2);
+    const size_t dsp = (size_t)(ds + kBwdCols - 1) / kBwdCols * kBwdCols;
+    const size_t lds_e = sizeof(float) * (2 * (size_t)kBwdRB * dsp + (size_t)kBwdRB * kBwdThreads);
+    const size_t lds_ew = lds_e + sizeof(T) * ((size_t)ds * (kBwdThreads + kWPad<T>) + (size_t)kBwdThreads * (ds + kWPad<T>));
+    const dim3 egrid((unsigned)P.chunks, hidden_groups, col_chunks);
+    if (lds_ew <= (size_t)max_lds_per_block()) {
+        auto kern = bwd_expert_kernel<T, true>;
+        if ((e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_ew)) != hipSuccess)
+            return e;
+        kern<<<egrid, kBwdThreads, lds_ew, s>>>((const T *)h, (const T *)d_out, pk, offsets, perm, ds, c.He, c.E, c.k,
+                                                 (const T *)w.W1, (const T *)w.b1, (const T *)w.W2, dxrow, dpk,
+                                                 P.rows_per_chunk, epart);
+    } else {
+        bwd_expert_kernel<T, false><<<egrid, kBwdThreads, lds_e, s>>>(
+            (const T *)h, (const T *)d_out, pk, offsets, perm, ds, c.He, c.E, c.k, (const T *)w.W1, (const T *)w.b1,
+            (const T *)w.W2, dxrow, dpk, P.rows_per_chunk, epart);
+    }
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    const size_t eslot = expert_slot_floats(ds, c.He);
+    bwd_reduce_expert_kernel<<<dim3((unsigned)c.E, (unsigned)((eslot + 255) / 256)), 256, 0, s>>>(
+        epart, offsets, ds, c.He, c.E, P.rows_per_chunk, g.W1, g.b1, g.W2, g.b2);
     if ((e = hipGetLastError()) != hipSuccess) return e;
 
-    const long long sblocks = (Ns + kBwdSlices - 1) / kBwdSlices;
     const size_t lds_r = sizeof(float) * kBwdRB * ((size_t)ds + 2 * (size_t)c.Hr + 2 * (size_t)c.E);
-    bwd_router_kernel<T><<<dim3((unsigned)sblocks, col_chunks), kBwdThreads, lds_r, s>>>(
-        (const T *)h, Ns, ds, c.Hr, c.E, c.k, (const T *)w.Wr1, (const T *)w.br1, (const T *)w.Wr2, (const T *)w.br2,
-        v.sigma > 0.f ? v.noise : nullptr, v.sigma, v.inv_tau, rate > 0.f ? drop_u : nullptr, rate, idx, inv, dpk, dxrow,
-        (T *)d_h, g.Wr1, g.br1, g.Wr2, g.br2);
+    const size_t lds_rw = lds_r + sizeof(T) * ((size_t)ds * (c.Hr + kWPad<T>) + (size_t)c.Hr * (c.E + kWPad<T>));
+    const dim3 rgrid((unsigned)P.slice_blocks, col_chunks);
+    const float *nz = v.sigma > 0.f ? v.noise : nullptr, *du = rate > 0.f ? drop_u : nullptr;
+    if (lds_rw <= (size_t)max_lds_per_block()) {
+        auto kern = bwd_router_kernel<T, true>;
+        if ((e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_rw)) != hipSuccess)
+            return e;
+        kern<<<rgrid, kBwdThreads, lds_rw, s>>>((const T *)h, Ns, ds, c.Hr, c.E, c.k, (const T *)w.Wr1, (const T *)w.br1,
+                                                 (const T *)w.Wr2, (const T *)w.br2, nz, v.sigma, v.inv_tau, du, rate, idx, inv,
+                                                 dpk, dxrow, (T *)d_h, rpart);
+    } else {
+        bwd_router_kernel<T, false><<<rgrid, kBwdThreads, lds_r, s>>>(
+            (const T *)h, Ns, ds, c.Hr, c.E, c.k, (const T *)w.Wr1, (const T *)w.br1, (const T *)w.Wr2, (const T *)w.br2,
+            nz, v.sigma, v.inv_tau, du, rate, idx, inv, dpk, dxrow, (T *)d_h, rpart);
+    }
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    const size_t rslot = router_slot_floats(ds, c.Hr, c.E);
+    bwd_reduce_router_kernel<<<(unsigned)((rslot + 255) / 256), 256, 0, s>>>(rpart, (int)P.slice_blocks, ds, c.Hr, c.E, g.Wr1,
+                                                                           g.br1, g.Wr2, g.br2);
     return hipGetLastError();
 }
 
 hipError_t launch_backward(const slicemoe_config &c, const void *h, const slicemoe_weights &w, const RouteVariant &v,
                            const float *drop_u, float rate, const int32_t *idx, const float *pk, const int32_t *offsets,
                            const int32_t *perm, const int32_t *inv, const void *d_out, void *d_h,
-                           const slicemoe_weight_grads &g, float *dxrow, float *dpk, hipStream_t s)
+                           const slicemoe_weight_grads &g, void *workspace, hipStream_t s)
 {
     if (c.dtype == SLICEMOE_BF16)
-        return run_backward<bf16_t>(c, h, w, v, drop_u, rate, idx, pk, offsets, perm, inv, d_out, d_h, g, dxrow, dpk, s);
-    return run_backward<float>(c, h, w, v, drop_u, rate, idx, pk, offsets, perm, inv, d_out, d_h, g, dxrow, dpk, s);
+        return run_backward<bf16_t>(c, h, w, v, drop_u, rate, idx, pk, offsets, perm, inv, d_out, d_h, g, workspace, s);
+    return run_backward<float>(c, h, w, v, drop_u, rate, idx, pk, offsets, perm, inv, d_out, d_h, g, workspace, s);
 }
 
 }  // namespace slicemoe

@@ -96,13 +96,21 @@ hipError_t launch_route_generic(const slicemoe_config &c, const void *h, const s
                                 int32_t *idx, float *p, hipStream_t s, const RouteVariant &v = RouteVariant());
 hipError_t launch_route_mfma(const slicemoe_config &c, const void *h, const void *packed,
                              int32_t *idx, float *p, hipStream_t s, const RouteVariant &v = RouteVariant());
-// Backward pass (backward.hip): weight gradients into g (zeroed first), dL/dh into d_h; dxrow[Na, ds] and dpk[Na] are
-// scratch.  backward_lds_bytes: dynamic LDS its kernels ask for.
+// Backward pass (backward.hip): weight gradients into g, dL/dh into d_h.  backward_plan: geometry and layout of its
+// scratch (row gradients, dL/dp, one slot of partial weight gradients per block); backward_lds_bytes: dynamic LDS its
+// kernels ask for at least.
+struct BackwardPlan {
+    int rows_per_chunk;            // stacked rows per block of the expert kernel
+    long long chunks;              // its grid.x (an upper bound on the chunks in use)
+    long long slice_blocks;        // grid.x of the router kernel
+    size_t dxrow, dpk, expert_part, router_part, total;   // byte offsets into the workspace, total size
+};
+BackwardPlan backward_plan(const slicemoe_config &c);
 size_t backward_lds_bytes(const slicemoe_config &c);
 hipError_t launch_backward(const slicemoe_config &c, const void *h, const slicemoe_weights &w, const RouteVariant &v,
                            const float *drop_u, float rate, const int32_t *idx, const float *pk, const int32_t *offsets,
                            const int32_t *perm, const int32_t *inv, const void *d_out, void *d_h,
-                           const slicemoe_weight_grads &g, float *dxrow, float *dpk, hipStream_t s);
+                           const slicemoe_weight_grads &g, void *workspace, hipStream_t s);
 // Cross-slice dropout (Section 3.3) on the selected probabilities p[Ns, k], in place.
 hipError_t launch_route_dropout(const slicemoe_config &c, float *p, const float *drop_u, float rate, hipStream_t s);
 hipError_t launch_dispatch(const slicemoe_config &c, const int32_t *idx, int32_t *counts_raw,
