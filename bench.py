@@ -214,7 +214,8 @@ def main():
         # gradients) plus the router's three passes forward-size each way
         bflops = 10 * ds * He * n_kept_rows(B, cfg, ws) + 6 * Ns * (ds * Hr + Hr * E)
         backward = {"ms": round(bms, 4), "calls": nb, "flops": bflops, "tflops": round(bflops / (bms * 1e-3) / 1e12, 2),
-                    "kernels": "vector-ALU fp32", "frac_of_fp32_vector_peak": round(bflops / (bms * 1e-3) / 1e12 / 157.3, 4)}
+                    "expert_kernels": "matrix-core" if B.slicemoe_backward_uses_mfma(cfg) == 1 else "vector-ALU fp32",
+                    "router_kernels": "vector-ALU fp32"}
 
     cpu = None
     if not args.no_cpu_baseline:

@@ -253,11 +253,16 @@ slicemoe_status slicemoe_forward_train(const slicemoe_config *cfg, const void *h
  *                        added in a fixed order: same inputs, bit-identical weight gradients (and dL/dh, unless
  *                        He > 256, where the hidden units are cut into groups whose parts of dL/dx are added atomically).
  *   workspace            >= slicemoe_backward_workspace_bytes(cfg), 256-byte aligned
- * This version runs on vector-ALU kernels for every shape.  UNSUPPORTED for Hr > 256.
+ * The expert part (row gradients, dL/dp, expert weight gradients) runs on the matrix cores for bf16 storage with
+ * d/S = 64 and He in {64, 128, 256} (slicemoe_backward_uses_mfma: 1, 0, or -1 for an invalid config; fp32
+ * pre-activations and derivative, two-term bf16 operands for the second matrix instructions: fp32-grade results);
+ * every other shape, and the router part always, runs on vector-ALU kernels in fp32.  SLICEMOE_FLAG_FORCE_GENERIC selects those
+ * throughout.  UNSUPPORTED for Hr > 256.
  */
 typedef struct {
     float *Wr1, *br1, *Wr2, *br2, *W1, *b1, *W2, *b2;
 } slicemoe_weight_grads;
+int slicemoe_backward_uses_mfma(const slicemoe_config *cfg);
 size_t slicemoe_backward_workspace_bytes(const slicemoe_config *cfg);
 slicemoe_status slicemoe_backward(const slicemoe_config *cfg, const void *h, const slicemoe_weights *w,
                                   const slicemoe_route_train_params *params, const float *noise, const float *drop_u,

@@ -30,6 +30,7 @@ EXPORTS = [
     "slicemoe_pack_weights", "slicemoe_route", "slicemoe_dispatch", "slicemoe_expert_ffn",
     "slicemoe_combine", "slicemoe_load_stats", "slicemoe_forward", "slicemoe_probe_clock",
     "slicemoe_route_train", "slicemoe_forward_train", "slicemoe_backward_workspace_bytes", "slicemoe_backward",
+    "slicemoe_backward_uses_mfma",
 ]
 
 
@@ -105,6 +106,8 @@ def lib() -> ctypes.CDLL:
         L.slicemoe_route_train.argtypes = [cfgp, vp, wp, tpp, vp, vp, vp, vp, vp, st, vp]
         L.slicemoe_forward_train.restype = ctypes.c_int
         L.slicemoe_forward_train.argtypes = [cfgp, vp, wp, tpp, vp, vp, vp, vp, st, vp]
+        L.slicemoe_backward_uses_mfma.restype = ctypes.c_int
+        L.slicemoe_backward_uses_mfma.argtypes = [cfgp]
         L.slicemoe_backward_workspace_bytes.restype = ctypes.c_size_t
         L.slicemoe_backward_workspace_bytes.argtypes = [cfgp]
         L.slicemoe_backward.restype = ctypes.c_int
@@ -300,6 +303,10 @@ def slicemoe_forward_train(cfg, h, w, h_out, workspace, temperature=1.0, noise_s
     _check(lib().slicemoe_forward_train(ctypes.byref(cfg), _ptr(h, _tdtype(cfg), cfg.T * cfg.d, "h"), ctypes.byref(ws),
                                         ctypes.byref(tp), npt, upt, _ptr(h_out, _tdtype(cfg), cfg.T * cfg.d, "h_out"),
                                         wsp, wsb, _stream(stream)), "slicemoe_forward_train")
+
+
+def slicemoe_backward_uses_mfma(cfg) -> int:
+    return int(lib().slicemoe_backward_uses_mfma(ctypes.byref(cfg)))
 
 
 def slicemoe_backward_workspace_bytes(cfg) -> int:

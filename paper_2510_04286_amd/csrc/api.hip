@@ -402,6 +402,12 @@ slicemoe_status slicemoe_forward_train(const slicemoe_config *cfg, const void *h
     return forward_common(cfg, h, w, v, drop_u, params->dropout_rate, h_out, workspace, workspace_bytes, stream);
 }
 
+int slicemoe_backward_uses_mfma(const slicemoe_config *cfg)
+{
+    if (validate(cfg) != SLICEMOE_OK) return -1;
+    return backward_mfma_shape(*cfg) ? 1 : 0;
+}
+
 size_t slicemoe_backward_workspace_bytes(const slicemoe_config *cfg)
 {
     if (validate(cfg) != SLICEMOE_OK) return 0;

@@ -522,7 +522,7 @@ BackwardPlan backward_plan(const slicemoe_config &c)
     // about a thousand chunks of stacked rows however large the batch (each has a slot of partial weight gradients),
     // at least 512 rows each, whole batches of rows
     size_t rows = (Na + 1023) / 1024;
-    rows = (rows + kBwdRB - 1) / kBwdRB * kBwdRB;
+    rows = (rows + 31) / 32 * 32;   // whole 32-row units of the matrix-core kernels (and whole batches of kBwdRB)
     p.rows_per_chunk = (int)(rows < 512 ? 512 : rows);
     p.chunks = (long long)((Na + p.rows_per_chunk - 1) / p.rows_per_chunk) + c.E;   // worst case: every expert ends on a partial chunk
     p.slice_blocks = (long long)((Ns + kBwdSlices - 1) / kBwdSlices);
@@ -531,6 +531,7 @@ BackwardPlan backward_plan(const slicemoe_config &c)
     p.dpk = at;    at = align_up(at + Na * sizeof(float), 256);
     p.expert_part = at;  at = align_up(at + (size_t)p.chunks * expert_slot_floats((int)ds, c.He) * sizeof(float), 256);
     p.router_part = at;  at = align_up(at + (size_t)p.slice_blocks * router_slot_floats((int)ds, c.Hr, c.E) * sizeof(float), 256);
+    p.packed = at;  at = align_up(at + backward_mfma_packed_bytes(c), 256);
     p.total = at + 256;
     return p;
 }
@@ -566,6 +567,12 @@ static hipError_t run_backward(const slicemoe_config &c, const void *h, const sl
         if ((e = zero_fill(dxrow, (size_t)Na * ds, s)) != hipSuccess) return e;
         if ((e = zero_fill(dpk, (size_t)Na, s)) != hipSuccess) return e;
     }
+    const size_t eslot = expert_slot_floats(ds, c.He);
+    if (backward_mfma_shape(c)) {
+        e = launch_backward_expert_mfma(c, h, w, d_out, pk, offsets, perm, ws + P.packed, P.rows_per_chunk, P.chunks, eslot,
+                                        dxrow, dpk, epart, s);
+        if (e != hipSuccess) return e;
+    } else {
     const size_t dsp = (size_t)(ds + kBwdCols - 1) / kBwdCols * kBwdCols;
     const size_t lds_e = sizeof(float) * (2 * (size_t)kBwdRB * dsp + (size_t)kBwdRB * kBwdThreads);
     const size_t lds_ew = lds_e + sizeof(T) * ((size_t)ds * (kBwdThreads + kWPad<T>) + (size_t)kBwdThreads * (ds + kWPad<T>));
@@ -583,7 +590,7 @@ static hipError_t run_backward(const slicemoe_config &c, const void *h, const sl
             (const T *)w.W2, dxrow, dpk, P.rows_per_chunk, epart);
     }
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    const size_t eslot = expert_slot_floats(ds, c.He);
+    }
     bwd_reduce_expert_kernel<<<dim3((unsigned)c.E, (unsigned)((eslot + 255) / 256)), 256, 0, s>>>(
         epart, offsets, ds, c.He, c.E, P.rows_per_chunk, g.W1, g.b1, g.W2, g.b2);
     if ((e = hipGetLastError()) != hipSuccess) return e;

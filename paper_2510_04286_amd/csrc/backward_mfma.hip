@@ -1,0 +1,498 @@
+// Matrix-core backward of the expert stage for slice width 64 and hidden widths up to 256 (the benchmark
+// shapes): the recomputed pre-activations, dL/dz, dL/dx, dL/dp and the expert weight gradients of the backward
+// pass described in backward.hip, on v_mfma_f32_32x32x16_bf16.  Two kernels, both without any exchange between
+// wavefronts:
+//
+//   bwd_rows_mfma_kernel     the forward's layout: a lane owns one stacked row (see mfma.h).  Per 32-row unit and
+//                            32-wide hidden tile: u = W1^T x and da = W2 dy (weight fragment = A operand, row
+//                            fragment = B), then per lane z = p u + b1, dz = da gelu'(z), and dx += W1 (p dz) with
+//                            p dz fed from the accumulator registers as the B operand, exactly like the forward's
+//                            second GEMM.  dL/dp = sum over the hidden units of dz u is a per-lane sum plus one
+//                            exchange with lane ^ 32.  Writes dL/dx of the rows (fp32) and dL/dp.
+//   bwd_weights_mfma_kernel  the transposed layout, because the weight gradients contract over ROWS, which the
+//                            layout above keeps on lanes.  Swapping the operands of an MFMA transposes its result:
+//                            with the row fragment as A and the weight fragment as B the accumulators come out as
+//                            lane = hidden unit, registers = 16 of the 32 rows.  There z, the activation a1 and
+//                            p dz are formed for the wavefront's own hidden tile, rounded to bf16 pairs (register
+//                            pairs are row pairs: the contraction slots), and dW2 += a1^T dy, dW1 += x^T (p dz) are
+//                            two MFMA pairs per 32 slice features.  The x and dy operands of those (lane = slice
+//                            feature, slots = rows) are the row fragments transposed by an MFMA against an
+//                            identity fragment, which is exact.  A block is one wavefront per hidden tile walking
+//                            the rows of one chunk of one expert; each wavefront stores its 32 x 64 pieces of dW1
+//                            and dW2 into the chunk's slot, which the reduction kernel of backward.hip adds up.
+//
+// Precision: u, da, z, the activation and its derivative in fp32 (erf by the five-term rational approximation of
+// Abramowitz & Stegun 7.1.26, absolute error 1.5e-7, sharing its exponential with the density); the operands of the
+// second-stage matrix instructions (p dz, a1) enter as two-term bf16 splits (hi + lo, 16 significant bits, one
+// matrix instruction per term against exact bf16 data), so the results are of fp32 grade.  The kernels are bound by
+// vector instructions, not by the matrix pipe, so the second term costs little.
+#include "mfma.h"
+
+namespace slicemoe {
+
+constexpr int kBmDS = 64;
+constexpr int kBmKS = kBmDS / 16;
+constexpr int kBmOT = kBmDS / 32;
+constexpr int kBmRowThreads = 768;   // rows kernel: 12 wavefronts of <= 168 registers
+constexpr int kBmRowWaves = kBmRowThreads / 64;
+
+// Backward copies of one expert's weights in fragment order (bytes from the start of the expert's block).
+//   w1f  [HT][KS][64]      W1 fragments as the forward packs them: lane (i, g), slot m: W1[16ks + 8g + m][32ht + i]
+//   w2r  [HT][KS][64]      rows of W2: lane (i, g), slot m: W2[32ht + i][16ks + 8g + m]
+//   w1c  [HT][2][OT][64]   W1 with the hidden units as contraction slots in accumulator order:
+//                          lane (i, g), slot m: W1[32ot + i][32ht + chain_feature(s, g, m)]
+//   b1   [He] fp32
+struct BwdPacked {
+    size_t w1f, w2r, w1c, b1, stride;
+};
+static BwdPacked bwd_packed_layout(int He)
+{
+    BwdPacked L;
+    const size_t frag = (size_t)kBmDS * He * 2;
+    L.w1f = 0;
+    L.w2r = frag;
+    L.w1c = 2 * frag;
+    L.b1 = 3 * frag;
+    L.stride = align_up(3 * frag + (size_t)He * 4, 256);
+    return L;
+}
+
+// One thread per fragment.  Generic strided source so that the same kernel packs a matrix or its transpose:
+// element (kk, col) of the [K, N] matrix being packed is src[kk * rs + col * cs].
+__global__ void bwd_pack_layer1_kernel(const bf16_t *__restrict__ W, int K, int N, size_t rs, size_t cs, size_t src_stride,
+                                       char *__restrict__ dst, size_t dst_stride, int nmat)
+{
+    const int KS = K / 16;
+    const long long per = (long long)(N / 32) * KS * 64;
+    const long long f = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (f >= per * nmat) return;
+    const int mat = (int)(f / per);
+    long long r = f - (long long)mat * per;
+    const int lane = (int)(r % 64);
+    r /= 64;
+    const int ks = (int)(r % KS), nt = (int)(r / KS);
+    const int i = lane & 31, g = lane >> 5;
+    const bf16_t *src = W + (size_t)mat * src_stride;
+    uint32_t v[4];
+    for (int m = 0; m < 8; m += 2) {
+        const uint32_t lo = src[(size_t)(16 * ks + 8 * g + m) * rs + (size_t)(32 * nt + i) * cs];
+        const uint32_t hi = src[(size_t)(16 * ks + 8 * g + m + 1) * rs + (size_t)(32 * nt + i) * cs];
+        v[m / 2] = lo | (hi << 16);
+    }
+    *(uint4 *)(dst + (size_t)mat * dst_stride + (size_t)(f - (long long)mat * per) * 16) = make_uint4(v[0], v[1], v[2], v[3]);
+}
+
+// Fragments [K/32][2][N/32][64] of a [K, N] matrix whose contraction slots follow the accumulator order.
+__global__ void bwd_pack_chain_kernel(const bf16_t *__restrict__ W, int K, int N, size_t rs, size_t cs, size_t src_stride,
+                                      char *__restrict__ dst, size_t dst_stride, int nmat)
+{
+    const int HT = K / 32, NT = N / 32;
+    const long long per = (long long)HT * 2 * NT * 64;
+    const long long f = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (f >= per * nmat) return;
+    const int mat = (int)(f / per);
+    long long r = f - (long long)mat * per;
+    const int lane = (int)(r % 64);
+    r /= 64;
+    const int nt = (int)(r % NT);
+    r /= NT;
+    const int s = (int)(r % 2), ht = (int)(r / 2);
+    const int i = lane & 31, g = lane >> 5;
+    const bf16_t *src = W + (size_t)mat * src_stride;
+    uint32_t v[4];
+    for (int m = 0; m < 8; m += 2) {
+        const uint32_t lo = src[(size_t)(32 * ht + chain_feature(s, g, m)) * rs + (size_t)(32 * nt + i) * cs];
+        const uint32_t hi = src[(size_t)(32 * ht + chain_feature(s, g, m + 1)) * rs + (size_t)(32 * nt + i) * cs];
+        v[m / 2] = lo | (hi << 16);
+    }
+    *(uint4 *)(dst + (size_t)mat * dst_stride + (size_t)(f - (long long)mat * per) * 16) = make_uint4(v[0], v[1], v[2], v[3]);
+}
+
+__global__ void bwd_pack_bias_kernel(const bf16_t *__restrict__ b, int n, size_t src_stride, char *__restrict__ dst,
+                                     size_t dst_stride, int nmat)
+{
+    const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (long long)n * nmat) return;
+    const int mat = (int)(t / n), i = (int)(t - (long long)mat * n);
+    ((float *)(dst + (size_t)mat * dst_stride))[i] = bf16_to_f32(b[(size_t)mat * src_stride + i]);
+}
+
+// Phi(z), and phi(z) through *density: the normal CDF by Abramowitz & Stegun 7.1.26 on |z| / sqrt 2 (|error| < 1.5e-7),
+// whose exponential exp(-z^2 / 2) is the density's.
+__device__ __forceinline__ float normal_cdf_pdf(float z, float *density)
+{
+    const float ax = fabsf(z) * 0.70710678118654752f;
+    const float ex = __builtin_amdgcn_exp2f(-0.72134752044448170f * z * z);   // exp(-z^2 / 2)
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.f));
+    float q = fmaf(1.061405429f, t, -1.453152027f);
+    q = fmaf(q, t, 1.421413741f);
+    q = fmaf(q, t, -0.284496736f);
+    q = fmaf(q, t, 0.254829592f);
+    const float tail = 0.5f * q * t * ex;   // 1 - Phi(|z|)
+    *density = 0.39894228040143267794f * ex;
+    return z > 0.f ? 1.f - tail : tail;
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)   // round to nearest even
+{
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
+// Two-term bf16 split of a pair: hi = bf16(v), lo = bf16(v - hi); hi + lo carries 16 significant bits, so a matrix
+// instruction run once per term is as good as an fp32 operand (the other operand being exact bf16 data).
+__device__ __forceinline__ void split_bf16x2(float a, float b, uint32_t &hi, uint32_t &lo)
+{
+    hi = pack_bf16x2(a, b);
+    lo = pack_bf16x2(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xffff0000u));
+}
+
+// Two fp32 values that are exactly bf16 values (results of an MFMA against an identity): their high halves.
+__device__ __forceinline__ uint32_t pack_exact_bf16x2(float a, float b)
+{
+    return (__float_as_uint(a) >> 16) | (__float_as_uint(b) & 0xffff0000u);
+}
+
+__device__ __forceinline__ void stage_expert(const char *__restrict__ src, char *lds, size_t bytes, int tid, int nthreads)
+{
+    const uint4 *g = (const uint4 *)src;
+    uint4 *l = (uint4 *)lds;
+    const int n = (int)(bytes / 16);
+    for (int i = tid; i < n; i += nthreads) l[i] = g[i];
+}
+
+// ------------------------------------------------------------------------------------------------ rows kernel
+template <int HT>
+__global__ __launch_bounds__(kBmRowThreads) void bwd_rows_mfma_kernel(
+    const bf16_t *__restrict__ x, const bf16_t *__restrict__ dout, const float *__restrict__ pk,
+    const int32_t *__restrict__ offsets, const int32_t *__restrict__ perm, const char *__restrict__ packed,
+    size_t e_stride, size_t off_w2r, size_t off_w1c, size_t off_b1, int E, int k,
+    float *__restrict__ dxrow, float *__restrict__ dpk)
+{
+    extern __shared__ __align__(16) char lds[];
+    const uint4 *w1f = (const uint4 *)lds;
+    const uint4 *w2r = (const uint4 *)(lds + off_w2r);
+    const uint4 *w1c = (const uint4 *)(lds + off_w1c);
+    const float *b1s = (const float *)(lds + off_b1);
+
+    const int tid = threadIdx.x, lane = tid & 63, j = lane & 31, g = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n_kept = offsets[E];
+    const int units_total = (n_kept + 31) / 32;
+    const int units_per_block = (units_total + (int)gridDim.x - 1) / (int)gridDim.x;
+    const long long r_begin = (long long)blockIdx.x * units_per_block * 32;
+    const int r_end = (int)min((long long)n_kept, r_begin + (long long)units_per_block * 32);
+
+    int r = (int)min(r_begin, (long long)n_kept);
+    while (r < r_end) {
+        int e = 0;
+        while (e + 1 < E && offsets[e + 1] <= r) ++e;   // uniform over the block
+        const int seg_end = min(offsets[e + 1], r_end);
+        __syncthreads();   // everyone is done with the previous expert's weights
+        stage_expert(packed + (size_t)e * e_stride, lds, e_stride, tid, kBmRowThreads);
+        __syncthreads();
+
+        const int nunits = (seg_end - r + 31) / 32;
+        for (int q = wave; q < nunits; q += kBmRowWaves) {
+            const int row = r + q * 32 + j;
+            const bool valid = row < seg_end;
+            const int a = perm[valid ? row : r];
+            const long long n = a / k;
+            const float p = valid ? pk[a] : 0.f;
+            const uint4 *xr = (const uint4 *)(x + n * kBmDS), *gr = (const uint4 *)(dout + n * kBmDS);
+            bf16x8 xb[kBmKS], gb[kBmKS];
+#pragma unroll
+            for (int ks = 0; ks < kBmKS; ++ks) {
+                xb[ks] = __builtin_bit_cast(bf16x8, xr[2 * ks + g]);
+                gb[ks] = __builtin_bit_cast(bf16x8, gr[2 * ks + g]);
+            }
+            f32x16 dx[kBmOT];
+#pragma unroll
+            for (int ot = 0; ot < kBmOT; ++ot)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) dx[ot][i] = 0.f;
+            float dp = 0.f;
+#pragma unroll 1
+            for (int ht = 0; ht < HT; ++ht) {
+                f32x16 u, da;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) u[i] = da[i] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < kBmKS; ++ks) {
+                    u = mfma_bf16(__builtin_bit_cast(bf16x8, w1f[(ht * kBmKS + ks) * 64 + lane]), xb[ks], u);
+                    da = mfma_bf16(__builtin_bit_cast(bf16x8, w2r[(ht * kBmKS + ks) * 64 + lane]), gb[ks], da);
+                }
+                uint32_t hb[8], lb[8];
+#pragma unroll
+                for (int qq = 0; qq < 4; ++qq) {
+                    const f32x4 bb = *(const f32x4 *)(b1s + ht * 32 + 8 * qq + 4 * g);
+                    float pdz[4];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const int i = 4 * qq + c;
+                        const float z = fmaf(p, u[i], bb[c]);
+                        float dens;
+                        const float cdf = normal_cdf_pdf(z, &dens);
+                        const float dz = da[i] * fmaf(z, dens, cdf);
+                        dp = fmaf(dz, u[i], dp);
+                        pdz[c] = p * dz;
+                    }
+                    split_bf16x2(pdz[0], pdz[1], hb[2 * qq], lb[2 * qq]);
+                    split_bf16x2(pdz[2], pdz[3], hb[2 * qq + 1], lb[2 * qq + 1]);
+                }
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    const bf16x8 bh = __builtin_bit_cast(bf16x8, make_uint4(hb[4 * s], hb[4 * s + 1], hb[4 * s + 2], hb[4 * s + 3]));
+                    const bf16x8 bl = __builtin_bit_cast(bf16x8, make_uint4(lb[4 * s], lb[4 * s + 1], lb[4 * s + 2], lb[4 * s + 3]));
+#pragma unroll
+                    for (int ot = 0; ot < kBmOT; ++ot) {
+                        const bf16x8 wf = __builtin_bit_cast(bf16x8, w1c[((ht * 2 + s) * kBmOT + ot) * 64 + lane]);
+                        dx[ot] = mfma_bf16(wf, bl, dx[ot]);   // small term first
+                        dx[ot] = mfma_bf16(wf, bh, dx[ot]);
+                    }
+                }
+            }
+            dp += __shfl_xor(dp, 32);
+            if (valid) {
+                if (g == 0) dpk[a] = dp;
+                float *dst = dxrow + (size_t)row * kBmDS;
+#pragma unroll
+                for (int ot = 0; ot < kBmOT; ++ot)
+#pragma unroll
+                    for (int qq = 0; qq < 4; ++qq) {
+                        const f32x4 v = {dx[ot][4 * qq], dx[ot][4 * qq + 1], dx[ot][4 * qq + 2], dx[ot][4 * qq + 3]};
+                        *(f32x4 *)(dst + ot * 32 + 8 * qq + 4 * g) = v;
+                    }
+            }
+        }
+        r = seg_end;
+    }
+}
+
+// --------------------------------------------------------------------------------------------- weights kernel
+// grid.x = chunk (as the vector-ALU expert kernel numbers them), block = HT wavefronts; part: the chunk slots.
+template <int HT>
+__global__ __launch_bounds__(HT * 64) void bwd_weights_mfma_kernel(
+    const bf16_t *__restrict__ x, const bf16_t *__restrict__ dout, const float *__restrict__ pk,
+    const int32_t *__restrict__ offsets, const int32_t *__restrict__ perm, const char *__restrict__ packed,
+    size_t e_stride, size_t off_w2r, size_t off_b1, int E, int k, int rows_per_chunk, size_t slot_floats,
+    float *__restrict__ part)
+{
+    constexpr int He = HT * 32;
+    extern __shared__ __align__(16) char lds[];
+    const uint4 *w1f = (const uint4 *)lds;
+    const uint4 *w2r = (const uint4 *)(lds + off_w2r);
+    const float *b1s = (const float *)(lds + off_b1);
+    __shared__ int blk[3];
+
+    const int tid = threadIdx.x, lane = tid & 63, jj = lane & 31, g = lane >> 5;
+    const int ht = __builtin_amdgcn_readfirstlane(tid >> 6);
+    if (tid == 0) {
+        int left = (int)blockIdx.x, e = 0, begin = 0, end = 0;
+        bool found = false;
+        for (e = 0; e < E; ++e) {
+            const int lo = offsets[e], hi = offsets[e + 1];
+            const int nch = (hi - lo + rows_per_chunk - 1) / rows_per_chunk;
+            if (left < nch) {
+                begin = lo + left * rows_per_chunk;
+                end = min(hi, begin + rows_per_chunk);
+                found = true;
+                break;
+            }
+            left -= nch;
+        }
+        blk[0] = found ? e : -1;
+        blk[1] = begin;
+        blk[2] = end;
+    }
+    __syncthreads();
+    const int e = blk[0], row_begin = blk[1], row_end = blk[2];
+    if (e < 0) return;   // uniform over the block
+    // w1f, w2r and w1c are adjacent: the first two (and the bias after w1c) are what this kernel reads
+    stage_expert(packed + (size_t)e * e_stride, lds, e_stride, tid, HT * 64);
+    __syncthreads();
+
+    // identity fragments: as B operand of K-step ks against output tile ot, slot m of lane (jj, g) is 1 where
+    // 16 ks + 8 g + m == 32 ot + jj; only the parity of ks matters
+    uint32_t ide[4] = {0, 0, 0, 0}, ido[4] = {0, 0, 0, 0};
+    {
+        const int me = jj - 8 * g, mo = jj - 16 - 8 * g;
+        if (me >= 0 && me < 8) ide[me >> 1] = (me & 1) ? 0x3f800000u : 0x00003f80u;
+        if (mo >= 0 && mo < 8) ido[mo >> 1] = (mo & 1) ? 0x3f800000u : 0x00003f80u;
+    }
+    const bf16x8 id_even = __builtin_bit_cast(bf16x8, make_uint4(ide[0], ide[1], ide[2], ide[3]));
+    const bf16x8 id_odd = __builtin_bit_cast(bf16x8, make_uint4(ido[0], ido[1], ido[2], ido[3]));
+    const float bias = b1s[ht * 32 + jj];
+
+    f32x16 aW1[kBmOT], aW2[kBmOT];
+#pragma unroll
+    for (int ot = 0; ot < kBmOT; ++ot)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) aW1[ot][i] = aW2[ot][i] = 0.f;
+    float ab1 = 0.f, ab2[kBmOT] = {0.f, 0.f};
+
+    for (int r0 = row_begin; r0 < row_end; r0 += 32) {
+        const int row = r0 + jj;   // as A operand a lane holds row jj of the unit, contraction slots 8g..8g+7
+        const bool valid = row < row_end;
+        const int a = perm[valid ? row : row_begin];
+        const long long n = a / k;
+        const float p_lane = valid ? pk[a] : 0.f;
+        const uint4 *xr = (const uint4 *)(x + n * kBmDS), *gr = (const uint4 *)(dout + n * kBmDS);
+        bf16x8 xa[kBmKS], ga[kBmKS];
+#pragma unroll
+        for (int ks = 0; ks < kBmKS; ++ks) {
+            xa[ks] = __builtin_bit_cast(bf16x8, xr[2 * ks + g]);
+            const uint4 gv = valid ? gr[2 * ks + g] : make_uint4(0, 0, 0, 0);   // rows past the end add nothing
+            ga[ks] = __builtin_bit_cast(bf16x8, gv);
+        }
+        // transposed results: lane = hidden unit jj of this tile, register i = row acc_feature(i, g) of the unit
+        f32x16 u, da;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) u[i] = da[i] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < kBmKS; ++ks) {
+            u = mfma_bf16(xa[ks], __builtin_bit_cast(bf16x8, w1f[(ht * kBmKS + ks) * 64 + lane]), u);
+            da = mfma_bf16(ga[ks], __builtin_bit_cast(bf16x8, w2r[(ht * kBmKS + ks) * 64 + lane]), da);
+        }
+        uint32_t a1p[8], a1l[8], pdzp[8], pdzl[8];
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) {
+            float act[2], pdz[2];
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const float p = __shfl(p_lane, acc_feature(i + c, g));   // probability of the register's row
+                const float z = fmaf(p, u[i + c], bias);
+                float dens;
+                const float cdf = normal_cdf_pdf(z, &dens);
+                const float dz = da[i + c] * fmaf(z, dens, cdf);
+                act[c] = z * cdf;
+                pdz[c] = p * dz;
+                ab1 += dz;
+            }
+            split_bf16x2(act[0], act[1], a1p[i / 2], a1l[i / 2]);
+            split_bf16x2(pdz[0], pdz[1], pdzp[i / 2], pdzl[i / 2]);
+        }
+#pragma unroll
+        for (int ot = 0; ot < kBmOT; ++ot) {
+            // x and dy of the unit with lane = slice feature 32 ot + jj, registers = rows
+            f32x16 xt, gt;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) xt[i] = gt[i] = 0.f;
+            xt = mfma_bf16(xa[2 * ot], id_even, xt);
+            xt = mfma_bf16(xa[2 * ot + 1], id_odd, xt);
+            gt = mfma_bf16(ga[2 * ot], id_even, gt);
+            gt = mfma_bf16(ga[2 * ot + 1], id_odd, gt);
+            if (ht == 0) {
+                float sum = 0.f;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sum += gt[i];
+                ab2[ot] += sum;
+            }
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const bf16x8 xs = __builtin_bit_cast(bf16x8, make_uint4(pack_exact_bf16x2(xt[8 * s], xt[8 * s + 1]), pack_exact_bf16x2(xt[8 * s + 2], xt[8 * s + 3]),
+                                                                         pack_exact_bf16x2(xt[8 * s + 4], xt[8 * s + 5]), pack_exact_bf16x2(xt[8 * s + 6], xt[8 * s + 7])));
+                const bf16x8 gs = __builtin_bit_cast(bf16x8, make_uint4(pack_exact_bf16x2(gt[8 * s], gt[8 * s + 1]), pack_exact_bf16x2(gt[8 * s + 2], gt[8 * s + 3]),
+                                                                         pack_exact_bf16x2(gt[8 * s + 4], gt[8 * s + 5]), pack_exact_bf16x2(gt[8 * s + 6], gt[8 * s + 7])));
+                const bf16x8 ah = __builtin_bit_cast(bf16x8, make_uint4(a1p[4 * s], a1p[4 * s + 1], a1p[4 * s + 2], a1p[4 * s + 3]));
+                const bf16x8 al = __builtin_bit_cast(bf16x8, make_uint4(a1l[4 * s], a1l[4 * s + 1], a1l[4 * s + 2], a1l[4 * s + 3]));
+                const bf16x8 dh = __builtin_bit_cast(bf16x8, make_uint4(pdzp[4 * s], pdzp[4 * s + 1], pdzp[4 * s + 2], pdzp[4 * s + 3]));
+                const bf16x8 dl = __builtin_bit_cast(bf16x8, make_uint4(pdzl[4 * s], pdzl[4 * s + 1], pdzl[4 * s + 2], pdzl[4 * s + 3]));
+                // [hidden unit][slice feature]: lane = feature, registers = hidden units; small term first
+                aW2[ot] = mfma_bf16(al, gs, aW2[ot]);
+                aW2[ot] = mfma_bf16(ah, gs, aW2[ot]);
+                // [slice feature][hidden unit]: lane = hidden unit, registers = features
+                aW1[ot] = mfma_bf16(xs, dl, aW1[ot]);
+                aW1[ot] = mfma_bf16(xs, dh, aW1[ot]);
+            }
+        }
+    }
+
+    // this chunk's slot: dW1 [ds][He] | dW2 [He][ds] | db1 [He] | db2 [ds]
+    float *slot = part + (size_t)blockIdx.x * slot_floats;
+    float *pW1 = slot, *pW2 = pW1 + (size_t)kBmDS * He, *pb1 = pW2 + (size_t)He * kBmDS, *pb2 = pb1 + He;
+#pragma unroll
+    for (int ot = 0; ot < kBmOT; ++ot)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            pW1[(size_t)(32 * ot + acc_feature(i, g)) * He + 32 * ht + jj] = aW1[ot][i];
+            pW2[(size_t)(32 * ht + acc_feature(i, g)) * kBmDS + 32 * ot + jj] = aW2[ot][i];
+        }
+    ab1 += __shfl_xor(ab1, 32);   // the two lane groups hold different rows of the same hidden unit
+    if (g == 0) pb1[32 * ht + jj] = ab1;
+    if (ht == 0) {
+#pragma unroll
+        for (int ot = 0; ot < kBmOT; ++ot) {
+            const float t = ab2[ot] + __shfl_xor(ab2[ot], 32);
+            if (g == 0) pb2[32 * ot + jj] = t;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------------ host
+bool backward_mfma_shape(const slicemoe_config &c)
+{
+    const int ds = c.d / c.S;
+    return c.dtype == SLICEMOE_BF16 && ds == kBmDS && (c.He == 64 || c.He == 128 || c.He == 256) &&
+           !(c.flags & SLICEMOE_FLAG_FORCE_GENERIC) && bwd_packed_layout(c.He).stride <= (size_t)max_lds_per_block();
+}
+
+size_t backward_mfma_packed_bytes(const slicemoe_config &c)
+{
+    return backward_mfma_shape(c) ? bwd_packed_layout(c.He).stride * (size_t)c.E : 0;
+}
+
+template <int HT>
+static hipError_t run_expert_mfma(const slicemoe_config &c, const BwdPacked &L, const void *h, const void *d_out,
+                                  const float *pk, const int32_t *offsets, const int32_t *perm, const char *packed,
+                                  int rows_per_chunk, long long chunks, size_t slot_floats, float *dxrow, float *dpk,
+                                  float *part, hipStream_t s)
+{
+    const long long Na = (long long)c.T * c.S * c.k;
+    long long blocks = (Na + 31) / 32;
+    if (blocks > num_compute_units()) blocks = num_compute_units();
+    auto rows = bwd_rows_mfma_kernel<HT>;
+    hipError_t e = hipFuncSetAttribute((const void *)rows, hipFuncAttributeMaxDynamicSharedMemorySize, (int)L.stride);
+    if (e != hipSuccess) return e;
+    rows<<<(int)blocks, kBmRowThreads, L.stride, s>>>((const bf16_t *)h, (const bf16_t *)d_out, pk, offsets, perm, packed,
+                                                      L.stride, L.w2r, L.w1c, L.b1, c.E, c.k, dxrow, dpk);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    auto wk = bwd_weights_mfma_kernel<HT>;
+    e = hipFuncSetAttribute((const void *)wk, hipFuncAttributeMaxDynamicSharedMemorySize, (int)L.stride);
+    if (e != hipSuccess) return e;
+    wk<<<(unsigned)chunks, HT * 64, L.stride, s>>>((const bf16_t *)h, (const bf16_t *)d_out, pk, offsets, perm, packed, L.stride,
+                                                   L.w2r, L.b1, c.E, c.k, rows_per_chunk, slot_floats, part);
+    return hipGetLastError();
+}
+
+// Packs the backward copies of the expert weights into `packed` (backward_mfma_packed_bytes), then runs the two kernels.
+// rows_per_chunk must be a multiple of 32; part holds `chunks` slots of slot_floats floats.
+hipError_t launch_backward_expert_mfma(const slicemoe_config &c, const void *h, const slicemoe_weights &w, const void *d_out,
+                                       const float *pk, const int32_t *offsets, const int32_t *perm, void *packed,
+                                       int rows_per_chunk, long long chunks, size_t slot_floats, float *dxrow, float *dpk,
+                                       float *part, hipStream_t s)
+{
+    if (!backward_mfma_shape(c) || rows_per_chunk % 32 != 0) return hipErrorInvalidValue;
+    const BwdPacked L = bwd_packed_layout(c.He);
+    const int He = c.He, E = c.E, ds = kBmDS;
+    char *pb = (char *)packed;
+    const long long nfrag = (long long)E * (He / 32) * kBmKS * 64;
+    const int fb = (int)((nfrag + 255) / 256);
+    const size_t wstride = (size_t)ds * He;
+    // w1f: the [ds, He] matrix W1 itself; w2r: the [ds, He] matrix M[c][hidden] = W2[hidden][c]
+    bwd_pack_layer1_kernel<<<fb, 256, 0, s>>>((const bf16_t *)w.W1, ds, He, (size_t)He, 1, wstride, pb + L.w1f, L.stride, E);
+    bwd_pack_layer1_kernel<<<fb, 256, 0, s>>>((const bf16_t *)w.W2, ds, He, 1, (size_t)ds, wstride, pb + L.w2r, L.stride, E);
+    // w1c: the [He, ds] matrix M[hidden][c] = W1[c][hidden], contraction over the hidden units in accumulator order
+    bwd_pack_chain_kernel<<<fb, 256, 0, s>>>((const bf16_t *)w.W1, He, ds, 1, (size_t)He, wstride, pb + L.w1c, L.stride, E);
+    bwd_pack_bias_kernel<<<(int)(((long long)E * He + 255) / 256), 256, 0, s>>>((const bf16_t *)w.b1, He, (size_t)He, pb + L.b1,
+                                                                               L.stride, E);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (He == 256) return run_expert_mfma<8>(c, L, h, d_out, pk, offsets, perm, pb, rows_per_chunk, chunks, slot_floats, dxrow, dpk, part, s);
+    if (He == 128) return run_expert_mfma<4>(c, L, h, d_out, pk, offsets, perm, pb, rows_per_chunk, chunks, slot_floats, dxrow, dpk, part, s);
+    return run_expert_mfma<2>(c, L, h, d_out, pk, offsets, perm, pb, rows_per_chunk, chunks, slot_floats, dxrow, dpk, part, s);
+}
+
+}  // namespace slicemoe

@@ -3,7 +3,10 @@
 Each case runs the forward on the GPU (inference or training-time router), then the backward with a seeded upstream
 gradient.  The oracle runs its own forward and backward from the same inputs; the routing must agree exactly on these
 cases (no near-tie among them), because a weight gradient sums over every slice.
-Bars, derived from the arithmetic (fp32 throughout, exact GELU; the forward's tolerance is stated for h' only):
+Bars, derived from the arithmetic (the forward's tolerance is stated for h' only).  Two kinds of kernels: vector-ALU
+(fp32 throughout, exact GELU) and, for the expert part of the benchmark shapes, matrix-core (fp32 pre-activations and
+derivative, erf to 1.5e-7; p dL/dz and the activation enter the second matrix instructions as two-term bf16 splits
+with 16 significant bits against exact bf16 data).  Both are of fp32 grade and share the bars:
 dL/dh is computed in fp32 and rounded once to the storage type, so per element |err| <= 2^-8 |ref| + 2e-4 RMS for
 bf16 storage (half a unit in the last place of 8 significant bits is at most 2^-8 relative; the RMS term covers the
 fp32 error, measured 3e-6 RMS, also where it moves a value across a rounding boundary) and <= 1e-4 RMS for fp32 storage; a max-over-RMS bar does not fit here, because with the
@@ -48,6 +51,9 @@ CASES = {
     "paper": (wl.CONFIGS["paper"], 100, dict(tau=1.0, sigma=0.0, rate=0.2)),       # slice width 96: two feature chunks
     "paper_S2": (wl.CONFIGS["paper_S2_k2"], 40, None),                             # He = 1536: six hidden groups (atomic rows)
     "headline_4k": (wl.CONFIGS["headline"], 4096, None),                           # 131 072 rows: many blocks per expert
+    "headline_generic": (wl.CONFIGS["headline"], 130, None, "generic"),             # vector-ALU kernels on a matrix-core shape
+    "He128": (wl.SliceMoEShape("He128", T=300, d=256, S=4, E=8, k=2, He=128), None, dict(tau=1.0, sigma=0.0, rate=0.2)),
+    "He64": (wl.SliceMoEShape("He64", T=97, d=128, S=2, E=4, k=1, He=64), None, None),
     "k3": (wl.SliceMoEShape("k3", T=150, d=256, S=4, E=8, k=3, He=96), None, dict(tau=0.7, sigma=0.0, rate=0.3)),
 }
 
@@ -55,9 +61,11 @@ CASES = {
 @pytest.mark.parametrize("name", list(CASES))
 def test_backward_matches_oracle(B, name):
     import torch
-    base, T, train = CASES[name]
+    base, T, train = CASES[name][:3]
     shape, h, w = make_inputs(base, T)
-    cfg = B.config_of(shape)
+    cfg = B.config_of(shape, flags=B.SLICEMOE_FLAG_FORCE_GENERIC if len(CASES[name]) > 3 else 0)
+    mfma = B.slicemoe_backward_uses_mfma(cfg) == 1
+    assert mfma == (shape.dtype == "bf16" and shape.ds == 64 and shape.He in (64, 128, 256) and len(CASES[name]) == 3)
     dout = wl.make_dout(shape)
     noise, drop_u = wl.make_router_draws(shape)
     okw = dict(tau=1.0, sigma=0.0, rate=0.0)
@@ -100,14 +108,17 @@ def test_backward_matches_oracle(B, name):
     excess = np.abs(got_dh - ref["d_h"]) / bound
     err_dh = np.abs(got_dh - ref["d_h"]).max() / scale_dh
     report = [f"d_h {err_dh:.2e} (worst element at {excess.max():.2f} of its bound)"]
+    failed = []
     for n in NAMES:
         got = grads[n].cpu().numpy().astype(np.float64)
         assert got.shape == ref[n].shape
         scale = rms(ref[n])
         err = np.abs(got - ref[n]).max() / scale if scale > 0 else np.abs(got).max()
-        report.append(f"{n} {err:.1e}")
-        assert err <= TOL_WGRAD, (n, err)
+        report.append(f"{n} {err:.1e}" + (f" (rms {rms(got - ref[n]) / scale:.1e})" if mfma and n in ("W1", "W2") else ""))
+        if err > TOL_WGRAD:
+            failed.append((n, err))
     print(f"\n[backward {name}] rows={int(ref_f['offsets'][-1])} max|err|/rms: " + " ".join(report))
+    assert not failed, failed
     assert excess.max() <= 1.0, excess.max()
 
 
