@@ -532,6 +532,7 @@ BackwardPlan backward_plan(const slicemoe_config &c)
     p.expert_part = at;  at = align_up(at + (size_t)p.chunks * expert_slot_floats((int)ds, c.He) * sizeof(float), 256);
     p.router_part = at;  at = align_up(at + (size_t)p.slice_blocks * router_slot_floats((int)ds, c.Hr, c.E) * sizeof(float), 256);
     p.packed = at;  at = align_up(at + backward_mfma_packed_bytes(c), 256);
+    p.router_scratch = at;  at = align_up(at + backward_router_mfma_scratch_bytes(c), 256);
     p.total = at + 256;
     return p;
 }
@@ -595,6 +596,12 @@ static hipError_t run_backward(const slicemoe_config &c, const void *h, const sl
         epart, offsets, ds, c.He, c.E, P.rows_per_chunk, g.W1, g.b1, g.W2, g.b2);
     if ((e = hipGetLastError()) != hipSuccess) return e;
 
+    const size_t rslot = router_slot_floats(ds, c.Hr, c.E);
+    if (backward_router_mfma_shape(c)) {
+        e = launch_backward_router_mfma(c, h, w, v, drop_u, rate, idx, inv, dpk, dxrow, d_h, ws + P.router_scratch,
+                                        P.slice_blocks, rslot, rpart, s);
+        if (e != hipSuccess) return e;
+    } else {
     const size_t lds_r = sizeof(float) * kBwdRB * ((size_t)ds + 2 * (size_t)c.Hr + 2 * (size_t)c.E);
     const size_t lds_rw = lds_r + sizeof(T) * ((size_t)ds * (c.Hr + kWPad<T>) + (size_t)c.Hr * (c.E + kWPad<T>));
     const dim3 rgrid((unsigned)P.slice_blocks, col_chunks);
@@ -612,7 +619,7 @@ static hipError_t run_backward(const slicemoe_config &c, const void *h, const sl
             nz, v.sigma, v.inv_tau, du, rate, idx, inv, dpk, dxrow, (T *)d_h, rpart);
     }
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    const size_t rslot = router_slot_floats(ds, c.Hr, c.E);
+    }
     bwd_reduce_router_kernel<<<(unsigned)((rslot + 255) / 256), 256, 0, s>>>(rpart, (int)P.slice_blocks, ds, c.Hr, c.E, g.Wr1,
                                                                            g.br1, g.Wr2, g.br2);
     return hipGetLastError();

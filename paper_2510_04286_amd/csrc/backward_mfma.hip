@@ -26,7 +26,7 @@
 // second-stage matrix instructions (p dz, a1) enter as two-term bf16 splits (hi + lo, 16 significant bits, one
 // matrix instruction per term against exact bf16 data), so the results are of fp32 grade.  The kernels are bound by
 // vector instructions, not by the matrix pipe, so the second term costs little.
-#include "mfma.h"
+#include "bwd_mfma.h"
 
 namespace slicemoe {
 
@@ -57,10 +57,8 @@ static BwdPacked bwd_packed_layout(int He)
     return L;
 }
 
-// One thread per fragment.  Generic strided source so that the same kernel packs a matrix or its transpose:
-// element (kk, col) of the [K, N] matrix being packed is src[kk * rs + col * cs].
-__global__ void bwd_pack_layer1_kernel(const bf16_t *__restrict__ W, int K, int N, size_t rs, size_t cs, size_t src_stride,
-                                       char *__restrict__ dst, size_t dst_stride, int nmat)
+__global__ void bwd_pack_layer1_kernel(const bf16_t *__restrict__ W, int K, int Kv, int N, int Nv, size_t rs, size_t cs,
+                                       size_t src_stride, char *__restrict__ dst, size_t dst_stride, int nmat)
 {
     const int KS = K / 16;
     const long long per = (long long)(N / 32) * KS * 64;
@@ -73,18 +71,19 @@ __global__ void bwd_pack_layer1_kernel(const bf16_t *__restrict__ W, int K, int 
     const int ks = (int)(r % KS), nt = (int)(r / KS);
     const int i = lane & 31, g = lane >> 5;
     const bf16_t *src = W + (size_t)mat * src_stride;
+    const int col = 32 * nt + i;
     uint32_t v[4];
     for (int m = 0; m < 8; m += 2) {
-        const uint32_t lo = src[(size_t)(16 * ks + 8 * g + m) * rs + (size_t)(32 * nt + i) * cs];
-        const uint32_t hi = src[(size_t)(16 * ks + 8 * g + m + 1) * rs + (size_t)(32 * nt + i) * cs];
+        const int k0 = 16 * ks + 8 * g + m;
+        const uint32_t lo = (k0 < Kv && col < Nv) ? src[(size_t)k0 * rs + (size_t)col * cs] : 0;
+        const uint32_t hi = (k0 + 1 < Kv && col < Nv) ? src[(size_t)(k0 + 1) * rs + (size_t)col * cs] : 0;
         v[m / 2] = lo | (hi << 16);
     }
     *(uint4 *)(dst + (size_t)mat * dst_stride + (size_t)(f - (long long)mat * per) * 16) = make_uint4(v[0], v[1], v[2], v[3]);
 }
 
-// Fragments [K/32][2][N/32][64] of a [K, N] matrix whose contraction slots follow the accumulator order.
-__global__ void bwd_pack_chain_kernel(const bf16_t *__restrict__ W, int K, int N, size_t rs, size_t cs, size_t src_stride,
-                                      char *__restrict__ dst, size_t dst_stride, int nmat)
+__global__ void bwd_pack_chain_kernel(const bf16_t *__restrict__ W, int K, int Kv, int N, int Nv, size_t rs, size_t cs,
+                                      size_t src_stride, char *__restrict__ dst, size_t dst_stride, int nmat, bool to_f16)
 {
     const int HT = K / 32, NT = N / 32;
     const long long per = (long long)HT * 2 * NT * 64;
@@ -99,68 +98,31 @@ __global__ void bwd_pack_chain_kernel(const bf16_t *__restrict__ W, int K, int N
     const int s = (int)(r % 2), ht = (int)(r / 2);
     const int i = lane & 31, g = lane >> 5;
     const bf16_t *src = W + (size_t)mat * src_stride;
+    const int col = 32 * nt + i;
     uint32_t v[4];
     for (int m = 0; m < 8; m += 2) {
-        const uint32_t lo = src[(size_t)(32 * ht + chain_feature(s, g, m)) * rs + (size_t)(32 * nt + i) * cs];
-        const uint32_t hi = src[(size_t)(32 * ht + chain_feature(s, g, m + 1)) * rs + (size_t)(32 * nt + i) * cs];
-        v[m / 2] = lo | (hi << 16);
+        uint32_t pr[2];
+        for (int c = 0; c < 2; ++c) {
+            const int kk = 32 * ht + chain_feature(s, g, m + c);
+            bf16_t w = (kk < Kv && col < Nv) ? src[(size_t)kk * rs + (size_t)col * cs] : (bf16_t)0;
+            if (to_f16) {   // bf16 values convert exactly unless tiny (rounded) or beyond the fp16 range (clamped)
+                const _Float16 hv = (_Float16)fminf(fmaxf(bf16_to_f32(w), -65504.f), 65504.f);
+                w = __builtin_bit_cast(bf16_t, hv);
+            }
+            pr[c] = w;
+        }
+        v[m / 2] = pr[0] | (pr[1] << 16);
     }
     *(uint4 *)(dst + (size_t)mat * dst_stride + (size_t)(f - (long long)mat * per) * 16) = make_uint4(v[0], v[1], v[2], v[3]);
 }
 
-__global__ void bwd_pack_bias_kernel(const bf16_t *__restrict__ b, int n, size_t src_stride, char *__restrict__ dst,
-                                     size_t dst_stride, int nmat)
+__global__ void bwd_pack_bias_kernel(const bf16_t *__restrict__ b, int n, int npad, size_t src_stride,
+                                     char *__restrict__ dst, size_t dst_stride, int nmat)
 {
     const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= (long long)n * nmat) return;
-    const int mat = (int)(t / n), i = (int)(t - (long long)mat * n);
-    ((float *)(dst + (size_t)mat * dst_stride))[i] = bf16_to_f32(b[(size_t)mat * src_stride + i]);
-}
-
-// Phi(z), and phi(z) through *density: the normal CDF by Abramowitz & Stegun 7.1.26 on |z| / sqrt 2 (|error| < 1.5e-7),
-// whose exponential exp(-z^2 / 2) is the density's.
-__device__ __forceinline__ float normal_cdf_pdf(float z, float *density)
-{
-    const float ax = fabsf(z) * 0.70710678118654752f;
-    const float ex = __builtin_amdgcn_exp2f(-0.72134752044448170f * z * z);   // exp(-z^2 / 2)
-    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.f));
-    float q = fmaf(1.061405429f, t, -1.453152027f);
-    q = fmaf(q, t, 1.421413741f);
-    q = fmaf(q, t, -0.284496736f);
-    q = fmaf(q, t, 0.254829592f);
-    const float tail = 0.5f * q * t * ex;   // 1 - Phi(|z|)
-    *density = 0.39894228040143267794f * ex;
-    return z > 0.f ? 1.f - tail : tail;
-}
-
-__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)   // round to nearest even
-{
-    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-    typedef float f32x2_t __attribute__((ext_vector_type(2)));
-    const f32x2_t v = {a, b};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
-}
-
-// Two-term bf16 split of a pair: hi = bf16(v), lo = bf16(v - hi); hi + lo carries 16 significant bits, so a matrix
-// instruction run once per term is as good as an fp32 operand (the other operand being exact bf16 data).
-__device__ __forceinline__ void split_bf16x2(float a, float b, uint32_t &hi, uint32_t &lo)
-{
-    hi = pack_bf16x2(a, b);
-    lo = pack_bf16x2(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xffff0000u));
-}
-
-// Two fp32 values that are exactly bf16 values (results of an MFMA against an identity): their high halves.
-__device__ __forceinline__ uint32_t pack_exact_bf16x2(float a, float b)
-{
-    return (__float_as_uint(a) >> 16) | (__float_as_uint(b) & 0xffff0000u);
-}
-
-__device__ __forceinline__ void stage_expert(const char *__restrict__ src, char *lds, size_t bytes, int tid, int nthreads)
-{
-    const uint4 *g = (const uint4 *)src;
-    uint4 *l = (uint4 *)lds;
-    const int n = (int)(bytes / 16);
-    for (int i = tid; i < n; i += nthreads) l[i] = g[i];
+    if (t >= (long long)npad * nmat) return;
+    const int mat = (int)(t / npad), i = (int)(t - (long long)mat * npad);
+    ((float *)(dst + (size_t)mat * dst_stride))[i] = i < n ? bf16_to_f32(b[(size_t)mat * src_stride + i]) : 0.f;
 }
 
 // ------------------------------------------------------------------------------------------------ rows kernel
@@ -191,7 +153,7 @@ __global__ __launch_bounds__(kBmRowThreads) void bwd_rows_mfma_kernel(
         while (e + 1 < E && offsets[e + 1] <= r) ++e;   // uniform over the block
         const int seg_end = min(offsets[e + 1], r_end);
         __syncthreads();   // everyone is done with the previous expert's weights
-        stage_expert(packed + (size_t)e * e_stride, lds, e_stride, tid, kBmRowThreads);
+        stage_bytes(packed + (size_t)e * e_stride, lds, e_stride, tid, kBmRowThreads);
         __syncthreads();
 
         const int nunits = (seg_end - r + 31) / 32;
@@ -311,19 +273,11 @@ __global__ __launch_bounds__(HT * 64) void bwd_weights_mfma_kernel(
     const int e = blk[0], row_begin = blk[1], row_end = blk[2];
     if (e < 0) return;   // uniform over the block
     // w1f, w2r and w1c are adjacent: the first two (and the bias after w1c) are what this kernel reads
-    stage_expert(packed + (size_t)e * e_stride, lds, e_stride, tid, HT * 64);
+    stage_bytes(packed + (size_t)e * e_stride, lds, e_stride, tid, HT * 64);
     __syncthreads();
 
-    // identity fragments: as B operand of K-step ks against output tile ot, slot m of lane (jj, g) is 1 where
-    // 16 ks + 8 g + m == 32 ot + jj; only the parity of ks matters
-    uint32_t ide[4] = {0, 0, 0, 0}, ido[4] = {0, 0, 0, 0};
-    {
-        const int me = jj - 8 * g, mo = jj - 16 - 8 * g;
-        if (me >= 0 && me < 8) ide[me >> 1] = (me & 1) ? 0x3f800000u : 0x00003f80u;
-        if (mo >= 0 && mo < 8) ido[mo >> 1] = (mo & 1) ? 0x3f800000u : 0x00003f80u;
-    }
-    const bf16x8 id_even = __builtin_bit_cast(bf16x8, make_uint4(ide[0], ide[1], ide[2], ide[3]));
-    const bf16x8 id_odd = __builtin_bit_cast(bf16x8, make_uint4(ido[0], ido[1], ido[2], ido[3]));
+    bf16x8 id_even, id_odd;
+    identity_fragments(jj, g, id_even, id_odd);
     const float bias = b1s[ht * 32 + jj];
 
     f32x16 aW1[kBmOT], aW2[kBmOT];
@@ -482,11 +436,11 @@ hipError_t launch_backward_expert_mfma(const slicemoe_config &c, const void *h, 
     const int fb = (int)((nfrag + 255) / 256);
     const size_t wstride = (size_t)ds * He;
     // w1f: the [ds, He] matrix W1 itself; w2r: the [ds, He] matrix M[c][hidden] = W2[hidden][c]
-    bwd_pack_layer1_kernel<<<fb, 256, 0, s>>>((const bf16_t *)w.W1, ds, He, (size_t)He, 1, wstride, pb + L.w1f, L.stride, E);
-    bwd_pack_layer1_kernel<<<fb, 256, 0, s>>>((const bf16_t *)w.W2, ds, He, 1, (size_t)ds, wstride, pb + L.w2r, L.stride, E);
+    bwd_pack_layer1_kernel<<<fb, 256, 0, s>>>((const bf16_t *)w.W1, ds, ds, He, He, (size_t)He, 1, wstride, pb + L.w1f, L.stride, E);
+    bwd_pack_layer1_kernel<<<fb, 256, 0, s>>>((const bf16_t *)w.W2, ds, ds, He, He, 1, (size_t)ds, wstride, pb + L.w2r, L.stride, E);
     // w1c: the [He, ds] matrix M[hidden][c] = W1[c][hidden], contraction over the hidden units in accumulator order
-    bwd_pack_chain_kernel<<<fb, 256, 0, s>>>((const bf16_t *)w.W1, He, ds, 1, (size_t)He, wstride, pb + L.w1c, L.stride, E);
-    bwd_pack_bias_kernel<<<(int)(((long long)E * He + 255) / 256), 256, 0, s>>>((const bf16_t *)w.b1, He, (size_t)He, pb + L.b1,
+    bwd_pack_chain_kernel<<<fb, 256, 0, s>>>((const bf16_t *)w.W1, He, He, ds, ds, 1, (size_t)He, wstride, pb + L.w1c, L.stride, E, false);
+    bwd_pack_bias_kernel<<<(int)(((long long)E * He + 255) / 256), 256, 0, s>>>((const bf16_t *)w.b1, He, He, (size_t)He, pb + L.b1,
                                                                                L.stride, E);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
