@@ -258,20 +258,33 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_expert_kernel(
     if (blockIdx.y == 0 && tid < ncols) pb2[c0 + tid] = ab2;
 }
 
-// Sum of the chunk slots of each expert, in chunk order: grid (E, pieces of the slot), one thread per slot element.
-__global__ __launch_bounds__(256) void bwd_reduce_expert_kernel(
+// Sum of the chunk slots of each expert in a fixed order: grid (E, pieces of 64 slot elements); a block is 64 elements
+// x 4 interleaved sequences of chunks, whose four partial sums are added in order at the end.
+constexpr int kRedElems = 64, kRedSeqs = 4;
+__global__ __launch_bounds__(kRedElems * kRedSeqs) void bwd_reduce_expert_kernel(
     const float *__restrict__ part, const int32_t *__restrict__ offsets, int ds, int He, int E, int rows_per_chunk,
     float *__restrict__ dW1, float *__restrict__ db1, float *__restrict__ dW2, float *__restrict__ db2)
 {
+    __shared__ float red[kRedSeqs][kRedElems];
     const int e = blockIdx.x;
+    const int ex = threadIdx.x % kRedElems, sq = threadIdx.x / kRedElems;
     const size_t slot = expert_slot_floats(ds, He);
-    const size_t t = (size_t)blockIdx.y * blockDim.x + threadIdx.x;
-    if (t >= slot) return;
-    int first = 0;   // chunks are numbered expert by expert, as the expert kernel finds them
-    for (int q = 0; q < e; ++q) first += (offsets[q + 1] - offsets[q] + rows_per_chunk - 1) / rows_per_chunk;
-    const int nch = (offsets[e + 1] - offsets[e] + rows_per_chunk - 1) / rows_per_chunk;
+    const size_t t = (size_t)blockIdx.y * kRedElems + ex;
+    // chunks are numbered expert by expert, as the expert kernels find them (E <= 64: one thread per expert)
+    __shared__ int nchs[64];
+    if (threadIdx.x < 64)
+        nchs[threadIdx.x] = (int)threadIdx.x < E ? (offsets[threadIdx.x + 1] - offsets[threadIdx.x] + rows_per_chunk - 1) / rows_per_chunk : 0;
+    __syncthreads();
+    int first = 0;
+    for (int q = 0; q < e; ++q) first += nchs[q];
+    const int nch = nchs[e];
     float acc = 0.f;
-    for (int c = 0; c < nch; ++c) acc += part[(size_t)(first + c) * slot + t];
+    if (t < slot)
+        for (int c = sq; c < nch; c += kRedSeqs) acc += part[(size_t)(first + c) * slot + t];
+    red[sq][ex] = acc;
+    __syncthreads();
+    if (sq != 0 || t >= slot) return;
+    acc = ((red[0][ex] + red[1][ex]) + red[2][ex]) + red[3][ex];
     const size_t nW = (size_t)ds * He;
     if (t < nW) dW1[(size_t)e * nW + t] = acc;
     else if (t < 2 * nW) dW2[(size_t)e * nW + (t - nW)] = acc;
@@ -488,16 +501,22 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_router_kernel(
     if (first_chunk && tid < E) pbr2[tid] = abr2;
 }
 
-// Sum of the router slots of all blocks, in block order: one thread per slot element.
-__global__ __launch_bounds__(256) void bwd_reduce_router_kernel(
+// Sum of the router slots of all blocks in a fixed order; same scheme as bwd_reduce_expert_kernel.
+__global__ __launch_bounds__(kRedElems * kRedSeqs) void bwd_reduce_router_kernel(
     const float *__restrict__ part, int nslots, int ds, int Hr, int E,
     float *__restrict__ dWr1, float *__restrict__ dbr1, float *__restrict__ dWr2, float *__restrict__ dbr2)
 {
+    __shared__ float red[kRedSeqs][kRedElems];
+    const int ex = threadIdx.x % kRedElems, sq = threadIdx.x / kRedElems;
     const size_t slot = router_slot_floats(ds, Hr, E);
-    const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= slot) return;
+    const size_t t = (size_t)blockIdx.x * kRedElems + ex;
     float acc = 0.f;
-    for (int b = 0; b < nslots; ++b) acc += part[(size_t)b * slot + t];
+    if (t < slot)
+        for (int b = sq; b < nslots; b += kRedSeqs) acc += part[(size_t)b * slot + t];
+    red[sq][ex] = acc;
+    __syncthreads();
+    if (sq != 0 || t >= slot) return;
+    acc = ((red[0][ex] + red[1][ex]) + red[2][ex]) + red[3][ex];
     const size_t n1 = (size_t)ds * Hr, n2 = (size_t)Hr * E;
     if (t < n1) dWr1[t] = acc;
     else if (t < n1 + n2) dWr2[t - n1] = acc;
@@ -519,9 +538,9 @@ BackwardPlan backward_plan(const slicemoe_config &c)
     BackwardPlan p;
     const size_t Ns = (size_t)c.T * c.S, Na = Ns * c.k;
     const size_t ds = (size_t)(c.d / c.S);
-    // about a thousand chunks of stacked rows however large the batch (each has a slot of partial weight gradients),
+    // about five hundred chunks of stacked rows however large the batch (each has a slot of partial weight gradients),
     // at least 512 rows each, whole batches of rows
-    size_t rows = (Na + 1023) / 1024;
+    size_t rows = (Na + 511) / 512;
     rows = (rows + 31) / 32 * 32;   // whole 32-row units of the matrix-core kernels (and whole batches of kBwdRB)
     p.rows_per_chunk = (int)(rows < 512 ? 512 : rows);
     p.chunks = (long long)((Na + p.rows_per_chunk - 1) / p.rows_per_chunk) + c.E;   // worst case: every expert ends on a partial chunk
@@ -592,7 +611,7 @@ static hipError_t run_backward(const slicemoe_config &c, const void *h, const sl
     }
     if ((e = hipGetLastError()) != hipSuccess) return e;
     }
-    bwd_reduce_expert_kernel<<<dim3((unsigned)c.E, (unsigned)((eslot + 255) / 256)), 256, 0, s>>>(
+    bwd_reduce_expert_kernel<<<dim3((unsigned)c.E, (unsigned)((eslot + kRedElems - 1) / kRedElems)), kRedElems * kRedSeqs, 0, s>>>(
         epart, offsets, ds, c.He, c.E, P.rows_per_chunk, g.W1, g.b1, g.W2, g.b2);
     if ((e = hipGetLastError()) != hipSuccess) return e;
 
@@ -620,7 +639,7 @@ static hipError_t run_backward(const slicemoe_config &c, const void *h, const sl
     }
     if ((e = hipGetLastError()) != hipSuccess) return e;
     }
-    bwd_reduce_router_kernel<<<(unsigned)((rslot + 255) / 256), 256, 0, s>>>(rpart, (int)P.slice_blocks, ds, c.Hr, c.E, g.Wr1,
+    bwd_reduce_router_kernel<<<(unsigned)((rslot + kRedElems - 1) / kRedElems), kRedElems * kRedSeqs, 0, s>>>(rpart, (int)P.slice_blocks, ds, c.Hr, c.E, g.Wr1,
                                                                            g.br1, g.Wr2, g.br2);
     return hipGetLastError();
 }
