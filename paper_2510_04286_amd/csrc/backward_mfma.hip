@@ -57,38 +57,33 @@ static BwdPacked bwd_packed_layout(int He)
     return L;
 }
 
-__global__ void bwd_pack_layer1_kernel(const bf16_t *__restrict__ W, int K, int Kv, int N, int Nv, size_t rs, size_t cs,
-                                       size_t src_stride, char *__restrict__ dst, size_t dst_stride, int nmat)
+// One thread per fragment (or bias value) of one job; see bwd_mfma.h for the layouts.
+__device__ __forceinline__ void pack_layer1_item(const BwdPackJob &J, long long f)
 {
-    const int KS = K / 16;
-    const long long per = (long long)(N / 32) * KS * 64;
-    const long long f = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (f >= per * nmat) return;
+    const int KS = J.K / 16;
+    const long long per = (long long)(J.N / 32) * KS * 64;
     const int mat = (int)(f / per);
     long long r = f - (long long)mat * per;
     const int lane = (int)(r % 64);
     r /= 64;
     const int ks = (int)(r % KS), nt = (int)(r / KS);
     const int i = lane & 31, g = lane >> 5;
-    const bf16_t *src = W + (size_t)mat * src_stride;
+    const bf16_t *src = J.src + (size_t)mat * J.src_stride;
     const int col = 32 * nt + i;
     uint32_t v[4];
     for (int m = 0; m < 8; m += 2) {
         const int k0 = 16 * ks + 8 * g + m;
-        const uint32_t lo = (k0 < Kv && col < Nv) ? src[(size_t)k0 * rs + (size_t)col * cs] : 0;
-        const uint32_t hi = (k0 + 1 < Kv && col < Nv) ? src[(size_t)(k0 + 1) * rs + (size_t)col * cs] : 0;
+        const uint32_t lo = (k0 < J.Kv && col < J.Nv) ? src[(size_t)k0 * J.rs + (size_t)col * J.cs] : 0;
+        const uint32_t hi = (k0 + 1 < J.Kv && col < J.Nv) ? src[(size_t)(k0 + 1) * J.rs + (size_t)col * J.cs] : 0;
         v[m / 2] = lo | (hi << 16);
     }
-    *(uint4 *)(dst + (size_t)mat * dst_stride + (size_t)(f - (long long)mat * per) * 16) = make_uint4(v[0], v[1], v[2], v[3]);
+    *(uint4 *)(J.dst + (size_t)mat * J.dst_stride + (size_t)(f - (long long)mat * per) * 16) = make_uint4(v[0], v[1], v[2], v[3]);
 }
 
-__global__ void bwd_pack_chain_kernel(const bf16_t *__restrict__ W, int K, int Kv, int N, int Nv, size_t rs, size_t cs,
-                                      size_t src_stride, char *__restrict__ dst, size_t dst_stride, int nmat, bool to_f16)
+__device__ __forceinline__ void pack_chain_item(const BwdPackJob &J, long long f)
 {
-    const int HT = K / 32, NT = N / 32;
+    const int HT = J.K / 32, NT = J.N / 32;
     const long long per = (long long)HT * 2 * NT * 64;
-    const long long f = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (f >= per * nmat) return;
     const int mat = (int)(f / per);
     long long r = f - (long long)mat * per;
     const int lane = (int)(r % 64);
@@ -97,15 +92,15 @@ __global__ void bwd_pack_chain_kernel(const bf16_t *__restrict__ W, int K, int K
     r /= NT;
     const int s = (int)(r % 2), ht = (int)(r / 2);
     const int i = lane & 31, g = lane >> 5;
-    const bf16_t *src = W + (size_t)mat * src_stride;
+    const bf16_t *src = J.src + (size_t)mat * J.src_stride;
     const int col = 32 * nt + i;
     uint32_t v[4];
     for (int m = 0; m < 8; m += 2) {
         uint32_t pr[2];
         for (int c = 0; c < 2; ++c) {
             const int kk = 32 * ht + chain_feature(s, g, m + c);
-            bf16_t w = (kk < Kv && col < Nv) ? src[(size_t)kk * rs + (size_t)col * cs] : (bf16_t)0;
-            if (to_f16) {   // bf16 values convert exactly unless tiny (rounded) or beyond the fp16 range (clamped)
+            bf16_t w = (kk < J.Kv && col < J.Nv) ? src[(size_t)kk * J.rs + (size_t)col * J.cs] : (bf16_t)0;
+            if (J.kind == kPackChainF16) {   // bf16 values convert exactly unless tiny (rounded) or beyond the fp16 range (clamped)
                 const _Float16 hv = (_Float16)fminf(fmaxf(bf16_to_f32(w), -65504.f), 65504.f);
                 w = __builtin_bit_cast(bf16_t, hv);
             }
@@ -113,16 +108,53 @@ __global__ void bwd_pack_chain_kernel(const bf16_t *__restrict__ W, int K, int K
         }
         v[m / 2] = pr[0] | (pr[1] << 16);
     }
-    *(uint4 *)(dst + (size_t)mat * dst_stride + (size_t)(f - (long long)mat * per) * 16) = make_uint4(v[0], v[1], v[2], v[3]);
+    *(uint4 *)(J.dst + (size_t)mat * J.dst_stride + (size_t)(f - (long long)mat * per) * 16) = make_uint4(v[0], v[1], v[2], v[3]);
 }
 
-__global__ void bwd_pack_bias_kernel(const bf16_t *__restrict__ b, int n, int npad, size_t src_stride,
-                                     char *__restrict__ dst, size_t dst_stride, int nmat)
+__device__ __forceinline__ void pack_bias_item(const BwdPackJob &J, long long t)
 {
-    const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= (long long)npad * nmat) return;
-    const int mat = (int)(t / npad), i = (int)(t - (long long)mat * npad);
-    ((float *)(dst + (size_t)mat * dst_stride))[i] = i < n ? bf16_to_f32(b[(size_t)mat * src_stride + i]) : 0.f;
+    // K = values per matrix, N = padded count
+    const int mat = (int)(t / J.N), i = (int)(t - (long long)mat * J.N);
+    ((float *)(J.dst + (size_t)mat * J.dst_stride))[i] = i < J.K ? bf16_to_f32(J.src[(size_t)mat * J.src_stride + i]) : 0.f;
+}
+
+__global__ void bwd_pack_jobs_kernel(BwdPackJobs jobs)
+{
+    long long f = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    for (int q = 0; q < jobs.count; ++q) {   // the jobs' items are numbered one job after the other
+        const BwdPackJob &J = jobs.job[q];
+        if (f < J.items) {
+            if (J.kind == kPackLayer1) pack_layer1_item(J, f);
+            else if (J.kind == kPackBias) pack_bias_item(J, f);
+            else pack_chain_item(J, f);
+            return;
+        }
+        f -= J.items;
+    }
+}
+
+BwdPackJob bwd_pack_job(int kind, const void *src, int K, int Kv, int N, int Nv, size_t rs, size_t cs, size_t src_stride,
+                        char *dst, size_t dst_stride, int nmat)
+{
+    BwdPackJob J;
+    J.kind = kind;
+    J.src = (const bf16_t *)src;
+    J.K = K; J.Kv = Kv; J.N = N; J.Nv = Nv;
+    J.rs = rs; J.cs = cs; J.src_stride = src_stride;
+    J.dst = dst; J.dst_stride = dst_stride;
+    if (kind == kPackLayer1) J.items = (long long)nmat * (N / 32) * (K / 16) * 64;
+    else if (kind == kPackBias) J.items = (long long)nmat * N;
+    else J.items = (long long)nmat * (K / 32) * 2 * (N / 32) * 64;
+    return J;
+}
+
+hipError_t bwd_pack_launch(const BwdPackJobs &jobs, hipStream_t s)
+{
+    long long total = 0;
+    for (int q = 0; q < jobs.count; ++q) total += jobs.job[q].items;
+    if (total == 0) return hipSuccess;
+    bwd_pack_jobs_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(jobs);
+    return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------------ rows kernel
@@ -432,17 +464,16 @@ hipError_t launch_backward_expert_mfma(const slicemoe_config &c, const void *h, 
     const BwdPacked L = bwd_packed_layout(c.He);
     const int He = c.He, E = c.E, ds = kBmDS;
     char *pb = (char *)packed;
-    const long long nfrag = (long long)E * (He / 32) * kBmKS * 64;
-    const int fb = (int)((nfrag + 255) / 256);
     const size_t wstride = (size_t)ds * He;
+    BwdPackJobs jobs;
+    jobs.count = 4;
     // w1f: the [ds, He] matrix W1 itself; w2r: the [ds, He] matrix M[c][hidden] = W2[hidden][c]
-    bwd_pack_layer1_kernel<<<fb, 256, 0, s>>>((const bf16_t *)w.W1, ds, ds, He, He, (size_t)He, 1, wstride, pb + L.w1f, L.stride, E);
-    bwd_pack_layer1_kernel<<<fb, 256, 0, s>>>((const bf16_t *)w.W2, ds, ds, He, He, 1, (size_t)ds, wstride, pb + L.w2r, L.stride, E);
+    jobs.job[0] = bwd_pack_job(kPackLayer1, w.W1, ds, ds, He, He, (size_t)He, 1, wstride, pb + L.w1f, L.stride, E);
+    jobs.job[1] = bwd_pack_job(kPackLayer1, w.W2, ds, ds, He, He, 1, (size_t)ds, wstride, pb + L.w2r, L.stride, E);
     // w1c: the [He, ds] matrix M[hidden][c] = W1[c][hidden], contraction over the hidden units in accumulator order
-    bwd_pack_chain_kernel<<<fb, 256, 0, s>>>((const bf16_t *)w.W1, He, He, ds, ds, 1, (size_t)He, wstride, pb + L.w1c, L.stride, E, false);
-    bwd_pack_bias_kernel<<<(int)(((long long)E * He + 255) / 256), 256, 0, s>>>((const bf16_t *)w.b1, He, He, (size_t)He, pb + L.b1,
-                                                                               L.stride, E);
-    hipError_t e = hipGetLastError();
+    jobs.job[2] = bwd_pack_job(kPackChain, w.W1, He, He, ds, ds, 1, (size_t)He, wstride, pb + L.w1c, L.stride, E);
+    jobs.job[3] = bwd_pack_job(kPackBias, w.b1, He, He, He, He, 0, 0, (size_t)He, pb + L.b1, L.stride, E);
+    const hipError_t e = bwd_pack_launch(jobs, s);
     if (e != hipSuccess) return e;
     if (He == 256) return run_expert_mfma<8>(c, L, h, d_out, pk, offsets, perm, pb, rows_per_chunk, chunks, slot_floats, dxrow, dpk, part, s);
     if (He == 128) return run_expert_mfma<4>(c, L, h, d_out, pk, offsets, perm, pb, rows_per_chunk, chunks, slot_floats, dxrow, dpk, part, s);

@@ -415,17 +415,19 @@ hipError_t launch_backward_router_mfma(const slicemoe_config &c, const void *h, 
     bf16_t *dg_lo = dg_hi + align_up((size_t)Ns * 32 * sizeof(bf16_t), 256) / sizeof(bf16_t);
     const bf16_t *Wr1 = (const bf16_t *)w.Wr1, *Wr2 = (const bf16_t *)w.Wr2;
     const int E = c.E, Hr = kRbHr, ds = kRbDS;
+    BwdPackJobs jobs;
+    jobs.count = 7;
     // w1f: Wr1 [ds, Hr] itself.  w2f: Wr2 [Hr, E] with the hidden units as contraction slots, fp16, experts padded to 32.
-    bwd_pack_layer1_kernel<<<(kRbHT * kRbKS * 64 + 255) / 256, 256, 0, s>>>(Wr1, ds, ds, Hr, Hr, (size_t)Hr, 1, 0, pb + L.w1f, 0, 1);
-    bwd_pack_chain_kernel<<<(kRbHT * 2 * 64 + 255) / 256, 256, 0, s>>>(Wr2, Hr, Hr, 32, E, (size_t)E, 1, 0, pb + L.w2f, 0, 1, true);
+    jobs.job[0] = bwd_pack_job(kPackLayer1, Wr1, ds, ds, Hr, Hr, (size_t)Hr, 1, 0, pb + L.w1f, 0, 1);
+    jobs.job[1] = bwd_pack_job(kPackChainF16, Wr2, Hr, Hr, 32, E, (size_t)E, 1, 0, pb + L.w2f, 0, 1);
     // w2c: M[e][h] = Wr2[h][e] ([32, Hr], experts as contraction slots).  w1c: M[h][c] = Wr1[c][h] ([Hr, ds]).
-    bwd_pack_chain_kernel<<<(2 * kRbHT * 64 + 255) / 256, 256, 0, s>>>(Wr2, 32, E, Hr, Hr, 1, (size_t)E, 0, pb + L.w2c, 0, 1, false);
-    bwd_pack_chain_kernel<<<(kRbHT * 2 * kRbOT * 64 + 255) / 256, 256, 0, s>>>(Wr1, Hr, Hr, ds, ds, 1, (size_t)Hr, 0, pb + L.w1c, 0, 1, false);
+    jobs.job[2] = bwd_pack_job(kPackChain, Wr2, 32, E, Hr, Hr, 1, (size_t)E, 0, pb + L.w2c, 0, 1);
+    jobs.job[3] = bwd_pack_job(kPackChain, Wr1, Hr, Hr, ds, ds, 1, (size_t)Hr, 0, pb + L.w1c, 0, 1);
     // w2r: M[e][h] = Wr2[h][e] ([32, Hr]) in plain K-steps of 16 experts
-    bwd_pack_layer1_kernel<<<(kRbHT * 2 * 64 + 255) / 256, 256, 0, s>>>(Wr2, 32, E, Hr, Hr, 1, (size_t)E, 0, pb + L.w2r, 0, 1);
-    bwd_pack_bias_kernel<<<1, 256, 0, s>>>((const bf16_t *)w.br1, Hr, Hr, 0, pb + L.b1, 0, 1);
-    bwd_pack_bias_kernel<<<1, 256, 0, s>>>((const bf16_t *)w.br2, E, 32, 0, pb + L.b2, 0, 1);
-    hipError_t e = hipGetLastError();
+    jobs.job[4] = bwd_pack_job(kPackLayer1, Wr2, 32, E, Hr, Hr, 1, (size_t)E, 0, pb + L.w2r, 0, 1);
+    jobs.job[5] = bwd_pack_job(kPackBias, w.br1, Hr, Hr, Hr, Hr, 0, 0, 0, pb + L.b1, 0, 1);
+    jobs.job[6] = bwd_pack_job(kPackBias, w.br2, E, E, 32, 32, 0, 0, 0, pb + L.b2, 0, 1);
+    hipError_t e = bwd_pack_launch(jobs, s);
     if (e != hipSuccess) return e;
 
     const long long ntiles = (Ns + 31) / 32;

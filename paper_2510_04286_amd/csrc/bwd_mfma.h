@@ -5,19 +5,30 @@
 
 namespace slicemoe {
 
-// One thread per 16-byte fragment.  Generic strided source so that the same kernel packs a matrix or its transpose:
-// element (kk, col) of the [K, N] matrix being packed is src[kk * rs + col * cs] for kk < Kv and col < Nv, and zero in
-// the padding up to K and N (multiples of 16 / 32).
-//   bwd_pack_layer1_kernel  [N/32][K/16][64]: lane (i, g), slot m: M[16ks + 8g + m][32nt + i]
-//   bwd_pack_chain_kernel   [K/32][2][N/32][64]: lane (i, g), slot m: M[32ht + chain_feature(s, g, m)][32nt + i], i.e. the
-//                           contraction slots follow the accumulator order; optionally converted to fp16
-__global__ void bwd_pack_layer1_kernel(const bf16_t *__restrict__ W, int K, int Kv, int N, int Nv, size_t rs, size_t cs,
-                                       size_t src_stride, char *__restrict__ dst, size_t dst_stride, int nmat);
-__global__ void bwd_pack_chain_kernel(const bf16_t *__restrict__ W, int K, int Kv, int N, int Nv, size_t rs, size_t cs,
-                                      size_t src_stride, char *__restrict__ dst, size_t dst_stride, int nmat, bool to_f16);
-// n values per matrix widened to fp32, zero-padded to npad
-__global__ void bwd_pack_bias_kernel(const bf16_t *__restrict__ b, int n, int npad, size_t src_stride,
-                                     char *__restrict__ dst, size_t dst_stride, int nmat);
+// Weight repacking for the backward kernels: a few jobs per launch, one thread per 16-byte fragment (or bias value).
+// Generic strided source so that the same code packs a matrix or its transpose: element (kk, col) of the [K, N] matrix
+// being packed is src[kk * rs + col * cs] for kk < Kv and col < Nv, and zero in the padding up to K and N (multiples of
+// 16 / 32).  nmat matrices, src_stride elements and dst_stride bytes apart.
+//   kPackLayer1    [N/32][K/16][64]: lane (i, g), slot m: M[16ks + 8g + m][32nt + i]
+//   kPackChain     [K/32][2][N/32][64]: lane (i, g), slot m: M[32ht + chain_feature(s, g, m)][32nt + i], i.e. the
+//                  contraction slots follow the accumulator order; kPackChainF16: the same converted to fp16
+//   kPackBias      K values per matrix widened to fp32, zero-padded to N
+enum { kPackLayer1 = 0, kPackChain = 1, kPackChainF16 = 2, kPackBias = 3 };
+struct BwdPackJob {
+    int kind, K, Kv, N, Nv;
+    const bf16_t *src;
+    size_t rs, cs, src_stride;
+    char *dst;
+    size_t dst_stride;
+    long long items;   // threads this job needs
+};
+struct BwdPackJobs {
+    int count;
+    BwdPackJob job[8];
+};
+BwdPackJob bwd_pack_job(int kind, const void *src, int K, int Kv, int N, int Nv, size_t rs, size_t cs, size_t src_stride,
+                        char *dst, size_t dst_stride, int nmat);
+hipError_t bwd_pack_launch(const BwdPackJobs &jobs, hipStream_t s);
 
 // Phi(z), and phi(z) through *density: the normal CDF by Abramowitz & Stegun 7.1.26 on |z| / sqrt 2 (|error| < 1.5e-7),
 // whose exponential exp(-z^2 / 2) is the density's.
