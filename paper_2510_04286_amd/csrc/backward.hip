@@ -259,8 +259,8 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_expert_kernel(
 }
 
 // Sum of the chunk slots of each expert in a fixed order: grid (E, pieces of 64 slot elements); a block is 64 elements
-// x 4 interleaved sequences of chunks, whose four partial sums are added in order at the end.
-constexpr int kRedElems = 64, kRedSeqs = 4;
+// x 8 interleaved sequences of chunks, whose eight partial sums are added in order at the end.
+constexpr int kRedElems = 64, kRedSeqs = 8;
 __global__ __launch_bounds__(kRedElems * kRedSeqs) void bwd_reduce_expert_kernel(
     const float *__restrict__ part, const int32_t *__restrict__ offsets, int ds, int He, int E, int rows_per_chunk,
     float *__restrict__ dW1, float *__restrict__ db1, float *__restrict__ dW2, float *__restrict__ db2)
@@ -279,12 +279,16 @@ __global__ __launch_bounds__(kRedElems * kRedSeqs) void bwd_reduce_expert_kernel
     for (int q = 0; q < e; ++q) first += nchs[q];
     const int nch = nchs[e];
     float acc = 0.f;
-    if (t < slot)
+    if (t < slot) {
+#pragma unroll 4
         for (int c = sq; c < nch; c += kRedSeqs) acc += part[(size_t)(first + c) * slot + t];
+    }
     red[sq][ex] = acc;
     __syncthreads();
     if (sq != 0 || t >= slot) return;
-    acc = ((red[0][ex] + red[1][ex]) + red[2][ex]) + red[3][ex];
+    acc = 0.f;
+#pragma unroll
+    for (int q = 0; q < kRedSeqs; ++q) acc += red[q][ex];   // fixed order
     const size_t nW = (size_t)ds * He;
     if (t < nW) dW1[(size_t)e * nW + t] = acc;
     else if (t < 2 * nW) dW2[(size_t)e * nW + (t - nW)] = acc;
@@ -511,12 +515,16 @@ __global__ __launch_bounds__(kRedElems * kRedSeqs) void bwd_reduce_router_kernel
     const size_t slot = router_slot_floats(ds, Hr, E);
     const size_t t = (size_t)blockIdx.x * kRedElems + ex;
     float acc = 0.f;
-    if (t < slot)
+    if (t < slot) {
+#pragma unroll 4
         for (int b = sq; b < nslots; b += kRedSeqs) acc += part[(size_t)b * slot + t];
+    }
     red[sq][ex] = acc;
     __syncthreads();
     if (sq != 0 || t >= slot) return;
-    acc = ((red[0][ex] + red[1][ex]) + red[2][ex]) + red[3][ex];
+    acc = 0.f;
+#pragma unroll
+    for (int q = 0; q < kRedSeqs; ++q) acc += red[q][ex];   // fixed order
     const size_t n1 = (size_t)ds * Hr, n2 = (size_t)Hr * E;
     if (t < n1) dWr1[t] = acc;
     else if (t < n1 + n2) dWr2[t - n1] = acc;
@@ -538,9 +546,9 @@ BackwardPlan backward_plan(const slicemoe_config &c)
     BackwardPlan p;
     const size_t Ns = (size_t)c.T * c.S, Na = Ns * c.k;
     const size_t ds = (size_t)(c.d / c.S);
-    // about five hundred chunks of stacked rows however large the batch (each has a slot of partial weight gradients),
+    // about a thousand chunks of stacked rows however large the batch (each has a slot of partial weight gradients),
     // at least 512 rows each, whole batches of rows
-    size_t rows = (Na + 511) / 512;
+    size_t rows = (Na + 1023) / 1024;
     rows = (rows + 31) / 32 * 32;   // whole 32-row units of the matrix-core kernels (and whole batches of kBwdRB)
     p.rows_per_chunk = (int)(rows < 512 ? 512 : rows);
     p.chunks = (long long)((Na + p.rows_per_chunk - 1) / p.rows_per_chunk) + c.E;   // worst case: every expert ends on a partial chunk
