@@ -253,10 +253,10 @@ slicemoe_status slicemoe_forward_train(const slicemoe_config *cfg, const void *h
  *                        added in a fixed order: same inputs, bit-identical weight gradients (and dL/dh, unless
  *                        He > 256, where the hidden units are cut into groups whose parts of dL/dx are added atomically).
  *   workspace            >= slicemoe_backward_workspace_bytes(cfg), 256-byte aligned
- * For bf16 storage with d/S = 64 and He in {64, 128, 256} (slicemoe_backward_uses_mfma: 1, 0, or -1 for an invalid
- * config) the expert part (row gradients, dL/dp, expert weight gradients) runs on the matrix cores, and with Hr = 256
- * and E <= 32 the router part too: fp32 pre-activations and derivatives, two-term bf16 operands for the second
- * matrix instructions, fp32-grade results.  Every other shape runs on vector-ALU kernels in fp32.
+ * For bf16 storage with d/S in {64, 96, 128} and He % 32 == 0 (slicemoe_backward_uses_mfma: 1, 0, or -1 for an
+ * invalid config) the expert part (row gradients, dL/dp, expert weight gradients) runs on the matrix cores, and with
+ * d/S = 64, Hr = 256 and E <= 32 the router part too: fp32 pre-activations and derivatives, two-term bf16 operands
+ * for the second matrix instructions, fp32-grade results.  Everything else runs on vector-ALU kernels in fp32.
  * SLICEMOE_FLAG_FORCE_GENERIC selects those throughout.  UNSUPPORTED for Hr > 256.
  */
 typedef struct {

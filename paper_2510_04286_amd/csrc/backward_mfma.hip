@@ -1,5 +1,5 @@
-// Matrix-core backward of the expert stage for slice width 64 and hidden widths up to 256 (the benchmark
-// shapes): the recomputed pre-activations, dL/dz, dL/dx, dL/dp and the expert weight gradients of the backward
+// Matrix-core backward of the expert stage for slice widths 64, 96 and 128 and any hidden width that is a multiple
+// of 32: the recomputed pre-activations, dL/dz, dL/dx, dL/dp and the expert weight gradients of the backward
 // pass described in backward.hip, on v_mfma_f32_32x32x16_bf16.  Two kernels, both without any exchange between
 // wavefronts:
 //
@@ -45,10 +45,10 @@ constexpr int kBmRowWaves = kBmRowThreads / 64;
 struct BwdPacked {
     size_t w1f, w2r, w1c, b1, stride;
 };
-static BwdPacked bwd_packed_layout(int He)
+static BwdPacked bwd_packed_layout(int ds, int He)
 {
     BwdPacked L;
-    const size_t frag = (size_t)kBmDS * He * 2;
+    const size_t frag = (size_t)ds * He * 2;
     L.w1f = 0;
     L.w2r = frag;
     L.w1c = 2 * frag;
@@ -265,24 +265,157 @@ __global__ __launch_bounds__(kBmRowThreads) void bwd_rows_mfma_kernel(
     }
 }
 
-// --------------------------------------------------------------------------------------------- weights kernel
-// grid.x = chunk (as the vector-ALU expert kernel numbers them), block = HT wavefronts; part: the chunk slots.
-template <int HT>
-__global__ __launch_bounds__(HT * 64) void bwd_weights_mfma_kernel(
+// ------------------------------------------------------------------------------------- rows kernel, streamed
+// The same computation for experts whose three fragment sets do not fit in LDS together (slice widths 96 and 128,
+// or He > 256 at width 64): a block takes tiles of kBmTileWaves x 32 rows of ONE expert and streams the fragments through
+// LDS in chunks of hc hidden tiles per row tile, the dL/dx accumulators staying in registers across the chunks.
+constexpr int kBmTileWaves = 8;
+constexpr int kBmTileRows = kBmTileWaves * 32;
+template <int DS>
+__global__ __launch_bounds__(kBmTileWaves * 64) void bwd_rows_streamed_mfma_kernel(
     const bf16_t *__restrict__ x, const bf16_t *__restrict__ dout, const float *__restrict__ pk,
     const int32_t *__restrict__ offsets, const int32_t *__restrict__ perm, const char *__restrict__ packed,
-    size_t e_stride, size_t off_w2r, size_t off_b1, int E, int k, int rows_per_chunk, size_t slot_floats,
+    size_t e_stride, size_t off_w2r, size_t off_w1c, size_t off_b1, int He, int hc, int E, int k,
+    float *__restrict__ dxrow, float *__restrict__ dpk)
+{
+    constexpr int KS = DS / 16, OT = DS / 32, THREADS = kBmTileWaves * 64;
+    const int HT = He / 32, nchunks = HT / hc;   // hc divides HT
+    extern __shared__ __align__(16) char lds[];
+    uint4 *w1f = (uint4 *)lds;                          // [hc][KS][64]
+    uint4 *w2r = w1f + (size_t)hc * KS * 64;            // [hc][KS][64]
+    uint4 *w1c = w2r + (size_t)hc * KS * 64;            // [hc][2][OT][64]
+    float *b1s = (float *)(w1c + (size_t)hc * 2 * OT * 64);   // [He]
+    int *tile_prefix = (int *)(b1s + He);               // [E + 1]
+
+    const int tid = threadIdx.x, lane = tid & 63, j = lane & 31, g = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    if (tid == 0) {
+        int run = 0;
+        for (int e = 0; e < E; ++e) {
+            tile_prefix[e] = run;
+            run += (offsets[e + 1] - offsets[e] + kBmTileRows - 1) / kBmTileRows;
+        }
+        tile_prefix[E] = run;
+    }
+    __syncthreads();
+    const int total = tile_prefix[E];
+    const int per_block = (total + (int)gridDim.x - 1) / (int)gridDim.x;
+    const int t_begin = (int)blockIdx.x * per_block;
+    const int t_end = min(total, t_begin + per_block);
+
+    int cur_e = -1, e = 0;
+    for (int t = t_begin; t < t_end; ++t) {
+        while (tile_prefix[e + 1] <= t) ++e;
+        const int row_begin = offsets[e] + (t - tile_prefix[e]) * kBmTileRows;
+        const int row_end = offsets[e + 1];
+        const char *ew = packed + (size_t)e * e_stride;
+        const int row = row_begin + wave * 32 + j;
+        const bool valid = row < row_end;
+        const int a = perm[valid ? row : row_begin];
+        const long long n = a / k;
+        const float p = valid ? pk[a] : 0.f;
+        const uint4 *xr = (const uint4 *)(x + n * DS), *gr = (const uint4 *)(dout + n * DS);
+        bf16x8 xb[KS], gb[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            xb[ks] = __builtin_bit_cast(bf16x8, xr[2 * ks + g]);
+            gb[ks] = __builtin_bit_cast(bf16x8, gr[2 * ks + g]);
+        }
+        f32x16 dx[OT];
+#pragma unroll
+        for (int ot = 0; ot < OT; ++ot)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) dx[ot][i] = 0.f;
+        float dp = 0.f;
+        for (int ch = 0; ch < nchunks; ++ch) {
+            __syncthreads();   // everyone is done with the previous contents
+            stage_bytes(ew + (size_t)ch * hc * KS * 1024, (char *)w1f, (size_t)hc * KS * 1024, tid, THREADS);
+            stage_bytes(ew + off_w2r + (size_t)ch * hc * KS * 1024, (char *)w2r, (size_t)hc * KS * 1024, tid, THREADS);
+            stage_bytes(ew + off_w1c + (size_t)ch * hc * 2 * OT * 1024, (char *)w1c, (size_t)hc * 2 * OT * 1024, tid, THREADS);
+            if (e != cur_e && ch == 0) {
+                const float *gb1 = (const float *)(ew + off_b1);
+                for (int i = tid; i < He; i += THREADS) b1s[i] = gb1[i];
+            }
+            __syncthreads();
+#pragma unroll 1
+            for (int hl = 0; hl < hc; ++hl) {
+                const int ht = ch * hc + hl;
+                f32x16 u, da;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) u[i] = da[i] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    u = mfma_bf16(__builtin_bit_cast(bf16x8, w1f[(hl * KS + ks) * 64 + lane]), xb[ks], u);
+                    da = mfma_bf16(__builtin_bit_cast(bf16x8, w2r[(hl * KS + ks) * 64 + lane]), gb[ks], da);
+                }
+                uint32_t hb[8], lb[8];
+#pragma unroll
+                for (int qq = 0; qq < 4; ++qq) {
+                    const f32x4 bb = *(const f32x4 *)(b1s + ht * 32 + 8 * qq + 4 * g);
+                    float pdz[4];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const int i = 4 * qq + c;
+                        const float z = fmaf(p, u[i], bb[c]);
+                        float dens;
+                        const float cdf = normal_cdf_pdf(z, &dens);
+                        const float dz = da[i] * fmaf(z, dens, cdf);
+                        dp = fmaf(dz, u[i], dp);
+                        pdz[c] = p * dz;
+                    }
+                    split_bf16x2(pdz[0], pdz[1], hb[2 * qq], lb[2 * qq]);
+                    split_bf16x2(pdz[2], pdz[3], hb[2 * qq + 1], lb[2 * qq + 1]);
+                }
+#pragma unroll
+                for (int s = 0; s < 2; ++s)
+#pragma unroll
+                    for (int ot = 0; ot < OT; ++ot) {
+                        const bf16x8 wf = __builtin_bit_cast(bf16x8, w1c[((hl * 2 + s) * OT + ot) * 64 + lane]);
+                        dx[ot] = mfma_bf16(wf, frag_of(lb, s), dx[ot]);   // small term first
+                        dx[ot] = mfma_bf16(wf, frag_of(hb, s), dx[ot]);
+                    }
+            }
+        }
+        cur_e = e;
+        dp += __shfl_xor(dp, 32);
+        if (valid) {
+            if (g == 0) dpk[a] = dp;
+            float *dst = dxrow + (size_t)row * DS;
+#pragma unroll
+            for (int ot = 0; ot < OT; ++ot)
+#pragma unroll
+                for (int qq = 0; qq < 4; ++qq) {
+                    const f32x4 v = {dx[ot][4 * qq], dx[ot][4 * qq + 1], dx[ot][4 * qq + 2], dx[ot][4 * qq + 3]};
+                    *(f32x4 *)(dst + ot * 32 + 8 * qq + 4 * g) = v;
+                }
+        }
+    }
+}
+
+// --------------------------------------------------------------------------------------------- weights kernel
+// grid.x = chunk (as the vector-ALU expert kernel numbers them), grid.y = group of kBmWgWaves hidden tiles, block = one
+// wavefront per hidden tile of the group; part: the chunk slots.  Slice width DS in {64, 96, 128}, any He % 32 == 0.
+constexpr int kBmWgWaves = 4;
+template <int DS>
+__global__ __launch_bounds__(kBmWgWaves * 64, DS <= 64 ? 2 : 1) void bwd_weights_mfma_kernel(   // width 64: two blocks per SIMD set
+    const bf16_t *__restrict__ x, const bf16_t *__restrict__ dout, const float *__restrict__ pk,
+    const int32_t *__restrict__ offsets, const int32_t *__restrict__ perm, const char *__restrict__ packed,
+    size_t e_stride, size_t off_w2r, size_t off_b1, int He, int E, int k, int rows_per_chunk, size_t slot_floats,
     float *__restrict__ part)
 {
-    constexpr int He = HT * 32;
+    constexpr int KS = DS / 16, OT = DS / 32;
+    const int HT = He / 32;
     extern __shared__ __align__(16) char lds[];
-    const uint4 *w1f = (const uint4 *)lds;
-    const uint4 *w2r = (const uint4 *)(lds + off_w2r);
-    const float *b1s = (const float *)(lds + off_b1);
+    // this group's fragments only: [wave][KS][64] of w1f, then of w2r, then 32 biases per wavefront
+    uint4 *w1f = (uint4 *)lds;
+    uint4 *w2r = w1f + kBmWgWaves * KS * 64;
+    float *b1s = (float *)(w2r + kBmWgWaves * KS * 64);
     __shared__ int blk[3];
 
     const int tid = threadIdx.x, lane = tid & 63, jj = lane & 31, g = lane >> 5;
-    const int ht = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ht0 = (int)blockIdx.y * kBmWgWaves;
+    const int ht = ht0 + wave;
     if (tid == 0) {
         int left = (int)blockIdx.x, e = 0, begin = 0, end = 0;
         bool found = false;
@@ -304,20 +437,30 @@ __global__ __launch_bounds__(HT * 64) void bwd_weights_mfma_kernel(
     __syncthreads();
     const int e = blk[0], row_begin = blk[1], row_end = blk[2];
     if (e < 0) return;   // uniform over the block
-    // w1f, w2r and w1c are adjacent: the first two (and the bias after w1c) are what this kernel reads
-    stage_bytes(packed + (size_t)e * e_stride, lds, e_stride, tid, HT * 64);
+    {   // fragments of the hidden tiles ht0 .. ht0 + 3 that exist (tile-major in the packed block, so one run each)
+        const int nt = min(kBmWgWaves, HT - ht0);
+        const char *src = packed + (size_t)e * e_stride;
+        const size_t run = (size_t)nt * KS * 1024;
+        stage_bytes(src + (size_t)ht0 * KS * 1024, (char *)w1f, run, tid, kBmWgWaves * 64);
+        stage_bytes(src + off_w2r + (size_t)ht0 * KS * 1024, (char *)w2r, run, tid, kBmWgWaves * 64);
+        const float *gb = (const float *)(src + off_b1);
+        if (tid < nt * 32) b1s[tid] = gb[ht0 * 32 + tid];
+    }
     __syncthreads();
+    if (ht >= HT) return;   // a group past the last hidden tile: no more barriers below
 
     bf16x8 id_even, id_odd;
     identity_fragments(jj, g, id_even, id_odd);
-    const float bias = b1s[ht * 32 + jj];
+    const float bias = b1s[wave * 32 + jj];
 
-    f32x16 aW1[kBmOT], aW2[kBmOT];
+    f32x16 aW1[OT], aW2[OT];
 #pragma unroll
-    for (int ot = 0; ot < kBmOT; ++ot)
+    for (int ot = 0; ot < OT; ++ot)
 #pragma unroll
         for (int i = 0; i < 16; ++i) aW1[ot][i] = aW2[ot][i] = 0.f;
-    float ab1 = 0.f, ab2[kBmOT] = {0.f, 0.f};
+    float ab1 = 0.f, ab2[OT];
+#pragma unroll
+    for (int ot = 0; ot < OT; ++ot) ab2[ot] = 0.f;
 
     for (int r0 = row_begin; r0 < row_end; r0 += 32) {
         const int row = r0 + jj;   // as A operand a lane holds row jj of the unit, contraction slots 8g..8g+7
@@ -325,10 +468,10 @@ __global__ __launch_bounds__(HT * 64) void bwd_weights_mfma_kernel(
         const int a = perm[valid ? row : row_begin];
         const long long n = a / k;
         const float p_lane = valid ? pk[a] : 0.f;
-        const uint4 *xr = (const uint4 *)(x + n * kBmDS), *gr = (const uint4 *)(dout + n * kBmDS);
-        bf16x8 xa[kBmKS], ga[kBmKS];
+        const uint4 *xr = (const uint4 *)(x + n * DS), *gr = (const uint4 *)(dout + n * DS);
+        bf16x8 xa[KS], ga[KS];
 #pragma unroll
-        for (int ks = 0; ks < kBmKS; ++ks) {
+        for (int ks = 0; ks < KS; ++ks) {
             xa[ks] = __builtin_bit_cast(bf16x8, xr[2 * ks + g]);
             const uint4 gv = valid ? gr[2 * ks + g] : make_uint4(0, 0, 0, 0);   // rows past the end add nothing
             ga[ks] = __builtin_bit_cast(bf16x8, gv);
@@ -338,9 +481,9 @@ __global__ __launch_bounds__(HT * 64) void bwd_weights_mfma_kernel(
 #pragma unroll
         for (int i = 0; i < 16; ++i) u[i] = da[i] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < kBmKS; ++ks) {
-            u = mfma_bf16(xa[ks], __builtin_bit_cast(bf16x8, w1f[(ht * kBmKS + ks) * 64 + lane]), u);
-            da = mfma_bf16(ga[ks], __builtin_bit_cast(bf16x8, w2r[(ht * kBmKS + ks) * 64 + lane]), da);
+        for (int ks = 0; ks < KS; ++ks) {
+            u = mfma_bf16(xa[ks], __builtin_bit_cast(bf16x8, w1f[(wave * KS + ks) * 64 + lane]), u);
+            da = mfma_bf16(ga[ks], __builtin_bit_cast(bf16x8, w2r[(wave * KS + ks) * 64 + lane]), da);
         }
         uint32_t a1p[8], a1l[8], pdzp[8], pdzl[8];
 #pragma unroll
@@ -361,7 +504,7 @@ __global__ __launch_bounds__(HT * 64) void bwd_weights_mfma_kernel(
             split_bf16x2(pdz[0], pdz[1], pdzp[i / 2], pdzl[i / 2]);
         }
 #pragma unroll
-        for (int ot = 0; ot < kBmOT; ++ot) {
+        for (int ot = 0; ot < OT; ++ot) {
             // x and dy of the unit with lane = slice feature 32 ot + jj, registers = rows
             f32x16 xt, gt;
 #pragma unroll
@@ -398,19 +541,19 @@ __global__ __launch_bounds__(HT * 64) void bwd_weights_mfma_kernel(
 
     // this chunk's slot: dW1 [ds][He] | dW2 [He][ds] | db1 [He] | db2 [ds]
     float *slot = part + (size_t)blockIdx.x * slot_floats;
-    float *pW1 = slot, *pW2 = pW1 + (size_t)kBmDS * He, *pb1 = pW2 + (size_t)He * kBmDS, *pb2 = pb1 + He;
+    float *pW1 = slot, *pW2 = pW1 + (size_t)DS * He, *pb1 = pW2 + (size_t)He * DS, *pb2 = pb1 + He;
 #pragma unroll
-    for (int ot = 0; ot < kBmOT; ++ot)
+    for (int ot = 0; ot < OT; ++ot)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             pW1[(size_t)(32 * ot + acc_feature(i, g)) * He + 32 * ht + jj] = aW1[ot][i];
-            pW2[(size_t)(32 * ht + acc_feature(i, g)) * kBmDS + 32 * ot + jj] = aW2[ot][i];
+            pW2[(size_t)(32 * ht + acc_feature(i, g)) * DS + 32 * ot + jj] = aW2[ot][i];
         }
     ab1 += __shfl_xor(ab1, 32);   // the two lane groups hold different rows of the same hidden unit
     if (g == 0) pb1[32 * ht + jj] = ab1;
     if (ht == 0) {
 #pragma unroll
-        for (int ot = 0; ot < kBmOT; ++ot) {
+        for (int ot = 0; ot < OT; ++ot) {
             const float t = ab2[ot] + __shfl_xor(ab2[ot], 32);
             if (g == 0) pb2[32 * ot + jj] = t;
         }
@@ -421,35 +564,68 @@ __global__ __launch_bounds__(HT * 64) void bwd_weights_mfma_kernel(
 bool backward_mfma_shape(const slicemoe_config &c)
 {
     const int ds = c.d / c.S;
-    return c.dtype == SLICEMOE_BF16 && ds == kBmDS && (c.He == 64 || c.He == 128 || c.He == 256) &&
-           !(c.flags & SLICEMOE_FLAG_FORCE_GENERIC) && bwd_packed_layout(c.He).stride <= (size_t)max_lds_per_block();
+    return c.dtype == SLICEMOE_BF16 && (ds == 64 || ds == 96 || ds == 128) && c.He % 32 == 0 &&
+           !(c.flags & SLICEMOE_FLAG_FORCE_GENERIC);
 }
 
 size_t backward_mfma_packed_bytes(const slicemoe_config &c)
 {
-    return backward_mfma_shape(c) ? bwd_packed_layout(c.He).stride * (size_t)c.E : 0;
+    return backward_mfma_shape(c) ? bwd_packed_layout(c.d / c.S, c.He).stride * (size_t)c.E : 0;
 }
 
-template <int HT>
+// Hidden tiles per chunk of the streamed rows kernel: the largest divisor of HT whose fragments fit, and its LDS bytes.
+static int streamed_chunk(int ds, int He, int E, size_t *lds)
+{
+    const int HT = He / 32, KS = ds / 16, OT = ds / 32;
+    const size_t per_ht = (size_t)(2 * KS + 2 * OT) * 1024, fixed = (size_t)He * 4 + (size_t)(E + 1) * 4 + 64;
+    const size_t want = 140 * 1024, dev = (size_t)max_lds_per_block();
+    const size_t budget = dev < want ? dev : want;
+    int hc = 1;
+    for (int c = HT; c >= 1; --c)
+        if (HT % c == 0 && per_ht * c + fixed <= budget) {
+            hc = c;
+            break;
+        }
+    *lds = per_ht * hc + fixed;
+    return hc;
+}
+
+template <int DS>
 static hipError_t run_expert_mfma(const slicemoe_config &c, const BwdPacked &L, const void *h, const void *d_out,
                                   const float *pk, const int32_t *offsets, const int32_t *perm, const char *packed,
                                   int rows_per_chunk, long long chunks, size_t slot_floats, float *dxrow, float *dpk,
                                   float *part, hipStream_t s)
 {
     const long long Na = (long long)c.T * c.S * c.k;
-    long long blocks = (Na + 31) / 32;
-    if (blocks > num_compute_units()) blocks = num_compute_units();
-    auto rows = bwd_rows_mfma_kernel<HT>;
-    hipError_t e = hipFuncSetAttribute((const void *)rows, hipFuncAttributeMaxDynamicSharedMemorySize, (int)L.stride);
-    if (e != hipSuccess) return e;
-    rows<<<(int)blocks, kBmRowThreads, L.stride, s>>>((const bf16_t *)h, (const bf16_t *)d_out, pk, offsets, perm, packed,
-                                                      L.stride, L.w2r, L.w1c, L.b1, c.E, c.k, dxrow, dpk);
+    const bf16_t *x = (const bf16_t *)h, *g = (const bf16_t *)d_out;
+    hipError_t e;
+    if (DS == 64 && (c.He == 64 || c.He == 128 || c.He == 256) && L.stride <= (size_t)max_lds_per_block()) {
+        // the whole expert resident in LDS, row units balanced over the blocks across expert boundaries
+        long long blocks = (Na + 31) / 32;
+        if (blocks > num_compute_units()) blocks = num_compute_units();
+        auto rows = c.He == 256 ? bwd_rows_mfma_kernel<8> : c.He == 128 ? bwd_rows_mfma_kernel<4> : bwd_rows_mfma_kernel<2>;
+        if ((e = hipFuncSetAttribute((const void *)rows, hipFuncAttributeMaxDynamicSharedMemorySize, (int)L.stride)) != hipSuccess)
+            return e;
+        rows<<<(int)blocks, kBmRowThreads, L.stride, s>>>(x, g, pk, offsets, perm, packed, L.stride, L.w2r, L.w1c, L.b1, c.E, c.k,
+                                                          dxrow, dpk);
+    } else {
+        size_t lds = 0;
+        const int hc = streamed_chunk(DS, c.He, c.E, &lds);
+        long long blocks = (Na + kBmTileRows - 1) / kBmTileRows + c.E;
+        if (blocks > num_compute_units()) blocks = num_compute_units();
+        auto rows = bwd_rows_streamed_mfma_kernel<DS>;
+        if ((e = hipFuncSetAttribute((const void *)rows, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess)
+            return e;
+        rows<<<(int)blocks, kBmTileWaves * 64, lds, s>>>(x, g, pk, offsets, perm, packed, L.stride, L.w2r, L.w1c, L.b1, c.He, hc,
+                                                         c.E, c.k, dxrow, dpk);
+    }
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    auto wk = bwd_weights_mfma_kernel<HT>;
-    e = hipFuncSetAttribute((const void *)wk, hipFuncAttributeMaxDynamicSharedMemorySize, (int)L.stride);
-    if (e != hipSuccess) return e;
-    wk<<<(unsigned)chunks, HT * 64, L.stride, s>>>((const bf16_t *)h, (const bf16_t *)d_out, pk, offsets, perm, packed, L.stride,
-                                                   L.w2r, L.b1, c.E, c.k, rows_per_chunk, slot_floats, part);
+    const int HT = c.He / 32;
+    const size_t lds_w = (size_t)2 * kBmWgWaves * (DS / 16) * 1024 + kBmWgWaves * 32 * sizeof(float);
+    auto wk = bwd_weights_mfma_kernel<DS>;
+    if ((e = hipFuncSetAttribute((const void *)wk, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_w)) != hipSuccess) return e;
+    wk<<<dim3((unsigned)chunks, (unsigned)((HT + kBmWgWaves - 1) / kBmWgWaves)), kBmWgWaves * 64, lds_w, s>>>(
+        x, g, pk, offsets, perm, packed, L.stride, L.w2r, L.b1, c.He, c.E, c.k, rows_per_chunk, slot_floats, part);
     return hipGetLastError();
 }
 
@@ -461,8 +637,8 @@ hipError_t launch_backward_expert_mfma(const slicemoe_config &c, const void *h, 
                                        float *part, hipStream_t s)
 {
     if (!backward_mfma_shape(c) || rows_per_chunk % 32 != 0) return hipErrorInvalidValue;
-    const BwdPacked L = bwd_packed_layout(c.He);
-    const int He = c.He, E = c.E, ds = kBmDS;
+    const int He = c.He, E = c.E, ds = c.d / c.S;
+    const BwdPacked L = bwd_packed_layout(ds, He);
     char *pb = (char *)packed;
     const size_t wstride = (size_t)ds * He;
     BwdPackJobs jobs;
@@ -475,9 +651,9 @@ hipError_t launch_backward_expert_mfma(const slicemoe_config &c, const void *h, 
     jobs.job[3] = bwd_pack_job(kPackBias, w.b1, He, He, He, He, 0, 0, (size_t)He, pb + L.b1, L.stride, E);
     const hipError_t e = bwd_pack_launch(jobs, s);
     if (e != hipSuccess) return e;
-    if (He == 256) return run_expert_mfma<8>(c, L, h, d_out, pk, offsets, perm, pb, rows_per_chunk, chunks, slot_floats, dxrow, dpk, part, s);
-    if (He == 128) return run_expert_mfma<4>(c, L, h, d_out, pk, offsets, perm, pb, rows_per_chunk, chunks, slot_floats, dxrow, dpk, part, s);
-    return run_expert_mfma<2>(c, L, h, d_out, pk, offsets, perm, pb, rows_per_chunk, chunks, slot_floats, dxrow, dpk, part, s);
+    if (ds == 64) return run_expert_mfma<64>(c, L, h, d_out, pk, offsets, perm, pb, rows_per_chunk, chunks, slot_floats, dxrow, dpk, part, s);
+    if (ds == 96) return run_expert_mfma<96>(c, L, h, d_out, pk, offsets, perm, pb, rows_per_chunk, chunks, slot_floats, dxrow, dpk, part, s);
+    return run_expert_mfma<128>(c, L, h, d_out, pk, offsets, perm, pb, rows_per_chunk, chunks, slot_floats, dxrow, dpk, part, s);
 }
 
 }  // namespace slicemoe

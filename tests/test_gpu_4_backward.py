@@ -58,6 +58,10 @@ CASES = {
     "E40": (wl.SliceMoEShape("E40", T=700, d=256, S=4, E=40, k=2, He=128), None, dict(tau=1.3, sigma=0.2, rate=0.2)),
     # one expert per slice under a capacity limit that drops: rows without gradient, experts cut short
     "k1_capacity": (wl.SliceMoEShape("k1cap", T=900, d=512, S=8, E=16, k=1, He=256, capacity_factor=0.8), None, None),
+    # streamed row kernel and several groups of hidden tiles at width 64; widths 96 and 128; a partial last group
+    "He512": (wl.SliceMoEShape("He512", T=300, d=256, S=4, E=4, k=2, He=512), None, None),
+    "ds128": (wl.SliceMoEShape("ds128", T=200, d=512, S=4, E=8, k=2, He=160), None, dict(tau=0.9, sigma=0.1, rate=0.2)),
+    "large_like": (wl.CONFIGS["large"], 24, None),
     "k3": (wl.SliceMoEShape("k3", T=150, d=256, S=4, E=8, k=3, He=96), None, dict(tau=0.7, sigma=0.0, rate=0.3)),
 }
 
@@ -69,7 +73,7 @@ def test_backward_matches_oracle(B, name):
     shape, h, w = make_inputs(base, T)
     cfg = B.config_of(shape, flags=B.SLICEMOE_FLAG_FORCE_GENERIC if len(CASES[name]) > 3 else 0)
     mfma = B.slicemoe_backward_uses_mfma(cfg) == 1
-    assert mfma == (shape.dtype == "bf16" and shape.ds == 64 and shape.He in (64, 128, 256) and len(CASES[name]) == 3)
+    assert mfma == (shape.dtype == "bf16" and shape.ds in (64, 96, 128) and shape.He % 32 == 0 and len(CASES[name]) == 3)
     dout = wl.make_dout(shape)
     noise, drop_u = wl.make_router_draws(shape)
     okw = dict(tau=1.0, sigma=0.0, rate=0.0)
