@@ -1,5 +1,5 @@
-// Matrix-core backward of the router and assembly of dL/dh, for slice width 64, Hr = 256 and E <= 32 (the benchmark
-// shapes with up to 32 experts).  Same mathematics as bwd_router_kernel in backward.hip; two kernels, both without
+// Matrix-core backward of the router and assembly of dL/dh, for slice widths 64 and 96, Hr = 256 and E <= 32 (the
+// benchmark shapes with up to 32 experts, and the paper's own).  Same mathematics as bwd_router_kernel in backward.hip; two kernels, both without
 // any exchange between wavefronts:
 //
 //   bwd_route_slices_mfma_kernel   the forward router's layout: a lane owns one slice of a 32-slice tile.  Pass 1
@@ -21,30 +21,31 @@ namespace slicemoe {
 typedef _Float16 r_h2 __attribute__((ext_vector_type(2)));
 typedef _Float16 r_f16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int kRbDS = 64, kRbKS = 4, kRbOT = 2;
 constexpr int kRbHr = 256, kRbHT = 8;
-constexpr int kRbThreads = 512;                 // both kernels: 8 wavefronts
+constexpr int kRbThreads = 512;                 // slices kernel: 8 wavefronts
 constexpr int kRbWaves = kRbThreads / 64;
-constexpr int kRbSliceBlock = 512;              // slices per block of the weights kernel (= kBwdSlices of backward.hip)
+constexpr int kRbWgWaves = 4;                   // weights kernel: one wavefront per hidden tile, two groups of four
+constexpr int kRbSliceBlock = 512;              // slices per slot of the weights kernel (= kBwdSlices of backward.hip)
 
 // Repacked router (bytes from the start of the buffer); every piece a multiple of 256 bytes.
-//   w1f  [8][4][64]     Wr1 fragments, lane (i, g), slot m: Wr1[16ks + 8g + m][32ht + i]           (bf16)
+//   w1f  [8][KS][64]    Wr1 fragments, lane (i, g), slot m: Wr1[16ks + 8g + m][32ht + i]           (bf16)
 //   w2f  [8][2][64]     Wr2 for the logits: lane (i, g), slot m: Wr2[32ht + chain(s, g, m)][i]      (fp16, experts >= E zero)
 //   w2c  [2][8][64]     Wr2 for dL/du:      lane (i, g), slot m: Wr2[32ht + i][chain(s, g, m)]      (bf16, experts >= E zero)
-//   w1c  [8][2][2][64]  Wr1 for dL/dx:      lane (i, g), slot m: Wr1[32ot + i][32ht + chain(s, g, m)] (bf16)
+//   w1c  [8][2][OT][64] Wr1 for dL/dx:      lane (i, g), slot m: Wr1[32ot + i][32ht + chain(s, g, m)] (bf16)
 //   w2r  [8][2][64]     rows of Wr2:        lane (i, g), slot m: Wr2[32ht + i][16s + 8g + m]        (bf16, experts >= E zero)
 //   b1 [256] fp32, b2 [32] fp32 (zero past E)
 struct RouterBwdPacked {
     size_t w1f, w2f, w2c, w1c, w2r, b1, b2, total;
 };
-static RouterBwdPacked router_bwd_layout()
+static RouterBwdPacked router_bwd_layout(int ds)
 {
     RouterBwdPacked L;
+    const int KS = ds / 16, OT = ds / 32;
     size_t at = 0;
-    L.w1f = at;  at += (size_t)kRbHT * kRbKS * 64 * 16;
+    L.w1f = at;  at += (size_t)kRbHT * KS * 64 * 16;
     L.w2f = at;  at += (size_t)kRbHT * 2 * 64 * 16;
     L.w2c = at;  at += (size_t)2 * kRbHT * 64 * 16;
-    L.w1c = at;  at += (size_t)kRbHT * 2 * kRbOT * 64 * 16;
+    L.w1c = at;  at += (size_t)kRbHT * 2 * OT * 64 * 16;
     L.w2r = at;  at += (size_t)kRbHT * 2 * 64 * 16;
     L.b1 = at;   at += (size_t)kRbHr * 4;
     L.b2 = at;   at += 256;
@@ -53,12 +54,14 @@ static RouterBwdPacked router_bwd_layout()
 }
 
 // ------------------------------------------------------------------------------------------------ slices kernel
+template <int DS>
 __global__ __launch_bounds__(kRbThreads) void bwd_route_slices_mfma_kernel(
     const bf16_t *__restrict__ x, long long Ns, int E, int k, const char *__restrict__ packed, RouterBwdPacked L,
     const float *__restrict__ noise, float sigma, float inv_tau, const float *__restrict__ drop_u, float rate,
     const int32_t *__restrict__ idx, const int32_t *__restrict__ inv, const float *__restrict__ dpk,
     const float *__restrict__ dxrow, bf16_t *__restrict__ dh, bf16_t *__restrict__ dg_hi, bf16_t *__restrict__ dg_lo)
 {
+    constexpr int kRbDS = DS, kRbKS = DS / 16, kRbOT = DS / 32;
     extern __shared__ __align__(16) char lds[];
     const uint4 *w1f = (const uint4 *)(lds + L.w1f);
     const uint4 *w2f = (const uint4 *)(lds + L.w2f);
@@ -268,28 +271,38 @@ __global__ __launch_bounds__(kRbThreads) void bwd_route_slices_mfma_kernel(
 }
 
 // ----------------------------------------------------------------------------------------------- weights kernel
-// grid.x = range of kRbSliceBlock slices (its slot of partial sums), block = one wavefront per hidden tile.
-__global__ __launch_bounds__(kRbThreads) void bwd_route_weights_mfma_kernel(
+// grid.x = range of kRbSliceBlock slices (its slot of partial sums), grid.y = group of four hidden tiles, block = one
+// wavefront per hidden tile of the group.
+template <int DS>
+__global__ __launch_bounds__(kRbWgWaves * 64, DS <= 64 ? 2 : 1) void bwd_route_weights_mfma_kernel(
     const bf16_t *__restrict__ x, long long Ns, int E, const char *__restrict__ packed, RouterBwdPacked L,
     const bf16_t *__restrict__ dg_hi, const bf16_t *__restrict__ dg_lo, size_t slot_floats, float *__restrict__ part)
 {
+    constexpr int kRbDS = DS, kRbKS = DS / 16, kRbOT = DS / 32;
     extern __shared__ __align__(16) char lds[];
-    // only w1f, w2r and b1 are read here; they are staged to the offsets they have in the packed buffer
-    const uint4 *w1f = (const uint4 *)(lds + L.w1f);
-    const uint4 *w2r = (const uint4 *)(lds + L.w2r);
-    const float *b1s = (const float *)(lds + L.b1);
+    // this group's fragments only: [wave][KS][64] of w1f, [wave][2][64] of w2r, 32 biases per wavefront
+    uint4 *w1f = (uint4 *)lds;
+    uint4 *w2r = w1f + kRbWgWaves * kRbKS * 64;
+    float *b1s = (float *)(w2r + kRbWgWaves * 2 * 64);
 
     const int tid = threadIdx.x, lane = tid & 63, jj = lane & 31, g = lane >> 5;
-    const int ht = __builtin_amdgcn_readfirstlane(tid >> 6);
-    stage_bytes(packed, lds, L.total, tid, kRbThreads);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ht0 = (int)blockIdx.y * kRbWgWaves, ht = ht0 + wave;   // kRbHT is a multiple of the group size
+    stage_bytes(packed + L.w1f + (size_t)ht0 * kRbKS * 1024, (char *)w1f, (size_t)kRbWgWaves * kRbKS * 1024, tid, kRbWgWaves * 64);
+    stage_bytes(packed + L.w2r + (size_t)ht0 * 2 * 1024, (char *)w2r, (size_t)kRbWgWaves * 2 * 1024, tid, kRbWgWaves * 64);
+    if (tid < kRbWgWaves * 32) b1s[tid] = ((const float *)(packed + L.b1))[ht0 * 32 + tid];
     __syncthreads();
     bf16x8 id_even, id_odd;
     identity_fragments(jj, g, id_even, id_odd);
-    const float bias = b1s[ht * 32 + jj];
+    const float bias = b1s[wave * 32 + jj];
 
     f32x16 aW1[kRbOT], aW2;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) aW1[0][i] = aW1[1][i] = aW2[i] = 0.f;
+    for (int i = 0; i < 16; ++i) {
+        aW2[i] = 0.f;
+#pragma unroll
+        for (int ot = 0; ot < kRbOT; ++ot) aW1[ot][i] = 0.f;
+    }
     float ab1 = 0.f, ab2 = 0.f;
 
     const long long n_begin = (long long)blockIdx.x * kRbSliceBlock;
@@ -316,10 +329,10 @@ __global__ __launch_bounds__(kRbThreads) void bwd_route_weights_mfma_kernel(
             du[i] = 0.f;
         }
 #pragma unroll
-        for (int ks = 0; ks < kRbKS; ++ks) u = mfma_bf16(xa[ks], __builtin_bit_cast(bf16x8, w1f[(ht * kRbKS + ks) * 64 + lane]), u);
+        for (int ks = 0; ks < kRbKS; ++ks) u = mfma_bf16(xa[ks], __builtin_bit_cast(bf16x8, w1f[(wave * kRbKS + ks) * 64 + lane]), u);
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
-            const bf16x8 wf = __builtin_bit_cast(bf16x8, w2r[(ht * 2 + s) * 64 + lane]);
+            const bf16x8 wf = __builtin_bit_cast(bf16x8, w2r[(wave * 2 + s) * 64 + lane]);
             du = mfma_bf16(gl[s], wf, du);
             du = mfma_bf16(gh[s], wf, du);
         }
@@ -389,15 +402,40 @@ __global__ __launch_bounds__(kRbThreads) void bwd_route_weights_mfma_kernel(
 // ------------------------------------------------------------------------------------------------------ host
 bool backward_router_mfma_shape(const slicemoe_config &c)
 {
-    return c.dtype == SLICEMOE_BF16 && c.d / c.S == kRbDS && c.Hr == kRbHr && c.E <= 32 &&
-           !(c.flags & SLICEMOE_FLAG_FORCE_GENERIC) && router_bwd_layout().total <= (size_t)max_lds_per_block();
+    const int ds = c.d / c.S;
+    return c.dtype == SLICEMOE_BF16 && (ds == 64 || ds == 96) && c.Hr == kRbHr && c.E <= 32 &&
+           !(c.flags & SLICEMOE_FLAG_FORCE_GENERIC) && router_bwd_layout(ds).total <= (size_t)max_lds_per_block();
 }
 
 size_t backward_router_mfma_scratch_bytes(const slicemoe_config &c)
 {
     if (!backward_router_mfma_shape(c)) return 0;
     const size_t Ns = (size_t)c.T * c.S;
-    return align_up(router_bwd_layout().total, 256) + 2 * align_up(Ns * 32 * sizeof(bf16_t), 256);
+    return align_up(router_bwd_layout(c.d / c.S).total, 256) + 2 * align_up(Ns * 32 * sizeof(bf16_t), 256);
+}
+
+template <int DS>
+static hipError_t run_router_mfma(const slicemoe_config &c, const RouterBwdPacked &L, const void *h, const RouteVariant &v,
+                                  const float *drop_u, float rate, const int32_t *idx, const int32_t *inv, const float *dpk,
+                                  const float *dxrow, void *d_h, const char *pb, bf16_t *dg_hi, bf16_t *dg_lo,
+                                  long long slice_blocks, size_t slot_floats, float *part, hipStream_t s)
+{
+    const long long Ns = (long long)c.T * c.S;
+    const long long ntiles = (Ns + 31) / 32;
+    const long long blocks = ntiles < num_compute_units() ? ntiles : num_compute_units();
+    auto sk = bwd_route_slices_mfma_kernel<DS>;
+    hipError_t e = hipFuncSetAttribute((const void *)sk, hipFuncAttributeMaxDynamicSharedMemorySize, (int)L.total);
+    if (e != hipSuccess) return e;
+    sk<<<(int)blocks, kRbThreads, L.total, s>>>((const bf16_t *)h, Ns, c.E, c.k, pb, L, v.sigma > 0.f ? v.noise : nullptr, v.sigma,
+                                                v.inv_tau, rate > 0.f ? drop_u : nullptr, rate, idx, inv, dpk, dxrow, (bf16_t *)d_h,
+                                                dg_hi, dg_lo);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    const size_t lds_w = (size_t)kRbWgWaves * (DS / 16 + 2) * 1024 + kRbWgWaves * 32 * sizeof(float);
+    auto wk = bwd_route_weights_mfma_kernel<DS>;
+    if ((e = hipFuncSetAttribute((const void *)wk, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_w)) != hipSuccess) return e;
+    wk<<<dim3((unsigned)slice_blocks, kRbHT / kRbWgWaves), kRbWgWaves * 64, lds_w, s>>>((const bf16_t *)h, Ns, c.E, pb, L, dg_hi, dg_lo,
+                                                                                       slot_floats, part);
+    return hipGetLastError();
 }
 
 // scratch: backward_router_mfma_scratch_bytes; part: ceil(Ns / 512) slots of slot_floats floats (the slice ranges of
@@ -409,12 +447,12 @@ hipError_t launch_backward_router_mfma(const slicemoe_config &c, const void *h, 
 {
     const long long Ns = (long long)c.T * c.S;
     if (!backward_router_mfma_shape(c) || slice_blocks != (Ns + kRbSliceBlock - 1) / kRbSliceBlock) return hipErrorInvalidValue;
-    const RouterBwdPacked L = router_bwd_layout();
+    const int E = c.E, Hr = kRbHr, ds = c.d / c.S;
+    const RouterBwdPacked L = router_bwd_layout(ds);
     char *pb = (char *)scratch;
     bf16_t *dg_hi = (bf16_t *)(pb + align_up(L.total, 256));
     bf16_t *dg_lo = dg_hi + align_up((size_t)Ns * 32 * sizeof(bf16_t), 256) / sizeof(bf16_t);
     const bf16_t *Wr1 = (const bf16_t *)w.Wr1, *Wr2 = (const bf16_t *)w.Wr2;
-    const int E = c.E, Hr = kRbHr, ds = kRbDS;
     BwdPackJobs jobs;
     jobs.count = 7;
     // w1f: Wr1 [ds, Hr] itself.  w2f: Wr2 [Hr, E] with the hidden units as contraction slots, fp16, experts padded to 32.
@@ -427,22 +465,11 @@ hipError_t launch_backward_router_mfma(const slicemoe_config &c, const void *h, 
     jobs.job[4] = bwd_pack_job(kPackLayer1, Wr2, 32, E, Hr, Hr, 1, (size_t)E, 0, pb + L.w2r, 0, 1);
     jobs.job[5] = bwd_pack_job(kPackBias, w.br1, Hr, Hr, Hr, Hr, 0, 0, 0, pb + L.b1, 0, 1);
     jobs.job[6] = bwd_pack_job(kPackBias, w.br2, E, E, 32, 32, 0, 0, 0, pb + L.b2, 0, 1);
-    hipError_t e = bwd_pack_launch(jobs, s);
+    const hipError_t e = bwd_pack_launch(jobs, s);
     if (e != hipSuccess) return e;
-
-    const long long ntiles = (Ns + 31) / 32;
-    long long blocks = ntiles < num_compute_units() ? ntiles : num_compute_units();
-    e = hipFuncSetAttribute((const void *)bwd_route_slices_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)L.total);
-    if (e != hipSuccess) return e;
-    bwd_route_slices_mfma_kernel<<<(int)blocks, kRbThreads, L.total, s>>>(
-        (const bf16_t *)h, Ns, E, c.k, pb, L, v.sigma > 0.f ? v.noise : nullptr, v.sigma, v.inv_tau, rate > 0.f ? drop_u : nullptr,
-        rate, idx, inv, dpk, dxrow, (bf16_t *)d_h, dg_hi, dg_lo);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void *)bwd_route_weights_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)L.total);
-    if (e != hipSuccess) return e;
-    bwd_route_weights_mfma_kernel<<<(unsigned)slice_blocks, kRbThreads, L.total, s>>>((const bf16_t *)h, Ns, E, pb, L, dg_hi, dg_lo,
-                                                                                     slot_floats, part);
-    return hipGetLastError();
+    if (ds == 64)
+        return run_router_mfma<64>(c, L, h, v, drop_u, rate, idx, inv, dpk, dxrow, d_h, pb, dg_hi, dg_lo, slice_blocks, slot_floats, part, s);
+    return run_router_mfma<96>(c, L, h, v, drop_u, rate, idx, inv, dpk, dxrow, d_h, pb, dg_hi, dg_lo, slice_blocks, slot_floats, part, s);
 }
 
 }  // namespace slicemoe
