@@ -215,7 +215,7 @@ def main():
         bflops = 10 * ds * He * n_kept_rows(B, cfg, ws) + 6 * Ns * (ds * Hr + Hr * E)
         backward = {"ms": round(bms, 4), "calls": nb, "flops": bflops, "tflops": round(bflops / (bms * 1e-3) / 1e12, 2),
                     "expert_kernels": "matrix-core" if B.slicemoe_backward_uses_mfma(cfg) == 1 else "vector-ALU fp32",
-                    "router_kernels": "matrix-core" if B.slicemoe_backward_uses_mfma(cfg) == 1 and shape.ds in (64, 96) and shape.E <= 32 else "vector-ALU fp32"}
+                    "router_kernels": "matrix-core" if B.slicemoe_backward_uses_mfma(cfg) == 1 and shape.Hr == 256 and shape.E <= 64 else "vector-ALU fp32"}
 
     cpu = None
     if not args.no_cpu_baseline:

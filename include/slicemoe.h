@@ -255,7 +255,7 @@ slicemoe_status slicemoe_forward_train(const slicemoe_config *cfg, const void *h
  *   workspace            >= slicemoe_backward_workspace_bytes(cfg), 256-byte aligned
  * For bf16 storage with d/S in {64, 96, 128} and He % 32 == 0 (slicemoe_backward_uses_mfma: 1, 0, or -1 for an
  * invalid config) the expert part (row gradients, dL/dp, expert weight gradients) runs on the matrix cores, and with
- * d/S in {64, 96}, Hr = 256 and E <= 32 the router part too: fp32 pre-activations and derivatives, two-term bf16 operands
+ * Hr = 256 the router part too: fp32 pre-activations and derivatives, two-term bf16 operands
  * for the second matrix instructions, fp32-grade results.  Everything else runs on vector-ALU kernels in fp32.
  * SLICEMOE_FLAG_FORCE_GENERIC selects those throughout.  UNSUPPORTED for Hr > 256.
  */

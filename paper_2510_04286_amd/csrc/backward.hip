@@ -591,7 +591,7 @@ static hipError_t run_backward(const slicemoe_config &c, const void *h, const sl
 
     const int hidden_groups = (c.He + kBwdThreads - 1) / kBwdThreads;
     const int col_chunks = (ds + kBwdCols - 1) / kBwdCols;
-    if (hidden_groups > 1) {   // partial sums over the hidden groups are added atomically
+    if (hidden_groups > 1 && !backward_mfma_shape(c)) {   // partial sums over the hidden groups are added atomically
         if ((e = zero_fill(dxrow, (size_t)Na * ds, s)) != hipSuccess) return e;
         if ((e = zero_fill(dpk, (size_t)Na, s)) != hipSuccess) return e;
     }

@@ -54,7 +54,7 @@ CASES = {
     "headline_generic": (wl.CONFIGS["headline"], 130, None, "generic"),             # vector-ALU kernels on a matrix-core shape
     "He128": (wl.SliceMoEShape("He128", T=300, d=256, S=4, E=8, k=2, He=128), None, dict(tau=1.0, sigma=0.0, rate=0.2)),
     "He64": (wl.SliceMoEShape("He64", T=97, d=128, S=2, E=4, k=1, He=64), None, None),
-    # matrix-core expert part with the vector-ALU router part (more than 32 experts)
+    # more than 32 experts: two expert tiles in the matrix-core router part, the second one partly padding
     "E40": (wl.SliceMoEShape("E40", T=700, d=256, S=4, E=40, k=2, He=128), None, dict(tau=1.3, sigma=0.2, rate=0.2)),
     # one expert per slice under a capacity limit that drops: rows without gradient, experts cut short
     "k1_capacity": (wl.SliceMoEShape("k1cap", T=900, d=512, S=8, E=16, k=1, He=256, capacity_factor=0.8), None, None),
@@ -62,6 +62,8 @@ CASES = {
     "He512": (wl.SliceMoEShape("He512", T=300, d=256, S=4, E=4, k=2, He=512), None, None),
     "ds128": (wl.SliceMoEShape("ds128", T=200, d=512, S=4, E=8, k=2, He=160), None, dict(tau=0.9, sigma=0.1, rate=0.2)),
     "large_like": (wl.CONFIGS["large"], 24, None),
+    "ds96_E48": (wl.SliceMoEShape("ds96_E48", T=333, d=384, S=4, E=48, k=2, He=96), None, dict(tau=1.2, sigma=0.1, rate=0.2)),
+    "ds128_E64": (wl.SliceMoEShape("ds128_E64", T=333, d=512, S=4, E=64, k=2, He=64), None, dict(tau=0.8, sigma=0.2, rate=0.25)),
     "k3": (wl.SliceMoEShape("k3", T=150, d=256, S=4, E=8, k=3, He=96), None, dict(tau=0.7, sigma=0.0, rate=0.3)),
 }
 
