@@ -232,7 +232,20 @@ __global__ __launch_bounds__(kRbThreads) void bwd_route_logits_mfma_kernel(
 }
 
 // ------------------------------------------------------------------------------------------------ inputs kernel
-// LDS: w2c | w1c (the third and fourth pieces of the packed buffer, adjacent).
+// Rows of the per-wavefront staging tile are 36 floats apart: 16-byte reads at a stride of one row then fall into
+// distinct banks.
+constexpr int kRbStageRow = 36;
+
+// Orders LDS traffic between the lanes of one wavefront (the hardware keeps a wavefront's LDS operations in order; this
+// keeps the compiler from moving them across).
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// LDS: w2c | w1c (the third and fourth pieces of the packed buffer, adjacent) | staging tiles.
 template <int DS, int ET>
 __global__ __launch_bounds__(kRbThreads) void bwd_route_inputs_mfma_kernel(
     long long Ns, int k, const char *__restrict__ packed, RouterBwdPacked L, const int32_t *__restrict__ inv,
@@ -243,11 +256,13 @@ __global__ __launch_bounds__(kRbThreads) void bwd_route_inputs_mfma_kernel(
     extern __shared__ __align__(16) char lds[];
     const uint4 *w2c = (const uint4 *)lds;                       // [ET][2][8][64]
     const uint4 *w1c = w2c + ET * 2 * kRbHT * 64;                // [8][2][OT][64]
+    float *stg_all = (float *)(w1c + kRbHT * 2 * OT * 64);       // [8 wavefronts][32][kRbStageRow]
 
     const int tid = threadIdx.x, lane = tid & 63, j = lane & 31, g = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     stage_bytes(packed + L.w2c, lds, (size_t)(ET * 2 * kRbHT + kRbHT * 2 * OT) * 1024, tid, kRbThreads);
     __syncthreads();
+    float *stg = stg_all + wave * 32 * kRbStageRow;
 
     const long long ntiles = (Ns + 31) / 32;
     for (long long tile = (long long)wave * gridDim.x + blockIdx.x; tile < ntiles; tile += (long long)gridDim.x * kRbWaves) {
@@ -310,22 +325,49 @@ __global__ __launch_bounds__(kRbThreads) void bwd_route_inputs_mfma_kernel(
                 }
         }
 
-        // dL/dh of the slice: router path plus the expert-path rows of its k assignments, one rounding
-        if (valid) {
-            int rows[8];
+        // dL/dh of the slices: router path plus the expert-path rows of their k assignments, one rounding.  The rows are
+        // gathered and the result is stored through a tile of LDS private to the wavefront, one 32-feature tile at a
+        // time, so that every memory instruction covers whole 128-byte (gather) or 64-byte (store) runs: eight lanes per
+        // slice fetch and add the k row pieces, lane (j, g) picks up its accumulator order from the tile, adds the router
+        // path, rounds, and puts the packed row back for four lanes per slice to store.
+        const long long n0 = tile * 32;
+        const int piece = lane & 7, sl = lane >> 3;
+        int rws[4][8];
 #pragma unroll
-            for (int jj = 0; jj < 8; ++jj) rows[jj] = jj < k ? inv[n * k + jj] : -1;
+        for (int it = 0; it < 4; ++it) {
+            const long long ns = n0 + it * 8 + sl;
 #pragma unroll
-            for (int ot = 0; ot < OT; ++ot)
+            for (int jj = 0; jj < 8; ++jj) rws[it][jj] = (jj < k && ns < Ns) ? inv[ns * k + jj] : -1;
+        }
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int feat = 32 * ot + 8 * q + 4 * g;
-                    f32x4 t = {dx[ot][4 * q], dx[ot][4 * q + 1], dx[ot][4 * q + 2], dx[ot][4 * q + 3]};
+        for (int ot = 0; ot < OT; ++ot) {
 #pragma unroll
-                    for (int jj = 0; jj < 8; ++jj)
-                        if (rows[jj] >= 0) t += *(const f32x4 *)(dxrow + (size_t)rows[jj] * DS + feat);
-                    *(uint2 *)(dh + n * DS + feat) = make_uint2(pack_bf16x2(t[0], t[1]), pack_bf16x2(t[2], t[3]));
-                }
+            for (int it = 0; it < 4; ++it) {
+                f32x4 v = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int jj = 0; jj < 8; ++jj)
+                    if (rws[it][jj] >= 0) v += *(const f32x4 *)(dxrow + (size_t)rws[it][jj] * DS + 32 * ot + 4 * piece);
+                *(f32x4 *)(stg + (it * 8 + sl) * kRbStageRow + 4 * piece) = v;
+            }
+            wave_lds_sync();
+            uint2 o[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x4 t = *(const f32x4 *)(stg + j * kRbStageRow + 8 * q + 4 * g);
+                o[q] = make_uint2(pack_bf16x2(dx[ot][4 * q] + t[0], dx[ot][4 * q + 1] + t[1]),
+                                  pack_bf16x2(dx[ot][4 * q + 2] + t[2], dx[ot][4 * q + 3] + t[3]));
+            }
+            wave_lds_sync();   // every lane has read its sums: the tile now takes the packed rows (64 bytes per slice)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) *(uint2 *)((char *)(stg + j * kRbStageRow) + (8 * q + 4 * g) * 2) = o[q];
+            wave_lds_sync();
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const int i = half * 16 + (lane >> 2), pc = lane & 3;
+                const long long ns = n0 + i;
+                if (ns < Ns) *(uint4 *)(dh + ns * DS + 32 * ot + 8 * pc) = *(const uint4 *)((const char *)(stg + i * kRbStageRow) + pc * 16);
+            }
+            wave_lds_sync();   // before the next gather overwrites the tile
         }
     }
 }
@@ -472,7 +514,10 @@ __global__ __launch_bounds__(kRbWgWaves * 64, (DS <= 64 && ET == 1) ? 2 : 1) voi
 
 // ------------------------------------------------------------------------------------------------------ host
 static size_t logits_lds(int ds, int ET) { return (size_t)(kRbHT * (ds / 16) + kRbHT * 2 * ET) * 1024 + (kRbHr + 32 * ET) * sizeof(float); }
-static size_t inputs_lds(int ds, int ET) { return (size_t)(ET * 2 * kRbHT + kRbHT * 2 * (ds / 32)) * 1024; }
+static size_t inputs_lds(int ds, int ET)
+{
+    return (size_t)(ET * 2 * kRbHT + kRbHT * 2 * (ds / 32)) * 1024 + (size_t)kRbWaves * 32 * kRbStageRow * sizeof(float);
+}
 static size_t weights_lds(int ds, int ET) { return (size_t)kRbWgWaves * (ds / 16 + 2 * ET) * 1024 + kRbWgWaves * 32 * sizeof(float); }
 
 bool backward_router_mfma_shape(const slicemoe_config &c)
@@ -511,17 +556,27 @@ static hipError_t run_router_mfma(const slicemoe_config &c, const RouterBwdPacke
                                   long long slice_blocks, size_t slot_floats, float *part, hipStream_t s)
 {
     const long long Ns = (long long)c.T * c.S;
-    const long long ntiles = (Ns + 31) / 32;
-    const long long blocks = ntiles < num_compute_units() ? ntiles : num_compute_units();
+    const long long ntiles = (Ns + 31) / 32, units = (ntiles + kRbWaves - 1) / kRbWaves;
     auto lk = bwd_route_logits_mfma_kernel<DS, ET>;
     hipError_t e = hipFuncSetAttribute((const void *)lk, hipFuncAttributeMaxDynamicSharedMemorySize, (int)logits_lds(DS, ET));
     if (e != hipSuccess) return e;
+    // as many blocks as can be resident at once (registers and LDS allow two per CU for the narrow shapes)
+    static int lk_per_cu = 0;   // per instantiation; the same on every device of the machine
+    if (lk_per_cu == 0) {
+        int n = 1;
+        if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, (const void *)lk, kRbThreads, logits_lds(DS, ET))) != hipSuccess) return e;
+        lk_per_cu = n < 1 ? 1 : n;
+    }
+    long long blocks = (long long)num_compute_units() * lk_per_cu;
+    if (blocks > units) blocks = units;
     lk<<<(int)blocks, kRbThreads, logits_lds(DS, ET), s>>>((const bf16_t *)h, Ns, c.E, c.k, pb, L, v.sigma > 0.f ? v.noise : nullptr,
                                                            v.sigma, v.inv_tau, rate > 0.f ? drop_u : nullptr, rate, idx, inv, dpk,
                                                            dg_hi, dg_lo, bits);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     auto ik = bwd_route_inputs_mfma_kernel<DS, ET>;
     if ((e = hipFuncSetAttribute((const void *)ik, hipFuncAttributeMaxDynamicSharedMemorySize, (int)inputs_lds(DS, ET))) != hipSuccess) return e;
+    // one block per CU: this kernel waits on its row gathers, and a second resident block measured slower (cache misses)
+    blocks = num_compute_units() < units ? num_compute_units() : units;
     ik<<<(int)blocks, kRbThreads, inputs_lds(DS, ET), s>>>(Ns, c.k, pb, L, inv, dxrow, dg_hi, dg_lo, bits, (bf16_t *)d_h);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     auto wk = bwd_route_weights_mfma_kernel<DS, ET>;
