@@ -2,7 +2,8 @@
 
 Each case runs the forward on the GPU (inference or training-time router), then the backward with a seeded upstream
 gradient.  The oracle runs its own forward and backward from the same inputs; the routing must agree exactly on these
-cases (no near-tie among them), because a weight gradient sums over every slice.
+cases (no near-tie among them), because a weight gradient sums over every slice; the one full-size case says how it
+treats the few near-ties it has.
 Bars, derived from the arithmetic (the forward's tolerance is stated for h' only).  Two kinds of kernels: vector-ALU
 (fp32 throughout, exact GELU) and, for the expert part of the benchmark shapes, matrix-core (fp32 pre-activations and
 derivative, erf to 1.5e-7; p dL/dz and the activation enter the second matrix instructions as two-term bf16 splits
@@ -64,6 +65,11 @@ CASES = {
     "large_like": (wl.CONFIGS["large"], 24, None),
     "ds96_E48": (wl.SliceMoEShape("ds96_E48", T=333, d=384, S=4, E=48, k=2, He=96), None, dict(tau=1.2, sigma=0.1, rate=0.2)),
     "ds128_E64": (wl.SliceMoEShape("ds128_E64", T=333, d=512, S=4, E=64, k=2, He=64), None, dict(tau=0.8, sigma=0.2, rate=0.25)),
+    # the benchmark workload at its full size (the launch configuration bench.py times): 524 288 rows, 16 384 per expert.
+    # Among 262 144 slices a few are near-ties; where the GPU resolves one the other way, that slice's dL/dh is left
+    # out and one row moves between two experts' sums, far below the weight-gradient bar
+    "headline_full": (wl.CONFIGS["headline"], None, None, "ties"),
+    "paper_full": (wl.CONFIGS["paper"], None, dict(tau=1.0, sigma=0.0, rate=0.2), "ties"),
     "k3": (wl.SliceMoEShape("k3", T=150, d=256, S=4, E=8, k=3, He=96), None, dict(tau=0.7, sigma=0.0, rate=0.3)),
 }
 
@@ -73,9 +79,10 @@ def test_backward_matches_oracle(B, name):
     import torch
     base, T, train = CASES[name][:3]
     shape, h, w = make_inputs(base, T)
-    cfg = B.config_of(shape, flags=B.SLICEMOE_FLAG_FORCE_GENERIC if len(CASES[name]) > 3 else 0)
+    option = CASES[name][3] if len(CASES[name]) > 3 else None
+    cfg = B.config_of(shape, flags=B.SLICEMOE_FLAG_FORCE_GENERIC if option == "generic" else 0)
     mfma = B.slicemoe_backward_uses_mfma(cfg) == 1
-    assert mfma == (shape.dtype == "bf16" and shape.ds in (64, 96, 128) and shape.He % 32 == 0 and len(CASES[name]) == 3)
+    assert mfma == (shape.dtype == "bf16" and shape.ds in (64, 96, 128) and shape.He % 32 == 0 and option != "generic")
     dout = wl.make_dout(shape)
     noise, drop_u = wl.make_router_draws(shape)
     okw = dict(tau=1.0, sigma=0.0, rate=0.0)
@@ -106,8 +113,11 @@ def test_backward_matches_oracle(B, name):
 
     views = B.workspace_views(cfg, ws)
     mism, n_tie = routing_agreement(views["topk_idx"].cpu().numpy(), ref_f["idx"], ref_f["logits"])
-    assert n_tie == 0, "this case was chosen to have no near-tie; pick another token count"
-    np.testing.assert_array_equal(views["inv"].cpu().numpy(), ref_f["inv"])
+    if option == "ties":
+        assert n_tie <= 8, n_tie
+    else:
+        assert n_tie == 0, "this case was chosen to have no near-tie; pick another token count"
+        np.testing.assert_array_equal(views["inv"].cpu().numpy(), ref_f["inv"])
 
     got_dh = d_h.float().cpu().numpy().astype(np.float64)
     scale_dh = rms(ref["d_h"])
@@ -116,6 +126,8 @@ def test_backward_matches_oracle(B, name):
     else:
         bound = 2.0 ** -8 * np.abs(ref["d_h"]) + 2e-4 * scale_dh
     excess = np.abs(got_dh - ref["d_h"]) / bound
+    if n_tie:
+        excess.reshape(shape.T * shape.S, shape.ds)[mism] = 0.0
     err_dh = np.abs(got_dh - ref["d_h"]).max() / scale_dh
     report = [f"d_h {err_dh:.2e} (worst element at {excess.max():.2f} of its bound)"]
     failed = []
@@ -127,7 +139,7 @@ def test_backward_matches_oracle(B, name):
         report.append(f"{n} {err:.1e}" + (f" (rms {rms(got - ref[n]) / scale:.1e})" if mfma and n in ("W1", "W2") else ""))
         if err > TOL_WGRAD:
             failed.append((n, err))
-    print(f"\n[backward {name}] rows={int(ref_f['offsets'][-1])} max|err|/rms: " + " ".join(report))
+    print(f"\n[backward {name}] near-tie slices resolved differently: {n_tie}; rows={int(ref_f['offsets'][-1])} max|err|/rms: " + " ".join(report))
     assert not failed, failed
     assert excess.max() <= 1.0, excess.max()
 
