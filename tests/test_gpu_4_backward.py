@@ -144,6 +144,60 @@ def test_backward_matches_oracle(B, name):
     assert excess.max() <= 1.0, excess.max()
 
 
+def test_backward_large_workload_full_size_sampled(B):
+    """The Large workload at its full size (4 194 304 rows), as bench.py --workload large --backward launches it.  The oracle
+    cannot run it whole, so it evaluates a seeded sample of tokens (dropless: a token's dL/dh depends on nothing but
+    that token), and the expert output bias, whose gradient has a closed form that holds at any size -- the sum of the
+    upstream gradient over the slices routed to the expert -- is checked for every expert through the routing table."""
+    import torch
+    shape = wl.CONFIGS["large"]
+    assert shape.capacity() < 0
+    w = wl.make_weights(shape)
+    h = wl.make_h(shape)
+    dout = wl.make_dout(shape)
+    cfg = B.config_of(shape)
+    assert B.slicemoe_backward_uses_mfma(cfg) == 1
+    wd = B.pack(cfg, B.weights_to_device(w, shape.dtype))
+    ws = B.alloc_workspace(cfg)
+    hd = B.to_device(h, shape.dtype)
+    out = torch.empty((shape.T, shape.d), dtype=torch.bfloat16, device="cuda:0")
+    B.slicemoe_forward(cfg, hd, wd, out, ws)
+    del out
+    grads = B.alloc_weight_grads(cfg)
+    d_h = torch.empty_like(hd)
+    bws = torch.empty(B.slicemoe_backward_workspace_bytes(cfg), dtype=torch.uint8, device="cuda:0")
+    B.slicemoe_backward(cfg, hd, wd, ws, B.to_device(dout, shape.dtype), d_h, grads, bws)
+    torch.cuda.synchronize()
+    del bws
+
+    tokens = np.unique((wl.uniform01(78, 0, 0, 96) * shape.T).astype(np.int64))
+    ref_f = oracle.forward_train(h[tokens], shape.S, shape.k, w, noise=None, drop_u=None, capacity=-1, tau=1.0, sigma=0.0,
+                                 rate=0.0)
+    ref = oracle.backward(h[tokens], shape.S, shape.k, w, dout[tokens], ref_f["idx"], ref_f["inv"])
+    idx = B.workspace_views(cfg, ws)["topk_idx"].cpu().numpy()
+    slices = (tokens[:, None] * shape.S + np.arange(shape.S)[None, :]).reshape(-1)
+    mism, n_tie = routing_agreement(idx[slices], ref_f["idx"], ref_f["logits"])
+    got = d_h[torch.from_numpy(tokens).to("cuda:0")].float().cpu().numpy().astype(np.float64)
+    scale = rms(ref["d_h"])
+    excess = np.abs(got - ref["d_h"]) / (2.0 ** -8 * np.abs(ref["d_h"]) + 2e-4 * scale)
+    excess.reshape(-1, shape.ds)[mism] = 0.0
+    # db2[e] = sum of dL/dh' over the slices routed to e (fp64 sum of the bf16 data; every assignment is kept)
+    g = dout.reshape(-1, shape.ds).astype(np.float64)
+    want_b2 = np.zeros((shape.E, shape.ds))
+    for j in range(shape.k):
+        for e in range(shape.E):
+            want_b2[e] += g[idx[:, j] == e].sum(axis=0)
+    got_b2 = grads["b2"].cpu().numpy().astype(np.float64)
+    err_b2 = np.abs(got_b2 - want_b2).max() / rms(want_b2)
+    finite = all(bool(torch.isfinite(t).all()) for t in grads.values())
+    print(f"\n[backward large, full size] sampled tokens={tokens.size} near-tie slices={n_tie} d_h worst element at "
+          f"{excess.max():.2f} of its bound; b2 max|err|/rms={err_b2:.1e}")
+    assert excess.max() <= 1.0
+    assert n_tie <= 2
+    assert err_b2 <= TOL_WGRAD
+    assert finite
+
+
 def test_backward_is_reproducible_bit_for_bit(B):
     """Partial weight gradients are summed in a fixed order: two calls give identical bits."""
     import torch
