@@ -123,3 +123,43 @@ def test_probe_clock_argument_checks(B):
     dummy = ctypes.c_void_p(256)   # never dereferenced: the size checks come first
     assert L.slicemoe_probe_clock(dummy, 0, 100, None) == B.SLICEMOE_ERR_INVALID_ARG
     assert L.slicemoe_probe_clock(dummy, 4, 0, None) == B.SLICEMOE_ERR_INVALID_ARG
+
+
+C_CALLER = r"""
+#include <stdio.h>
+#include "slicemoe.h"
+int main(void)
+{
+    slicemoe_config c;
+    c.T = 16384; c.d = 1024; c.S = 16; c.k = 2; c.E = 32; c.Hr = 256; c.He = 256;
+    c.capacity_factor = 0.0f; c.dtype = SLICEMOE_BF16; c.flags = 0;
+    printf("%zu %zu %s\n", slicemoe_workspace_bytes(&c), slicemoe_backward_workspace_bytes(&c),
+           slicemoe_status_string(SLICEMOE_ERR_WORKSPACE));
+    c.S = 3;   /* d %% S != 0 */
+    printf("%zu %d\n", slicemoe_workspace_bytes(&c), (int)slicemoe_route(&c, 0, 0, 0, 0, 0, 0, 0));
+    return 0;
+}
+"""
+
+
+def test_header_is_plain_c_and_the_library_links_from_c(B, tmp_path):
+    """The boundary is a C ABI: the header compiles as pedantic C99 without any HIP include, and a C program linked
+    against the shared library gets the same sizes as the Python binding (size queries and argument checks only)."""
+    import subprocess
+    from paper_2510_04286_amd import workload as wl
+    src = tmp_path / "caller.c"
+    src.write_text(C_CALLER.replace("%%", "%"))
+    exe = tmp_path / "caller"
+    libdir = os.path.dirname(B.LIB_PATH)
+    libname = os.path.basename(B.LIB_PATH)
+    assert libname.startswith("lib") and libname.endswith(".so")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe), "-L", libdir, "-l" + libname[3:-3], "-Wl,-rpath," + libdir,
+                    "-Wl,-rpath,/opt/rocm/lib", "-Wl,--allow-shlib-undefined"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    cfg = B.config_of(wl.CONFIGS["headline"])
+    first = out[0].split(" ", 2)
+    assert int(first[0]) == B.slicemoe_workspace_bytes(cfg)
+    assert int(first[1]) == B.slicemoe_backward_workspace_bytes(cfg)
+    assert first[2] == B.lib().slicemoe_status_string(B.SLICEMOE_ERR_WORKSPACE).decode()
+    assert out[1].split() == ["0", str(B.SLICEMOE_ERR_INVALID_ARG)]
