@@ -114,7 +114,9 @@ __device__ __forceinline__ void load_bias_tile(const uint4 *__restrict__ b1s, in
     bias[4] = as_h2(b1.x); bias[5] = as_h2(b1.y); bias[6] = as_h2(b1.z); bias[7] = as_h2(b1.w);
 }
 
-template <int DS, int NSUB>
+// AHEAD: the weight fragment of the next K-step is requested from LDS before this step's matrix instructions, so
+// that they do not each wait for an LDS round trip (for kernels with few wavefronts per SIMD to cover it).
+template <int DS, int NSUB, bool AHEAD = false>
 __device__ __forceinline__ void gemm1_tile(const RowUnit<DS, NSUB> &u, const uint4 *__restrict__ w1s, int hl, int lane,
                                            f32x16 (&acc)[NSUB])
 {
@@ -123,28 +125,51 @@ __device__ __forceinline__ void gemm1_tile(const RowUnit<DS, NSUB> &u, const uin
     for (int sub = 0; sub < NSUB; ++sub)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[sub][r] = 0.f;
+    if constexpr (AHEAD) {
+        uint4 nxt = w1s[(hl * KS) * 64 + lane];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8 a1 = __builtin_bit_cast(bf16x8, w1s[(hl * KS + ks) * 64 + lane]);
+        for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 a1 = __builtin_bit_cast(bf16x8, nxt);
+            if (ks + 1 < KS) nxt = w1s[(hl * KS + ks + 1) * 64 + lane];
 #pragma unroll
-        for (int sub = 0; sub < NSUB; ++sub) acc[sub] = mfma_bf16(a1, u.xb[sub][ks], acc[sub]);
+            for (int sub = 0; sub < NSUB; ++sub) acc[sub] = mfma_bf16(a1, u.xb[sub][ks], acc[sub]);
+        }
+    } else {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 a1 = __builtin_bit_cast(bf16x8, w1s[(hl * KS + ks) * 64 + lane]);
+#pragma unroll
+            for (int sub = 0; sub < NSUB; ++sub) acc[sub] = mfma_bf16(a1, u.xb[sub][ks], acc[sub]);
+        }
     }
 }
 
-template <int DS, int NSUB>
+template <int DS, int NSUB, bool AHEAD = false>
 __device__ __forceinline__ void gemm2_tile(const uint4 (&hb)[NSUB][2], const uint4 *__restrict__ w2s, int hl, int lane,
                                            f32x16 (&yacc)[NSUB][SliceTiles<DS>::OT])
 {
     constexpr int OT = SliceTiles<DS>::OT;
+    if constexpr (AHEAD) {
+        uint4 nxt = w2s[(hl * 2 * OT) * 64 + lane];
 #pragma unroll
-    for (int s = 0; s < 2; ++s)
-#pragma unroll
-        for (int ot = 0; ot < OT; ++ot) {
-            const f16x8 a2 = __builtin_bit_cast(f16x8, w2s[((hl * 2 + s) * OT + ot) * 64 + lane]);
+        for (int i = 0; i < 2 * OT; ++i) {   // i = s * OT + ot
+            const f16x8 a2 = __builtin_bit_cast(f16x8, nxt);
+            if (i + 1 < 2 * OT) nxt = w2s[(hl * 2 * OT + i + 1) * 64 + lane];
 #pragma unroll
             for (int sub = 0; sub < NSUB; ++sub)
-                yacc[sub][ot] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a2, __builtin_bit_cast(f16x8, hb[sub][s]), yacc[sub][ot], 0, 0, 0);
+                yacc[sub][i % OT] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a2, __builtin_bit_cast(f16x8, hb[sub][i / OT]), yacc[sub][i % OT], 0, 0, 0);
         }
+    } else {
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int ot = 0; ot < OT; ++ot) {
+                const f16x8 a2 = __builtin_bit_cast(f16x8, w2s[((hl * 2 + s) * OT + ot) * 64 + lane]);
+#pragma unroll
+                for (int sub = 0; sub < NSUB; ++sub)
+                    yacc[sub][ot] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a2, __builtin_bit_cast(f16x8, hb[sub][s]), yacc[sub][ot], 0, 0, 0);
+            }
+    }
 }
 
 __device__ __forceinline__ uint32_t pack_half2(float a, float b)
@@ -410,13 +435,13 @@ __global__ __launch_bounds__(THREADS) void ffn_streamed_kernel(
             __syncthreads();
             for (int hl = 0; hl < hc; ++hl) {
                 f32x16 acc[NSUB];
-                gemm1_tile<DS, NSUB>(cur, w1s, hl, lane, acc);
+                gemm1_tile<DS, NSUB, true>(cur, w1s, hl, lane, acc);
                 h2 bias[8];
                 load_bias_tile(b1s, ch * hc + hl, g, bias);
                 uint4 hb[NSUB][2];
 #pragma unroll
                 for (int sub = 0; sub < NSUB; ++sub) activation_tile(acc[sub], cur.p2[sub], bias, K, hb[sub]);
-                gemm2_tile<DS, NSUB>(hb, w2s, hl, lane, yacc);
+                gemm2_tile<DS, NSUB, true>(hb, w2s, hl, lane, yacc);
             }
         }
         cur_e = e;
