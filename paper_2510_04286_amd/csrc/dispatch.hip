@@ -4,10 +4,10 @@
 //
 // Three kernels over chunks of kDispChunk consecutive assignment ids a = n*k + j:
 //   1. histogram   block_counts[b][e] = # assignments of chunk b bound for expert e
-//   2. scan        per expert, exclusive prefix over chunks (in place) -> rank of a chunk's first
-//                  assignment inside its expert; totals -> counts_raw, counts, offsets
-//   3. scatter     stable rank of every assignment inside its chunk, final row, perm / inv;
-//                  one extra block computes the load statistics from the counts
+//   2. scan        per expert (one wavefront each), exclusive prefix over chunks (in place) -> rank of a
+//                  chunk's first assignment inside its expert; totals -> counts_raw, counts
+//   3. scatter     offsets from the counts, stable rank of every assignment inside its chunk, final
+//                  row, perm / inv; one extra block computes the load statistics from the counts
 // When the table of step 1 is small (the headline has 512 chunks x 32 experts) step 2 is folded into
 // step 3: every scatter block sums the table itself, which is cheaper than a latency-bound launch.
 // Stability needs ranks in ascending a.  A block walks its chunk in rounds of 256 consecutive
@@ -87,15 +87,6 @@ __device__ __forceinline__ void load_stats_wave(int raw, int kept_e, bool have, 
     }
 }
 
-// One block of 1024 threads walks the [nblocks][E] table in tiles of kScanTile entries staged in
-// LDS (coalesced 16-byte loads and stores; the table is tiny, the kernel is latency-bound, so every
-// global access is issued in one batch and every scan is a wavefront shuffle scan).  Inside a tile,
-// thread (seg, e) with e = tid % Epow2 owns a contiguous run of chunks of expert e and sums it; the
-// nseg <= 64 segment sums of an expert are then re-read segment-fastest, so that they sit in
-// consecutive lanes, and scanned with shuffles on top of the running total carried from the previous
-// tiles; finally each thread rewrites its run as exclusive prefixes.
-constexpr int kScanTileMax = 32768;   // table entries per tile at most: 128 KiB of LDS (the headline table is 16384)
-
 __device__ __forceinline__ int group_inclusive_scan(int v, int pos, int width)
 {
     for (int o = 1; o < width; o <<= 1) {
@@ -105,92 +96,45 @@ __device__ __forceinline__ int group_inclusive_scan(int v, int pos, int width)
     return v;
 }
 
-__global__ __launch_bounds__(1024) void dispatch_scan_kernel(
-    int32_t *__restrict__ block_counts, int nblocks, int E, int Epow2, long long capacity,
-    int32_t *__restrict__ counts_raw, int32_t *__restrict__ counts, int32_t *__restrict__ offsets, int tile_entries)
+// The columns of the [nblocks][E] table are independent: one block per expert, so that the experts spread over the
+// CUs (a lane's loads are a whole table row apart; what bounds the kernel is the rate of such scattered requests of
+// one CU and their latency: 67 us for Large's 4096 x 64 table with eight experts per block, 33 us with one wavefront
+// per expert).  Thread `seg` owns a contiguous run of chunks of the expert: it sums the run, the run sums are scanned
+// (shuffles inside a wavefront, a small LDS table across), and the thread rewrites its run as exclusive prefixes.
+// The expert's total goes to counts_raw and, capped, to counts; the scatter kernel turns the counts into offsets.
+constexpr int kScanWaves = 16, kScanSegs = kScanWaves * 64;
+__global__ __launch_bounds__(kScanSegs) void dispatch_scan_kernel(
+    int32_t *__restrict__ table, int nblocks, int E, long long capacity, int32_t *__restrict__ counts_raw,
+    int32_t *__restrict__ counts)
 {
-    extern __shared__ __align__(16) int tile[];   // [tile_entries]
-    __shared__ int seg_sum[1024];
-    __shared__ int carry[64];
-    const int tid = threadIdx.x;
-    const int nseg = min(64, 1024 / Epow2);       // power of two: a segment group never straddles a wavefront
-    // tile passes: expert fastest (consecutive lanes touch consecutive LDS words)
-    const int e = tid % Epow2;
-    const int seg = tid / Epow2;
-    const bool active = e < E && seg < nseg;
-    // scan of the segment sums: segment fastest (an expert's sums sit in consecutive lanes)
-    const int e2 = tid / nseg;
-    const int seg2 = tid % nseg;
-    const bool active2 = e2 < E;
-    const int chunks_per_tile = tile_entries / E;    // whole chunks only
-    if (tid < 64) carry[tid] = 0;
-
-    for (int c0 = 0; c0 < nblocks; c0 += chunks_per_tile) {
-        const int nc = min(chunks_per_tile, nblocks - c0);
-        const long long first = (long long)c0 * E;            // entry index of the tile start
-        const int n_entries = nc * E;
-        const bool vec = ((first & 3) == 0);                  // 16-byte pieces need an aligned tile start
-        __syncthreads();   // previous tile fully written back, carry visible
-        if (vec) {
-            for (int i = tid * 4; i < n_entries; i += 1024 * 4) {
-                if (i + 4 <= n_entries) *(int4 *)(tile + i) = *(const int4 *)(block_counts + first + i);
-                else for (int q = i; q < n_entries; ++q) tile[q] = block_counts[first + q];
-            }
-        } else {
-            for (int i = tid; i < n_entries; i += 1024) tile[i] = block_counts[first + i];
-        }
-        __syncthreads();
-        const int per = (nc + nseg - 1) / nseg;
-        const int b0 = seg * per;
-        const int b1 = min(nc, b0 + per);
-        int s = 0;
-        if (active)
-            for (int b = b0; b < b1; ++b) s += tile[b * E + e];
-        if (active) seg_sum[seg * Epow2 + e] = s;
-        __syncthreads();
-        {
-            const int v = active2 ? seg_sum[seg2 * Epow2 + e2] : 0;
-            const int incl = group_inclusive_scan(v, seg2, nseg);
-            const int base = active2 ? carry[e2] : 0;
-            __syncthreads();                                   // everyone has read seg_sum and carry
-            if (active2) seg_sum[seg2 * Epow2 + e2] = base + incl - v;   // exclusive prefix of the segment
-            if (active2 && seg2 == nseg - 1) carry[e2] = base + incl;
-        }
-        __syncthreads();
-        if (active) {
-            int run = seg_sum[seg * Epow2 + e];
-            for (int b = b0; b < b1; ++b) {
-                const int t = tile[b * E + e];
-                tile[b * E + e] = run;
-                run += t;
-            }
-        }
-        __syncthreads();
-        if (vec) {
-            for (int i = tid * 4; i < n_entries; i += 1024 * 4) {
-                if (i + 4 <= n_entries) *(int4 *)(block_counts + first + i) = *(const int4 *)(tile + i);
-                else for (int q = i; q < n_entries; ++q) block_counts[first + q] = tile[q];
-            }
-        } else {
-            for (int i = tid; i < n_entries; i += 1024) block_counts[first + i] = tile[i];
-        }
-    }
+    __shared__ int wave_total[kScanWaves];
+    const int seg = threadIdx.x, lane = seg & 63, wave = seg >> 6;
+    const int e = (int)blockIdx.x;   // < E by the launch
+    const int per = (nblocks + kScanSegs - 1) / kScanSegs;
+    const int b0 = min(nblocks, seg * per), b1 = min(nblocks, b0 + per);
+    int s = 0;
+    for (int b = b0; b < b1; ++b) s += table[(size_t)b * E + e];
+    const int incl = group_inclusive_scan(s, lane, 64);
+    if (lane == 63) wave_total[wave] = incl;
     __syncthreads();
-    if (tid < 64) {   // one wavefront: lane x owns expert x
-        const int raw = tid < E ? carry[tid] : 0;
-        const int c = (capacity >= 0 && raw > capacity) ? (int)capacity : raw;
-        const int incl = group_inclusive_scan(c, tid, 64);
-        if (tid < E) {
-            counts_raw[tid] = raw;
-            counts[tid] = c;
-            offsets[tid] = incl - c;
-        }
-        if (tid == E - 1) offsets[E] = incl;
+    int run = incl - s, total = 0;
+    for (int w = 0; w < kScanWaves; ++w) {
+        if (w < wave) run += wave_total[w];
+        total += wave_total[w];
+    }
+    for (int b = b0; b < b1; ++b) {
+        const int t = table[(size_t)b * E + e];
+        table[(size_t)b * E + e] = run;
+        run += t;
+    }
+    if (seg == 0) {
+        counts_raw[e] = total;
+        counts[e] = (capacity >= 0 && total > capacity) ? (int)capacity : total;
     }
 }
 
-// FUSED = false: `table` holds the exclusive per-expert prefixes written by dispatch_scan_kernel and the
-// per-expert offsets come from `offsets`.
+// FUSED = false: `table` holds the exclusive per-expert prefixes and counts_raw / counts the totals written by
+// dispatch_scan_kernel; every block derives the per-expert offsets from the counts and block 0 writes them out.
 // FUSED = true (small tables, E a power of two >= 4): there is no scan kernel.  `table` holds the raw
 // per-chunk counts; every block sums the whole table (coalesced 16-byte loads, all in flight at once) into
 // the per-expert totals and into the prefix of its own chunk, derives counts and offsets itself, and block 0
@@ -206,7 +150,7 @@ __global__ __launch_bounds__(kDispThreads) void dispatch_scatter_kernel(
     constexpr int kWaves = kDispThreads / 64;
     __shared__ int wcnt[kDispItems][kWaves][64];
     __shared__ int s_pre[64];      // FUSED: rank of this chunk's first assignment inside each expert
-    __shared__ int s_off[65];      // FUSED: per-expert offsets
+    __shared__ int s_off[65];      // per-expert offsets
     const int tid = threadIdx.x;
     const bool stats_block = (int)blockIdx.x == nchunks;   // one extra block: the load statistics, off everyone's critical path
     if constexpr (FUSED) {
@@ -253,10 +197,20 @@ __global__ __launch_bounds__(kDispThreads) void dispatch_scatter_kernel(
         }
         if (stats_block) return;
     } else {
-        if (stats_block) {
-            if (stats && tid < 64) load_stats_wave(tid < E ? counts_raw[tid] : 0, tid < E ? counts[tid] : 0, tid < E, E, stats);
-            return;
+        if (tid < 64) {   // one wavefront: lane x owns expert x
+            const int c = tid < E ? counts[tid] : 0;
+            const int incl = group_inclusive_scan(c, tid, 64);
+            if (tid < E) {
+                s_off[tid] = incl - c;
+                if (blockIdx.x == 0) offsets[tid] = incl - c;
+            }
+            if (tid == E - 1) {
+                s_off[E] = incl;
+                if (blockIdx.x == 0) offsets[E] = incl;
+            }
+            if (stats_block && stats) load_stats_wave(tid < E ? counts_raw[tid] : 0, c, tid < E, E, stats);
         }
+        if (stats_block) return;
     }
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -298,7 +252,7 @@ __global__ __launch_bounds__(kDispThreads) void dispatch_scatter_kernel(
         const int a = base + i * kDispThreads + tid;
         const int rank = wcnt[i][wave][e] + rk[i];
         if (capacity < 0 || rank < capacity) {
-            const int row = (FUSED ? s_off[e] : offsets[e]) + rank;
+            const int row = s_off[e] + rank;
             perm[row] = a;
             inv[a] = row;
         } else {
@@ -325,20 +279,9 @@ hipError_t launch_dispatch(const slicemoe_config &c, const int32_t *idx, int32_t
             idx, (int)Na, c.E, nbits, cap, block_counts, offsets, perm, inv, nblocks, counts_raw, counts, stats);
         return hipGetLastError();
     }
-    {
-        long long want = (long long)nblocks * c.E;
-        int tile_entries = (int)(want < 1024 ? 1024 : (want > kScanTileMax ? kScanTileMax : (want + 3) / 4 * 4));
-        const int lds_cap = (max_lds_per_block() - 8 * 1024) / 4;
-        if (tile_entries > lds_cap) tile_entries = lds_cap / 4 * 4;
-        if (tile_entries < c.E) return hipErrorInvalidValue;
-        hipError_t err = hipFuncSetAttribute((const void *)dispatch_scan_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                             tile_entries * 4);
-        if (err != hipSuccess) return err;
-        dispatch_scan_kernel<<<1, 1024, (size_t)tile_entries * 4, s>>>(block_counts, nblocks, c.E, Epow2, cap, counts_raw,
-                                                                     counts, offsets, tile_entries);
-    }
-    if (nblocks > 0 || stats)
-        dispatch_scatter_kernel<false><<<nblocks + (stats ? 1 : 0), kDispThreads, 0, s>>>(
+    dispatch_scan_kernel<<<c.E, kScanSegs, 0, s>>>(block_counts, nblocks, c.E, cap, counts_raw, counts);
+    // without any assignment the one block launched is the statistics block, which also writes the (zero) offsets
+    dispatch_scatter_kernel<false><<<nblocks + ((stats || nblocks == 0) ? 1 : 0), kDispThreads, 0, s>>>(
             idx, (int)Na, c.E, nbits, cap, block_counts, offsets, perm, inv, nblocks, counts_raw, counts, stats);
     return hipGetLastError();
 }
