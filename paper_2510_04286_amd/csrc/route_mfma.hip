@@ -233,7 +233,6 @@ static hipError_t run_route(const slicemoe_config &c, const void *h, const void 
     constexpr int KS = SliceTiles<DS>::KS;
     const size_t lds = (size_t)((W1_LDS ? kRouteHT * KS * 64 : 0) + ET * kRouteHT * 2 * 64) * 16 + (kRouteHr + ET * 32) * 4;
     const long long ntiles = (Ns + 31) / 32;
-    constexpr int kRouteWaves = THREADS / 64;
     long long blocks = ntiles;   // one tile per block before a second wavefront of any block gets one
     const long long cap = (long long)num_compute_units();
     if (blocks > cap) blocks = cap;
