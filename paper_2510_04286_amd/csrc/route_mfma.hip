@@ -25,8 +25,9 @@ constexpr int kRouteHT = kRouteHr / 32;
 typedef _Float16 h2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
-// One block per CU shares one LDS copy of the router: THREADS = 1024 (16 wavefronts, <= 128 VGPRs)
-// for the small shapes, 512 where the accumulators of two expert tiles or K = 128 need more registers.
+// One block per CU shares one LDS copy of the router, with as many wavefronts as the registers allow (more wavefronts
+// per SIMD hide more of the LDS and matrix-instruction latencies): THREADS = 1024 (16 wavefronts, <= 128 VGPRs) for
+// the small shapes, 768 (<= 168) where two expert tiles or a wide slice need more, 512 where that would spill.
 // W1_LDS = false (slice width 384, whose first layer of 192 KiB exceeds the LDS): the first-layer fragments are read
 // from memory as they are used; only the second layer and the biases are staged.
 template <int DS, int ET, int THREADS, bool W1_LDS>
@@ -258,12 +259,12 @@ hipError_t launch_route_mfma(const slicemoe_config &c, const void *h, const void
     if (ds == 64)
         return et == 1 ? run_route<64, 1, 1024>(c, h, packed, idx, p, s, v) : run_route<64, 2, 512>(c, h, packed, idx, p, s, v);
     if (ds == 96)   // the slice width of the paper's own configuration (d = 768, S = 8): six K-steps
-        return et == 1 ? run_route<96, 1, 512>(c, h, packed, idx, p, s, v) : run_route<96, 2, 512>(c, h, packed, idx, p, s, v);
+        return et == 1 ? run_route<96, 1, 1024>(c, h, packed, idx, p, s, v) : run_route<96, 2, 768>(c, h, packed, idx, p, s, v);
     if (ds == 192)
-        return et == 1 ? run_route<192, 1, 512>(c, h, packed, idx, p, s, v) : run_route<192, 2, 512>(c, h, packed, idx, p, s, v);
+        return et == 1 ? run_route<192, 1, 768>(c, h, packed, idx, p, s, v) : run_route<192, 2, 512>(c, h, packed, idx, p, s, v);
     if (ds == 384)
         return et == 1 ? run_route<384, 1, 256, false>(c, h, packed, idx, p, s, v) : run_route<384, 2, 256, false>(c, h, packed, idx, p, s, v);
-    return et == 1 ? run_route<128, 1, 512>(c, h, packed, idx, p, s, v) : run_route<128, 2, 512>(c, h, packed, idx, p, s, v);
+    return et == 1 ? run_route<128, 1, 768>(c, h, packed, idx, p, s, v) : run_route<128, 2, 768>(c, h, packed, idx, p, s, v);
 }
 
 }  // namespace slicemoe
