@@ -261,15 +261,22 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_expert_kernel(
 // Sum of the chunk slots of each expert in a fixed order: grid (E, pieces of 64 slot elements); a block is 64 elements
 // x 8 interleaved sequences of chunks, whose eight partial sums are added in order at the end.
 constexpr int kRedElems = 64, kRedSeqs = 8;
+template <int V> struct RedVec;
+template <> struct RedVec<1> { typedef float type; };
+typedef float red_f32x4 __attribute__((ext_vector_type(4)));
+template <> struct RedVec<4> { typedef red_f32x4 type; };
+// V = 4: four consecutive entries per thread (16-byte loads and stores) where the tensors' sizes and addresses allow.
+template <int V>
 __global__ __launch_bounds__(kRedElems * kRedSeqs) void bwd_reduce_expert_kernel(
     const float *__restrict__ part, const int32_t *__restrict__ offsets, int ds, int He, int E, int rows_per_chunk,
     float *__restrict__ dW1, float *__restrict__ db1, float *__restrict__ dW2, float *__restrict__ db2)
 {
-    __shared__ float red[kRedSeqs][kRedElems];
+    typedef typename RedVec<V>::type vec;
+    __shared__ vec red[kRedSeqs][kRedElems];
     const int e = blockIdx.x;
     const int ex = threadIdx.x % kRedElems, sq = threadIdx.x / kRedElems;
     const size_t slot = expert_slot_floats(ds, He);
-    const size_t t = (size_t)blockIdx.y * kRedElems + ex;
+    const size_t t = ((size_t)blockIdx.y * kRedElems + ex) * V;
     // chunks are numbered expert by expert, as the expert kernels find them (E <= 64: one thread per expert)
     __shared__ int nchs[64];
     if (threadIdx.x < 64)
@@ -278,22 +285,22 @@ __global__ __launch_bounds__(kRedElems * kRedSeqs) void bwd_reduce_expert_kernel
     int first = 0;
     for (int q = 0; q < e; ++q) first += nchs[q];
     const int nch = nchs[e];
-    float acc = 0.f;
+    vec acc = {};
     if (t < slot) {
 #pragma unroll 4
-        for (int c = sq; c < nch; c += kRedSeqs) acc += part[(size_t)(first + c) * slot + t];
+        for (int c = sq; c < nch; c += kRedSeqs) acc += *(const vec *)(part + (size_t)(first + c) * slot + t);
     }
     red[sq][ex] = acc;
     __syncthreads();
     if (sq != 0 || t >= slot) return;
-    acc = 0.f;
+    acc = vec{};
 #pragma unroll
     for (int q = 0; q < kRedSeqs; ++q) acc += red[q][ex];   // fixed order
     const size_t nW = (size_t)ds * He;
-    if (t < nW) dW1[(size_t)e * nW + t] = acc;
-    else if (t < 2 * nW) dW2[(size_t)e * nW + (t - nW)] = acc;
-    else if (t < 2 * nW + He) db1[(size_t)e * He + (t - 2 * nW)] = acc;
-    else db2[(size_t)e * ds + (t - 2 * nW - He)] = acc;
+    if (t < nW) *(vec *)(dW1 + (size_t)e * nW + t) = acc;
+    else if (t < 2 * nW) *(vec *)(dW2 + (size_t)e * nW + (t - nW)) = acc;
+    else if (t < 2 * nW + He) *(vec *)(db1 + (size_t)e * He + (t - 2 * nW)) = acc;
+    else *(vec *)(db2 + (size_t)e * ds + (t - 2 * nW - He)) = acc;
 }
 
 // Router backward and the assembly of dL/dh.  Hr <= kBwdThreads (one thread per router hidden unit), E <= 64.
@@ -619,8 +626,14 @@ static hipError_t run_backward(const slicemoe_config &c, const void *h, const sl
     }
     if ((e = hipGetLastError()) != hipSuccess) return e;
     }
-    bwd_reduce_expert_kernel<<<dim3((unsigned)c.E, (unsigned)((eslot + kRedElems - 1) / kRedElems)), kRedElems * kRedSeqs, 0, s>>>(
-        epart, offsets, ds, c.He, c.E, P.rows_per_chunk, g.W1, g.b1, g.W2, g.b2);
+    const bool vec4 = ds % 4 == 0 && c.He % 4 == 0 &&
+                      (((uintptr_t)g.W1 | (uintptr_t)g.b1 | (uintptr_t)g.W2 | (uintptr_t)g.b2 | (uintptr_t)epart) & 15) == 0;
+    if (vec4)
+        bwd_reduce_expert_kernel<4><<<dim3((unsigned)c.E, (unsigned)((eslot / 4 + kRedElems - 1) / kRedElems)), kRedElems * kRedSeqs, 0, s>>>(
+            epart, offsets, ds, c.He, c.E, P.rows_per_chunk, g.W1, g.b1, g.W2, g.b2);
+    else
+        bwd_reduce_expert_kernel<1><<<dim3((unsigned)c.E, (unsigned)((eslot + kRedElems - 1) / kRedElems)), kRedElems * kRedSeqs, 0, s>>>(
+            epart, offsets, ds, c.He, c.E, P.rows_per_chunk, g.W1, g.b1, g.W2, g.b2);
     if ((e = hipGetLastError()) != hipSuccess) return e;
 
     const size_t rslot = router_slot_floats(ds, c.Hr, c.E);
