@@ -10,7 +10,7 @@
 //                      hidden unit: recomputes u = x W1 and z, forms dz = (dy W2^T) gelu'(z), accumulates its
 //                      column of dW1 and its row of dW2 in registers (stores them once, at the end),
 //                      reduces dL/dp over the hidden units and writes the row's dL/dx.
-//   bwd_router_kernel  a block walks up to kBwdSlices slices in batches of kRB, one thread per router hidden unit:
+//   bwd_router_kernel  a block walks up to slices_per_block slices in batches of kRB, one thread per router hidden unit:
 //                      recomputes the router, goes back through the dropout's renormalisation and the softmax to
 //                      dL/dg, accumulates the router's weight gradients the same way, and writes dL/dh = router path
 //                      + the k expert-path rows of the slice (the gather that mirrors the combine).
@@ -26,7 +26,7 @@ namespace slicemoe {
 
 constexpr int kBwdThreads = 256;
 constexpr int kBwdRB = 8;         // rows (slices) per batch
-constexpr int kBwdSlices = 512;   // slices per block of the router kernel
+constexpr int kBwdSlices = 512;   // slices per block of the router kernel at least (about a thousand blocks for large batches)
 constexpr int kBwdCols = 64;      // slice features per grid chunk (register accumulators per thread)
 
 __host__ __device__ __forceinline__ size_t expert_slot_floats(int ds, int He) { return 2 * (size_t)ds * He + He + ds; }
@@ -311,7 +311,7 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_router_kernel(
     const T *__restrict__ Wr1, const T *__restrict__ br1, const T *__restrict__ Wr2, const T *__restrict__ br2,
     const float *__restrict__ noise, float sigma, float inv_tau, const float *__restrict__ drop_u, float rate,
     const int32_t *__restrict__ idx, const int32_t *__restrict__ inv, const float *__restrict__ dpk,
-    const float *__restrict__ dxrow, T *__restrict__ dh, float *__restrict__ part)
+    const float *__restrict__ dxrow, T *__restrict__ dh, int slices_per_block, float *__restrict__ part)
 {
     extern __shared__ float smem[];
     float *xs = smem;                      // [kBwdRB][ds]
@@ -327,8 +327,8 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_router_kernel(
     const int c0 = (int)blockIdx.y * kBwdCols;
     const int ncols = min(kBwdCols, ds - c0);
     const bool first_chunk = blockIdx.y == 0;
-    const long long n_begin = (long long)blockIdx.x * kBwdSlices;
-    const long long n_end = min(Ns, n_begin + kBwdSlices);
+    const long long n_begin = (long long)blockIdx.x * slices_per_block;
+    const long long n_end = min(Ns, n_begin + slices_per_block);
     const bool hok = tid < Hr;
 
     float aWr1[kBwdCols], aWr2[64];
@@ -559,7 +559,9 @@ BackwardPlan backward_plan(const slicemoe_config &c)
     rows = (rows + 31) / 32 * 32;   // whole 32-row units of the matrix-core kernels (and whole batches of kBwdRB)
     p.rows_per_chunk = (int)(rows < 512 ? 512 : rows);
     p.chunks = (long long)((Na + p.rows_per_chunk - 1) / p.rows_per_chunk) + c.E;   // worst case: every expert ends on a partial chunk
-    p.slice_blocks = (long long)((Ns + kBwdSlices - 1) / kBwdSlices);
+    size_t spb = ((Ns + 1023) / 1024 + 31) / 32 * 32;
+    p.slices_per_block = (int)(spb < (size_t)kBwdSlices ? (size_t)kBwdSlices : spb);
+    p.slice_blocks = (long long)((Ns + p.slices_per_block - 1) / p.slices_per_block);
     size_t at = 0;
     p.dxrow = at;  at = align_up(at + Na * ds * sizeof(float), 256);
     p.dpk = at;    at = align_up(at + Na * sizeof(float), 256);
@@ -639,7 +641,7 @@ static hipError_t run_backward(const slicemoe_config &c, const void *h, const sl
     const size_t rslot = router_slot_floats(ds, c.Hr, c.E);
     if (backward_router_mfma_shape(c)) {
         e = launch_backward_router_mfma(c, h, w, v, drop_u, rate, idx, inv, dpk, dxrow, d_h, ws + P.router_scratch,
-                                        P.slice_blocks, rslot, rpart, s);
+                                        P.slices_per_block, P.slice_blocks, rslot, rpart, s);
         if (e != hipSuccess) return e;
     } else {
     const size_t lds_r = sizeof(float) * kBwdRB * ((size_t)ds + 2 * (size_t)c.Hr + 2 * (size_t)c.E);
@@ -652,11 +654,11 @@ static hipError_t run_backward(const slicemoe_config &c, const void *h, const sl
             return e;
         kern<<<rgrid, kBwdThreads, lds_rw, s>>>((const T *)h, Ns, ds, c.Hr, c.E, c.k, (const T *)w.Wr1, (const T *)w.br1,
                                                  (const T *)w.Wr2, (const T *)w.br2, nz, v.sigma, v.inv_tau, du, rate, idx, inv,
-                                                 dpk, dxrow, (T *)d_h, rpart);
+                                                 dpk, dxrow, (T *)d_h, P.slices_per_block, rpart);
     } else {
         bwd_router_kernel<T, false><<<rgrid, kBwdThreads, lds_r, s>>>(
             (const T *)h, Ns, ds, c.Hr, c.E, c.k, (const T *)w.Wr1, (const T *)w.br1, (const T *)w.Wr2, (const T *)w.br2,
-            nz, v.sigma, v.inv_tau, du, rate, idx, inv, dpk, dxrow, (T *)d_h, rpart);
+            nz, v.sigma, v.inv_tau, du, rate, idx, inv, dpk, dxrow, (T *)d_h, P.slices_per_block, rpart);
     }
     if ((e = hipGetLastError()) != hipSuccess) return e;
     }

@@ -27,7 +27,6 @@ constexpr int kRbHr = 256, kRbHT = 8;
 constexpr int kRbThreads = 512;                 // slice kernels: 8 wavefronts
 constexpr int kRbWaves = kRbThreads / 64;
 constexpr int kRbWgWaves = 4;                   // weights kernel: one wavefront per hidden tile, two groups of four
-constexpr int kRbSliceBlock = 512;              // slices per slot of the weights kernel (= kBwdSlices of backward.hip)
 
 // Repacked router (bytes from the start of the buffer); KS = ds / 16, OT = ds / 32, ET = expert tiles of 32 (experts
 // past E are zero).
@@ -373,12 +372,13 @@ __global__ __launch_bounds__(kRbThreads) void bwd_route_inputs_mfma_kernel(
 }
 
 // ----------------------------------------------------------------------------------------------- weights kernel
-// grid.x = range of kRbSliceBlock slices (its slot of partial sums), grid.y = group of four hidden tiles, block = one
+// grid.x = range of slices_per_block slices (its slot of partial sums), grid.y = group of four hidden tiles, block = one
 // wavefront per hidden tile of the group.
 template <int DS, int ET>
 __global__ __launch_bounds__(kRbWgWaves * 64, (DS <= 64 && ET == 1) ? 2 : 1) void bwd_route_weights_mfma_kernel(
     const bf16_t *__restrict__ x, long long Ns, int E, const char *__restrict__ packed, RouterBwdPacked L,
-    const bf16_t *__restrict__ dg_hi, const bf16_t *__restrict__ dg_lo, size_t slot_floats, float *__restrict__ part)
+    const bf16_t *__restrict__ dg_hi, const bf16_t *__restrict__ dg_lo, int slices_per_block, size_t slot_floats,
+    float *__restrict__ part)
 {
     constexpr int KS = DS / 16, OT = DS / 32, EP = ET * 32, GS = 2 * ET;   // GS: K-steps of 16 experts
     extern __shared__ __align__(16) char lds[];
@@ -410,8 +410,8 @@ __global__ __launch_bounds__(kRbWgWaves * 64, (DS <= 64 && ET == 1) ? 2 : 1) voi
 #pragma unroll
     for (int et = 0; et < ET; ++et) ab2[et] = 0.f;
 
-    const long long n_begin = (long long)blockIdx.x * kRbSliceBlock;
-    const long long n_end = min(Ns, n_begin + kRbSliceBlock);
+    const long long n_begin = (long long)blockIdx.x * slices_per_block;
+    const long long n_end = min(Ns, n_begin + slices_per_block);
     for (long long n0 = n_begin; n0 < n_end; n0 += 32) {
         const long long n = n0 + jj;   // as A operand a lane holds slice jj of the unit, contraction slots 8g..8g+7
         const bool valid = n < n_end;
@@ -553,7 +553,7 @@ template <int DS, int ET>
 static hipError_t run_router_mfma(const slicemoe_config &c, const RouterBwdPacked &L, const void *h, const RouteVariant &v,
                                   const float *drop_u, float rate, const int32_t *idx, const int32_t *inv, const float *dpk,
                                   const float *dxrow, void *d_h, const char *pb, bf16_t *dg_hi, bf16_t *dg_lo, uint32_t *bits,
-                                  long long slice_blocks, size_t slot_floats, float *part, hipStream_t s)
+                                  int slices_per_block, long long slice_blocks, size_t slot_floats, float *part, hipStream_t s)
 {
     const long long Ns = (long long)c.T * c.S;
     const long long ntiles = (Ns + 31) / 32, units = (ntiles + kRbWaves - 1) / kRbWaves;
@@ -582,19 +582,22 @@ static hipError_t run_router_mfma(const slicemoe_config &c, const RouterBwdPacke
     auto wk = bwd_route_weights_mfma_kernel<DS, ET>;
     if ((e = hipFuncSetAttribute((const void *)wk, hipFuncAttributeMaxDynamicSharedMemorySize, (int)weights_lds(DS, ET))) != hipSuccess) return e;
     wk<<<dim3((unsigned)slice_blocks, kRbHT / kRbWgWaves), kRbWgWaves * 64, weights_lds(DS, ET), s>>>(
-        (const bf16_t *)h, Ns, c.E, pb, L, dg_hi, dg_lo, slot_floats, part);
+        (const bf16_t *)h, Ns, c.E, pb, L, dg_hi, dg_lo, slices_per_block, slot_floats, part);
     return hipGetLastError();
 }
 
-// scratch: backward_router_mfma_scratch_bytes; part: ceil(Ns / 512) slots of slot_floats floats (the slice ranges of
-// the vector-ALU router kernel).  dxrow, dpk: the expert stage's row gradients and dL/dp.
+// scratch: backward_router_mfma_scratch_bytes; part: slice_blocks = ceil(Ns / slices_per_block) slots of slot_floats
+// floats (the slice ranges of the vector-ALU router kernel; slices_per_block a multiple of 32).  dxrow, dpk: the expert stage's row gradients and dL/dp.
 hipError_t launch_backward_router_mfma(const slicemoe_config &c, const void *h, const slicemoe_weights &w,
                                        const RouteVariant &v, const float *drop_u, float rate, const int32_t *idx,
                                        const int32_t *inv, const float *dpk, const float *dxrow, void *d_h, void *scratch,
-                                       long long slice_blocks, size_t slot_floats, float *part, hipStream_t s)
+                                       int slices_per_block, long long slice_blocks, size_t slot_floats, float *part,
+                                       hipStream_t s)
 {
     const long long Ns = (long long)c.T * c.S;
-    if (!backward_router_mfma_shape(c) || slice_blocks != (Ns + kRbSliceBlock - 1) / kRbSliceBlock) return hipErrorInvalidValue;
+    if (!backward_router_mfma_shape(c) || slices_per_block < 32 || slices_per_block % 32 != 0 ||
+        slice_blocks != (Ns + slices_per_block - 1) / slices_per_block)
+        return hipErrorInvalidValue;
     const int E = c.E, Hr = kRbHr, ds = c.d / c.S, ET = (E + 31) / 32, EP = 32 * ET;
     const RouterBwdPacked L = router_bwd_layout(ds, ET);
     const RouterBwdScratch R = router_bwd_scratch(c);
@@ -618,7 +621,7 @@ hipError_t launch_backward_router_mfma(const slicemoe_config &c, const void *h, 
     if (e != hipSuccess) return e;
 #define SLICEMOE_ROUTER_BWD(DSV, ETV)                                                                                            \
     if (ds == DSV && ET == ETV)                                                                                                  \
-        return run_router_mfma<DSV, ETV>(c, L, h, v, drop_u, rate, idx, inv, dpk, dxrow, d_h, pb, dg_hi, dg_lo, bits, slice_blocks, \
+        return run_router_mfma<DSV, ETV>(c, L, h, v, drop_u, rate, idx, inv, dpk, dxrow, d_h, pb, dg_hi, dg_lo, bits, slices_per_block, slice_blocks, \
                                          slot_floats, part, s);
     SLICEMOE_ROUTER_BWD(64, 1)
     SLICEMOE_ROUTER_BWD(64, 2)

@@ -102,6 +102,7 @@ hipError_t launch_route_mfma(const slicemoe_config &c, const void *h, const void
 struct BackwardPlan {
     int rows_per_chunk;            // stacked rows per block of the expert kernel
     long long chunks;              // its grid.x (an upper bound on the chunks in use)
+    int slices_per_block;          // slices per block of the router kernel (its slot of partial weight gradients)
     long long slice_blocks;        // grid.x of the router kernel
     size_t dxrow, dpk, expert_part, router_part, packed, router_scratch, total;   // byte offsets into the workspace, total size
 };
@@ -112,13 +113,14 @@ bool backward_mfma_shape(const slicemoe_config &c);
 size_t backward_mfma_packed_bytes(const slicemoe_config &c);
 // Matrix-core router backward (backward_router_mfma.hip): shapes it takes, bytes of its scratch (repacked router and
 // the dL/dg tables), and the launch (same outputs as the vector-ALU router kernel: dL/dh and one slot of partial
-// weight gradients per range of 512 slices).
+// weight gradients per range of slices_per_block slices).
 bool backward_router_mfma_shape(const slicemoe_config &c);
 size_t backward_router_mfma_scratch_bytes(const slicemoe_config &c);
 hipError_t launch_backward_router_mfma(const slicemoe_config &c, const void *h, const slicemoe_weights &w,
                                        const RouteVariant &v, const float *drop_u, float rate, const int32_t *idx,
                                        const int32_t *inv, const float *dpk, const float *dxrow, void *d_h, void *scratch,
-                                       long long slice_blocks, size_t slot_floats, float *part, hipStream_t s);
+                                       int slices_per_block, long long slice_blocks, size_t slot_floats, float *part,
+                                       hipStream_t s);
 hipError_t launch_backward_expert_mfma(const slicemoe_config &c, const void *h, const slicemoe_weights &w, const void *d_out,
                                        const float *pk, const int32_t *offsets, const int32_t *perm, void *packed,
                                        int rows_per_chunk, long long chunks, size_t slot_floats, float *dxrow, float *dpk,
