@@ -393,11 +393,11 @@ __global__ __launch_bounds__(kBmTileWaves * 64) void bwd_rows_streamed_mfma_kern
 }
 
 // --------------------------------------------------------------------------------------------- weights kernel
-// grid.x = chunk (as the vector-ALU expert kernel numbers them), grid.y = group of kBmWgWaves hidden tiles, block = one
-// wavefront per hidden tile of the group; part: the chunk slots.  Slice width DS in {64, 96, 128}, any He % 32 == 0.
+// grid = chunks (as the vector-ALU expert kernel numbers them, rounded up to eight) x groups of kBmWgWaves hidden tiles, block = one
+// wavefront per hidden tile of the group; part: the chunk slots.  Any He % 32 == 0; used at slice width 64.
 constexpr int kBmWgWaves = 4;
 template <int DS>
-__global__ __launch_bounds__(kBmWgWaves * 64, DS <= 64 ? 2 : 1) void bwd_weights_mfma_kernel(   // width 64: two blocks per SIMD set
+__global__ __launch_bounds__(kBmWgWaves * 64, 2) void bwd_weights_mfma_kernel(   // two wavefronts per SIMD
     const bf16_t *__restrict__ x, const bf16_t *__restrict__ dout, const float *__restrict__ pk,
     const int32_t *__restrict__ offsets, const int32_t *__restrict__ perm, const char *__restrict__ packed,
     size_t e_stride, size_t off_w2r, size_t off_b1, int He, int E, int k, int rows_per_chunk, size_t slot_floats,
@@ -414,10 +414,14 @@ __global__ __launch_bounds__(kBmWgWaves * 64, DS <= 64 ? 2 : 1) void bwd_weights
 
     const int tid = threadIdx.x, lane = tid & 63, jj = lane & 31, g = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int ht0 = (int)blockIdx.y * kBmWgWaves;
+    // Consecutive blocks go to the eight XCDs in turn, each with its own L2: the groups of a chunk, which read the
+    // same rows, take block ids that are equal modulo 8.
+    const int groups = (HT + kBmWgWaves - 1) / kBmWgWaves;
+    const int ht0 = ((int)(blockIdx.x / 8) % groups) * kBmWgWaves;
+    const int chunk = (int)(blockIdx.x / (8 * groups)) * 8 + (int)(blockIdx.x % 8);
     const int ht = ht0 + wave;
     if (tid == 0) {
-        int left = (int)blockIdx.x, e = 0, begin = 0, end = 0;
+        int left = chunk, e = 0, begin = 0, end = 0;
         bool found = false;
         for (e = 0; e < E; ++e) {
             const int lo = offsets[e], hi = offsets[e + 1];
@@ -540,7 +544,7 @@ __global__ __launch_bounds__(kBmWgWaves * 64, DS <= 64 ? 2 : 1) void bwd_weights
     }
 
     // this chunk's slot: dW1 [ds][He] | dW2 [He][ds] | db1 [He] | db2 [ds]
-    float *slot = part + (size_t)blockIdx.x * slot_floats;
+    float *slot = part + (size_t)chunk * slot_floats;
     float *pW1 = slot, *pW2 = pW1 + (size_t)DS * He, *pb1 = pW2 + (size_t)He * DS, *pb2 = pb1 + He;
 #pragma unroll
     for (int ot = 0; ot < OT; ++ot)
@@ -830,13 +834,14 @@ static hipError_t run_expert_mfma(const slicemoe_config &c, const BwdPacked &L, 
         pk2<<<(unsigned)((chunks + 7) / 8 * 8 * HT), 128, lds_p, s>>>(x, g, pk, offsets, perm, packed, L.stride, L.w2r, L.b1, c.He, c.E, c.k,
                                                                    rows_per_chunk, slot_floats, part);
         return hipGetLastError();
-    }
+    } else {
     const size_t lds_w = (size_t)2 * kBmWgWaves * (DS / 16) * 1024 + kBmWgWaves * 32 * sizeof(float);
     auto wk = bwd_weights_mfma_kernel<DS>;
     if ((e = hipFuncSetAttribute((const void *)wk, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_w)) != hipSuccess) return e;
-    wk<<<dim3((unsigned)chunks, (unsigned)((HT + kBmWgWaves - 1) / kBmWgWaves)), kBmWgWaves * 64, lds_w, s>>>(
+    wk<<<(unsigned)((chunks + 7) / 8 * 8 * ((HT + kBmWgWaves - 1) / kBmWgWaves)), kBmWgWaves * 64, lds_w, s>>>(
         x, g, pk, offsets, perm, packed, L.stride, L.w2r, L.b1, c.He, c.E, c.k, rows_per_chunk, slot_floats, part);
     return hipGetLastError();
+    }
 }
 
 // Packs the backward copies of the expert weights into `packed` (backward_mfma_packed_bytes), then runs the two kernels.

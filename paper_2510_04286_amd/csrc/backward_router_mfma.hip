@@ -372,7 +372,7 @@ __global__ __launch_bounds__(kRbThreads) void bwd_route_inputs_mfma_kernel(
 }
 
 // ----------------------------------------------------------------------------------------------- weights kernel
-// grid.x = range of slices_per_block slices (its slot of partial sums), grid.y = group of four hidden tiles, block = one
+// grid = ranges of slices_per_block slices (each a slot of partial sums; rounded up to eight) x two groups of four hidden tiles, block = one
 // wavefront per hidden tile of the group.
 template <int DS, int ET>
 __global__ __launch_bounds__(kRbWgWaves * 64, (DS <= 64 && ET == 1) ? 2 : 1) void bwd_route_weights_mfma_kernel(
@@ -389,7 +389,11 @@ __global__ __launch_bounds__(kRbWgWaves * 64, (DS <= 64 && ET == 1) ? 2 : 1) voi
 
     const int tid = threadIdx.x, lane = tid & 63, jj = lane & 31, g = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int ht0 = (int)blockIdx.y * kRbWgWaves, ht = ht0 + wave;   // kRbHT is a multiple of the group size
+    // Consecutive blocks go to the eight XCDs in turn, each with its own L2: the two groups of a slice range, which
+    // read the same rows, take block ids that are equal modulo 8.
+    constexpr int kGroups = kRbHT / kRbWgWaves;   // kRbHT is a multiple of the group size
+    const int ht0 = ((int)(blockIdx.x / 8) % kGroups) * kRbWgWaves, ht = ht0 + wave;
+    const long long range = (long long)(blockIdx.x / (8 * kGroups)) * 8 + (long long)(blockIdx.x % 8);
     stage_bytes(packed + L.w1f + (size_t)ht0 * KS * 1024, (char *)w1f, (size_t)kRbWgWaves * KS * 1024, tid, kRbWgWaves * 64);
     stage_bytes(packed + L.w2r + (size_t)ht0 * GS * 1024, (char *)w2r, (size_t)kRbWgWaves * GS * 1024, tid, kRbWgWaves * 64);
     if (tid < kRbWgWaves * 32) b1s[tid] = ((const float *)(packed + L.b1))[ht0 * 32 + tid];
@@ -410,7 +414,8 @@ __global__ __launch_bounds__(kRbWgWaves * 64, (DS <= 64 && ET == 1) ? 2 : 1) voi
 #pragma unroll
     for (int et = 0; et < ET; ++et) ab2[et] = 0.f;
 
-    const long long n_begin = (long long)blockIdx.x * slices_per_block;
+    const long long n_begin = range * slices_per_block;
+    if (n_begin >= Ns) return;   // the grid is rounded up to whole groups of eight ranges (no barrier follows)
     const long long n_end = min(Ns, n_begin + slices_per_block);
     for (long long n0 = n_begin; n0 < n_end; n0 += 32) {
         const long long n = n0 + jj;   // as A operand a lane holds slice jj of the unit, contraction slots 8g..8g+7
@@ -493,7 +498,7 @@ __global__ __launch_bounds__(kRbWgWaves * 64, (DS <= 64 && ET == 1) ? 2 : 1) voi
     }
 
     // this block's slot: dWr1 [ds][Hr] | dWr2 [Hr][E] | dbr1 [Hr] | dbr2 [E]
-    float *slot = part + (size_t)blockIdx.x * slot_floats;
+    float *slot = part + (size_t)range * slot_floats;
     float *pWr1 = slot, *pWr2 = pWr1 + (size_t)DS * kRbHr, *pbr1 = pWr2 + (size_t)kRbHr * E, *pbr2 = pbr1 + kRbHr;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -581,7 +586,7 @@ static hipError_t run_router_mfma(const slicemoe_config &c, const RouterBwdPacke
     if ((e = hipGetLastError()) != hipSuccess) return e;
     auto wk = bwd_route_weights_mfma_kernel<DS, ET>;
     if ((e = hipFuncSetAttribute((const void *)wk, hipFuncAttributeMaxDynamicSharedMemorySize, (int)weights_lds(DS, ET))) != hipSuccess) return e;
-    wk<<<dim3((unsigned)slice_blocks, kRbHT / kRbWgWaves), kRbWgWaves * 64, weights_lds(DS, ET), s>>>(
+    wk<<<(unsigned)((slice_blocks + 7) / 8 * 8 * (kRbHT / kRbWgWaves)), kRbWgWaves * 64, weights_lds(DS, ET), s>>>(
         (const bf16_t *)h, Ns, c.E, pb, L, dg_hi, dg_lo, slices_per_block, slot_floats, part);
     return hipGetLastError();
 }
