@@ -567,30 +567,33 @@ __global__ __launch_bounds__(kBmWgWaves * 64, 2) void bwd_weights_mfma_kernel(  
 // ------------------------------------------------------------------------------- weights kernel, wavefront pairs
 // The same for slice widths 96 and 128, whose 6 or 8 accumulator tiles plus operands exceed half a SIMD's registers
 // (the kernel above then runs one wavefront per SIMD and leaves its latencies uncovered).  Here TWO wavefronts share a
-// hidden tile: both form u and da of the 32-row unit, each evaluates the activation and dL/dz for the sixteen rows
-// of one K-step (registers 8 W .. 8 W + 7), they trade the resulting fragments through LDS (one barrier per unit,
-// buffers alternating with the unit's parity), and each accumulates the weight-gradient tiles of its half of the
-// slice features.  grid = chunks (rounded up to eight) x hidden tiles, block = the pair.
+// hidden tile and split the work by operand: wavefront 0 reads the x rows, forms u and accumulates dW1 = x^T (p dz);
+// wavefront 1 reads the dy rows, forms da and accumulates dW2 = a1^T dy.  Each evaluates the activation and dL/dz for
+// the sixteen rows of one K-step (registers 8 W .. 8 W + 7): they trade the halves of u and da those rows need, then
+// the resulting fragments (a1 to wavefront 1, p dz to wavefront 0), through LDS: two barriers per unit, buffers
+// alternating with the unit's parity.  Every row piece is read once per pair.
+// grid = chunks (rounded up to eight) x hidden tiles, block = the pair.
 template <int DS, int W>
 __device__ __forceinline__ void bwd_weights_pair_body(
     const bf16_t *__restrict__ x, const bf16_t *__restrict__ dout, const float *__restrict__ pk,
     const int32_t *__restrict__ perm, int He, int k, int row_begin, int row_end, const uint4 *w1f, const uint4 *w2r,
-    uint4 *xch, const float *b1s, float *red, int ht, int lane, float *__restrict__ slot)
+    float *fx, uint4 *xch, const float *b1s, float *red, int ht, int lane, float *__restrict__ slot)
 {
-    constexpr int KS = DS / 16, OT = DS / 32, OTW = (OT + 1) / 2;
-    constexpr int OT0 = W * OTW, NOT = (OT0 + OTW <= OT) ? OTW : OT - OT0;   // this wavefront's output tiles
+    constexpr int KS = DS / 16, OT = DS / 32;
     const int jj = lane & 31, g = lane >> 5;
     bf16x8 id_even, id_odd;
     identity_fragments(jj, g, id_even, id_odd);
     const float bias = b1s[jj];
+    const uint4 *wf = W == 0 ? w1f : w2r;            // fragments of this wavefront's first contraction
+    const bf16_t *rows = W == 0 ? x : dout;          // and the rows it reads
 
-    f32x16 aW1[NOT], aW2[NOT];
-    float ab1 = 0.f, ab2[NOT];
+    f32x16 aW[OT];   // W = 0: dW1 tiles (lane = hidden unit, registers = features); W = 1: dW2 tiles (lane = feature)
+    float ab1 = 0.f, ab2[OT];
 #pragma unroll
-    for (int o = 0; o < NOT; ++o) {
-        ab2[o] = 0.f;
+    for (int ot = 0; ot < OT; ++ot) {
+        ab2[ot] = 0.f;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) aW1[o][i] = aW2[o][i] = 0.f;
+        for (int i = 0; i < 16; ++i) aW[ot][i] = 0.f;
     }
     int parity = 0;
     for (int r0 = row_begin; r0 < row_end; r0 += 32) {
@@ -599,37 +602,39 @@ __device__ __forceinline__ void bwd_weights_pair_body(
         const int a = perm[valid ? row : row_begin];
         const long long n = a / k;
         const float p_lane = valid ? pk[a] : 0.f;
-        const uint4 *xr = (const uint4 *)(x + n * DS), *gr = (const uint4 *)(dout + n * DS);
-        bf16x8 xa[KS], ga[KS];
+        const uint4 *rr = (const uint4 *)(rows + n * DS);
+        bf16x8 ra[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            xa[ks] = __builtin_bit_cast(bf16x8, xr[2 * ks + g]);
-            const uint4 gv = valid ? gr[2 * ks + g] : make_uint4(0, 0, 0, 0);   // rows past the end add nothing
-            ga[ks] = __builtin_bit_cast(bf16x8, gv);
+            const uint4 v = (W == 0 || valid) ? rr[2 * ks + g] : make_uint4(0, 0, 0, 0);   // dy of rows past the end adds nothing
+            ra[ks] = __builtin_bit_cast(bf16x8, v);
         }
-        // transposed results: lane = hidden unit jj of the tile, register i = row acc_feature(i, g) of the unit
-        f32x16 u, da;
+        // transposed result: lane = hidden unit jj of the tile, register i = row acc_feature(i, g): u (W = 0) or da (W = 1)
+        f32x16 v;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) u[i] = da[i] = 0.f;
+        for (int i = 0; i < 16; ++i) v[i] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            u = mfma_bf16(xa[ks], __builtin_bit_cast(bf16x8, w1f[ks * 64 + lane]), u);
-            da = mfma_bf16(ga[ks], __builtin_bit_cast(bf16x8, w2r[ks * 64 + lane]), da);
-        }
-        // this wavefront's K-step of the four operands: the activation and p dz, two bf16 terms each
+        for (int ks = 0; ks < KS; ++ks) v = mfma_bf16(ra[ks], __builtin_bit_cast(bf16x8, wf[ks * 64 + lane]), v);
+        // the partner evaluates registers 8 (1 - W) ..: it gets those of this result, this wavefront those of the partner's
+        float *out = fx + ((parity * 2 + W) * 8) * 64 + lane;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) out[i * 64] = v[8 * (1 - W) + i];
+        __syncthreads();
+        const float *in = fx + ((parity * 2 + (1 - W)) * 8) * 64 + lane;
         uint32_t a1p[4], a1l[4], pdzp[4], pdzl[4];
 #pragma unroll
         for (int ii = 0; ii < 8; ii += 2) {
             float act[2], pdz[2];
 #pragma unroll
             for (int c = 0; c < 2; ++c) {
-                constexpr int base = 8 * W;
-                const int i = base + ii + c;
+                const int i = 8 * W + ii + c;
+                const float other = in[(ii + c) * 64];
+                const float u = W == 0 ? v[i] : other, da = W == 0 ? other : v[i];
                 const float p = __shfl(p_lane, acc_feature(i, g));   // probability of the register's row
-                const float z = fmaf(p, u[i], bias);
+                const float z = fmaf(p, u, bias);
                 float dens;
                 const float cdf = normal_cdf_pdf(z, &dens);
-                const float dz = da[i] * fmaf(z, dens, cdf);
+                const float dz = da * fmaf(z, dens, cdf);
                 act[c] = z * cdf;
                 pdz[c] = p * dz;
                 ab1 += dz;
@@ -637,54 +642,48 @@ __device__ __forceinline__ void bwd_weights_pair_body(
             split_bf16x2(act[0], act[1], a1p[ii / 2], a1l[ii / 2]);
             split_bf16x2(pdz[0], pdz[1], pdzp[ii / 2], pdzl[ii / 2]);
         }
-        uint4 *mine = xch + ((parity * 2 + W) * 4) * 64 + lane;
-        mine[0] = make_uint4(a1p[0], a1p[1], a1p[2], a1p[3]);
-        mine[64] = make_uint4(a1l[0], a1l[1], a1l[2], a1l[3]);
-        mine[128] = make_uint4(pdzp[0], pdzp[1], pdzp[2], pdzp[3]);
-        mine[192] = make_uint4(pdzl[0], pdzl[1], pdzl[2], pdzl[3]);
+        // wavefront 0 needs p dz of both K-steps, wavefront 1 the activation: each sends what the other lacks
+        uint4 *mine = xch + ((parity * 2 + W) * 2) * 64 + lane;
+        if (W == 0) {
+            mine[0] = make_uint4(a1p[0], a1p[1], a1p[2], a1p[3]);
+            mine[64] = make_uint4(a1l[0], a1l[1], a1l[2], a1l[3]);
+        } else {
+            mine[0] = make_uint4(pdzp[0], pdzp[1], pdzp[2], pdzp[3]);
+            mine[64] = make_uint4(pdzl[0], pdzl[1], pdzl[2], pdzl[3]);
+        }
         __syncthreads();
-        const uint4 *theirs = xch + ((parity * 2 + (1 - W)) * 4) * 64 + lane;
-        bf16x8 ah[2], al[2], dh[2], dl[2];   // by K-step: step W is this wavefront's own
-        ah[W] = __builtin_bit_cast(bf16x8, make_uint4(a1p[0], a1p[1], a1p[2], a1p[3]));
-        al[W] = __builtin_bit_cast(bf16x8, make_uint4(a1l[0], a1l[1], a1l[2], a1l[3]));
-        dh[W] = __builtin_bit_cast(bf16x8, make_uint4(pdzp[0], pdzp[1], pdzp[2], pdzp[3]));
-        dl[W] = __builtin_bit_cast(bf16x8, make_uint4(pdzl[0], pdzl[1], pdzl[2], pdzl[3]));
-        ah[1 - W] = __builtin_bit_cast(bf16x8, theirs[0]);
-        al[1 - W] = __builtin_bit_cast(bf16x8, theirs[64]);
-        dh[1 - W] = __builtin_bit_cast(bf16x8, theirs[128]);
-        dl[1 - W] = __builtin_bit_cast(bf16x8, theirs[192]);
+        const uint4 *theirs = xch + ((parity * 2 + (1 - W)) * 2) * 64 + lane;
+        bf16x8 hi[2], lo[2];   // by K-step (step W is this wavefront's own): p dz for W = 0, the activation for W = 1
+        hi[W] = __builtin_bit_cast(bf16x8, W == 0 ? make_uint4(pdzp[0], pdzp[1], pdzp[2], pdzp[3]) : make_uint4(a1p[0], a1p[1], a1p[2], a1p[3]));
+        lo[W] = __builtin_bit_cast(bf16x8, W == 0 ? make_uint4(pdzl[0], pdzl[1], pdzl[2], pdzl[3]) : make_uint4(a1l[0], a1l[1], a1l[2], a1l[3]));
+        hi[1 - W] = __builtin_bit_cast(bf16x8, theirs[0]);
+        lo[1 - W] = __builtin_bit_cast(bf16x8, theirs[64]);
         parity ^= 1;
 #pragma unroll
-        for (int o = 0; o < NOT; ++o) {
-            constexpr int dummy = 0;
-            (void)dummy;
-            const int ot = OT0 + o;   // a constant after unrolling
-            // x and dy of the unit with lane = slice feature 32 ot + jj, registers = rows
-            f32x16 xt, gt;
+        for (int ot = 0; ot < OT; ++ot) {
+            // the rows of the unit with lane = slice feature 32 ot + jj, registers = rows (exact)
+            f32x16 t;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) xt[i] = gt[i] = 0.f;
-            xt = mfma_bf16(xa[2 * ot], id_even, xt);
-            xt = mfma_bf16(xa[2 * ot + 1], id_odd, xt);
-            gt = mfma_bf16(ga[2 * ot], id_even, gt);
-            gt = mfma_bf16(ga[2 * ot + 1], id_odd, gt);
-            if (ht == 0) {
+            for (int i = 0; i < 16; ++i) t[i] = 0.f;
+            t = mfma_bf16(ra[2 * ot], id_even, t);
+            t = mfma_bf16(ra[2 * ot + 1], id_odd, t);
+            if (W == 1 && ht == 0) {
                 float sum = 0.f;
 #pragma unroll
-                for (int i = 0; i < 16; ++i) sum += gt[i];
-                ab2[o] += sum;
+                for (int i = 0; i < 16; ++i) sum += t[i];
+                ab2[ot] += sum;
             }
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
-                const bf16x8 xs = __builtin_bit_cast(bf16x8, make_uint4(pack_exact_bf16x2(xt[8 * s], xt[8 * s + 1]), pack_exact_bf16x2(xt[8 * s + 2], xt[8 * s + 3]),
-                                                                         pack_exact_bf16x2(xt[8 * s + 4], xt[8 * s + 5]), pack_exact_bf16x2(xt[8 * s + 6], xt[8 * s + 7])));
-                const bf16x8 gs = __builtin_bit_cast(bf16x8, make_uint4(pack_exact_bf16x2(gt[8 * s], gt[8 * s + 1]), pack_exact_bf16x2(gt[8 * s + 2], gt[8 * s + 3]),
-                                                                         pack_exact_bf16x2(gt[8 * s + 4], gt[8 * s + 5]), pack_exact_bf16x2(gt[8 * s + 6], gt[8 * s + 7])));
-                // [hidden unit][slice feature]: lane = feature, registers = hidden units; small term first
-                aW2[o] = mfma_bf16(al[s], gs, aW2[o]);
-                aW2[o] = mfma_bf16(ah[s], gs, aW2[o]);
-                // [slice feature][hidden unit]: lane = hidden unit, registers = features
-                aW1[o] = mfma_bf16(xs, dl[s], aW1[o]);
-                aW1[o] = mfma_bf16(xs, dh[s], aW1[o]);
+                const bf16x8 ts = __builtin_bit_cast(bf16x8, make_uint4(pack_exact_bf16x2(t[8 * s], t[8 * s + 1]), pack_exact_bf16x2(t[8 * s + 2], t[8 * s + 3]),
+                                                                         pack_exact_bf16x2(t[8 * s + 4], t[8 * s + 5]), pack_exact_bf16x2(t[8 * s + 6], t[8 * s + 7])));
+                if (W == 0) {   // [slice feature][hidden unit]: lane = hidden unit, registers = features; small term first
+                    aW[ot] = mfma_bf16(ts, lo[s], aW[ot]);
+                    aW[ot] = mfma_bf16(ts, hi[s], aW[ot]);
+                } else {        // [hidden unit][slice feature]: lane = feature, registers = hidden units
+                    aW[ot] = mfma_bf16(lo[s], ts, aW[ot]);
+                    aW[ot] = mfma_bf16(hi[s], ts, aW[ot]);
+                }
             }
         }
     }
@@ -692,15 +691,14 @@ __device__ __forceinline__ void bwd_weights_pair_body(
     // the chunk's slot: dW1 [ds][He] | dW2 [He][ds] | db1 [He] | db2 [ds]
     float *pW1 = slot, *pW2 = pW1 + (size_t)DS * He, *pb1 = pW2 + (size_t)He * DS, *pb2 = pb1 + He;
 #pragma unroll
-    for (int o = 0; o < NOT; ++o) {
-        const int ot = OT0 + o;
+    for (int ot = 0; ot < OT; ++ot) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            pW1[(size_t)(32 * ot + acc_feature(i, g)) * He + 32 * ht + jj] = aW1[o][i];
-            pW2[(size_t)(32 * ht + acc_feature(i, g)) * DS + 32 * ot + jj] = aW2[o][i];
+            if (W == 0) pW1[(size_t)(32 * ot + acc_feature(i, g)) * He + 32 * ht + jj] = aW[ot][i];
+            else pW2[(size_t)(32 * ht + acc_feature(i, g)) * DS + 32 * ot + jj] = aW[ot][i];
         }
-        if (ht == 0) {
-            const float t = ab2[o] + __shfl_xor(ab2[o], 32);
+        if (W == 1 && ht == 0) {
+            const float t = ab2[ot] + __shfl_xor(ab2[ot], 32);
             if (g == 0) pb2[32 * ot + jj] = t;
         }
     }
@@ -722,8 +720,9 @@ __global__ __launch_bounds__(128, 2) void bwd_weights_pair_mfma_kernel(
     extern __shared__ __align__(16) char lds[];
     uint4 *w1f = (uint4 *)lds;              // [KS][64] fragments of this hidden tile
     uint4 *w2r = w1f + KS * 64;             // [KS][64]
-    uint4 *xch = w2r + KS * 64;             // [parity][wavefront][operand][64]
-    float *b1s = (float *)(xch + 2 * 2 * 4 * 64);   // [32]
+    uint4 *xch = w2r + KS * 64;             // [parity][wavefront][term][64] fragments traded
+    float *fx = (float *)(xch + 2 * 2 * 2 * 64);    // [parity][wavefront][8][64] halves of u / da traded
+    float *b1s = fx + 2 * 2 * 8 * 64;       // [32]
     float *red = b1s + 32;                  // [32]
     __shared__ int blk[3];
 
@@ -762,8 +761,8 @@ __global__ __launch_bounds__(128, 2) void bwd_weights_pair_mfma_kernel(
     __syncthreads();
     float *slot = part + (size_t)chunk * slot_floats;
     // the same number of units, hence of barriers, in both wavefronts
-    if (wave == 0) bwd_weights_pair_body<DS, 0>(x, dout, pk, perm, He, k, row_begin, row_end, w1f, w2r, xch, b1s, red, ht, lane, slot);
-    else bwd_weights_pair_body<DS, 1>(x, dout, pk, perm, He, k, row_begin, row_end, w1f, w2r, xch, b1s, red, ht, lane, slot);
+    if (wave == 0) bwd_weights_pair_body<DS, 0>(x, dout, pk, perm, He, k, row_begin, row_end, w1f, w2r, fx, xch, b1s, red, ht, lane, slot);
+    else bwd_weights_pair_body<DS, 1>(x, dout, pk, perm, He, k, row_begin, row_end, w1f, w2r, fx, xch, b1s, red, ht, lane, slot);
 }
 
 // ------------------------------------------------------------------------------------------------------ host
@@ -828,7 +827,7 @@ static hipError_t run_expert_mfma(const slicemoe_config &c, const BwdPacked &L, 
     if ((e = hipGetLastError()) != hipSuccess) return e;
     const int HT = c.He / 32;
     if constexpr (DS >= 96) {
-        const size_t lds_p = (size_t)2 * (DS / 16) * 1024 + 2 * 2 * 4 * 1024 + 64 * sizeof(float);
+        const size_t lds_p = (size_t)2 * (DS / 16) * 1024 + 2 * 2 * 2 * 1024 + 2 * 2 * 8 * 64 * sizeof(float) + 64 * sizeof(float);
         auto pk2 = bwd_weights_pair_mfma_kernel<DS>;
         if ((e = hipFuncSetAttribute((const void *)pk2, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_p)) != hipSuccess) return e;
         pk2<<<(unsigned)((chunks + 7) / 8 * 8 * HT), 128, lds_p, s>>>(x, g, pk, offsets, perm, packed, L.stride, L.w2r, L.b1, c.He, c.E, c.k,
