@@ -1,7 +1,7 @@
 // Matrix-core backward of the expert stage for slice widths 64, 96 and 128 and any hidden width that is a multiple
 // of 32: the recomputed pre-activations, dL/dz, dL/dx, dL/dp and the expert weight gradients of the backward
-// pass described in backward.hip, on v_mfma_f32_32x32x16_bf16.  Two kernels, both without any exchange between
-// wavefronts:
+// pass described in backward.hip, on v_mfma_f32_32x32x16_bf16.  Two kernels per width (the weights kernel of the wide
+// slices, further down, is the only one whose wavefronts exchange anything):
 //
 //   bwd_rows_mfma_kernel     the forward's layout: a lane owns one stacked row (see mfma.h).  Per 32-row unit and
 //                            32-wide hidden tile: u = W1^T x and da = W2 dy (weight fragment = A operand, row
