@@ -198,10 +198,17 @@ def test_backward_large_workload_full_size_sampled(B):
     assert finite
 
 
-def test_backward_is_reproducible_bit_for_bit(B):
-    """Partial weight gradients are summed in a fixed order: two calls give identical bits."""
+@pytest.mark.parametrize("which", ["headline", "ds128", "paper"])
+def test_backward_is_reproducible_bit_for_bit(B, which):
+    """Partial weight gradients are summed in a fixed order: two calls give identical bits (width 64: one wavefront per
+    hidden tile; widths 128 and 96: the wavefront pairs that trade operands through LDS)."""
     import torch
-    shape, h, w = make_inputs(wl.CONFIGS["headline"], 1500)
+    if which == "headline":
+        shape, h, w = make_inputs(wl.CONFIGS["headline"], 1500)
+    elif which == "paper":
+        shape, h, w = make_inputs(wl.CONFIGS["paper"], 700)
+    else:
+        shape, h, w = make_inputs(wl.SliceMoEShape("ds128r", T=900, d=512, S=4, E=8, k=2, He=160), None)
     cfg = B.config_of(shape)
     wd = B.pack(cfg, B.weights_to_device(w, shape.dtype))
     ws = B.alloc_workspace(cfg)
