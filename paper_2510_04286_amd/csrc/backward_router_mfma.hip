@@ -375,7 +375,7 @@ __global__ __launch_bounds__(kRbThreads) void bwd_route_inputs_mfma_kernel(
 // grid = ranges of slices_per_block slices (each a slot of partial sums; rounded up to eight) x two groups of four hidden tiles, block = one
 // wavefront per hidden tile of the group.
 template <int DS, int ET>
-__global__ __launch_bounds__(kRbWgWaves * 64, (DS <= 64 && ET == 1) ? 2 : 1) void bwd_route_weights_mfma_kernel(
+__global__ __launch_bounds__(kRbWgWaves * 64, (DS * (ET + 1) <= 256) ? 2 : 1) void bwd_route_weights_mfma_kernel(
     const bf16_t *__restrict__ x, long long Ns, int E, const char *__restrict__ packed, RouterBwdPacked L,
     const bf16_t *__restrict__ dg_hi, const bf16_t *__restrict__ dg_lo, int slices_per_block, size_t slot_floats,
     float *__restrict__ part)
