@@ -63,6 +63,8 @@ CASES = {
     "He512": (wl.SliceMoEShape("He512", T=300, d=256, S=4, E=4, k=2, He=512), None, None),
     "ds128": (wl.SliceMoEShape("ds128", T=200, d=512, S=4, E=8, k=2, He=160), None, dict(tau=0.9, sigma=0.1, rate=0.2)),
     "large_like": (wl.CONFIGS["large"], 24, None),
+    # width 128 with many chunks per expert and a ragged last one: the wavefront-pair weights kernel over >100 slots
+    "ds128_chunks": (wl.SliceMoEShape("ds128_chunks", T=8200, d=512, S=4, E=8, k=2, He=256), None, None, "ties"),
     "ds96_E48": (wl.SliceMoEShape("ds96_E48", T=333, d=384, S=4, E=48, k=2, He=96), None, dict(tau=1.2, sigma=0.1, rate=0.2)),
     "ds128_E64": (wl.SliceMoEShape("ds128_E64", T=333, d=512, S=4, E=64, k=2, He=64), None, dict(tau=0.8, sigma=0.2, rate=0.25)),
     # the benchmark workload at its full size (the launch configuration bench.py times): 524 288 rows, 16 384 per expert.
