@@ -270,17 +270,6 @@ slicemoe_status slicemoe_backward(const slicemoe_config *cfg, const void *h, con
                                   const void *d_out, void *d_h, const slicemoe_weight_grads *grads,
                                   void *workspace, size_t workspace_bytes, slicemoe_stream_t stream);
 
-/*
- * Measurement aid (not a step of the layer): runs `nblocks` blocks of 256 threads, each doing `iters`
- * rounds of a fixed register-only mix of bf16 matrix and packed-fp16 vector instructions, and writes
- * per block cycles_and_ticks[2*b] = elapsed shader cycles, [2*b+1] = elapsed ticks of the constant
- * 100 MHz counter (DEVICE memory, 2*nblocks uint64).  cycles / ticks * 100 MHz is the shader clock
- * sustained under matrix + vector load, against which the 2.4 GHz peak figures are to be read.
- * INVALID_ARG for a null pointer, nblocks outside [1, 65536] or iters outside [1, 2^24].
- */
-slicemoe_status slicemoe_probe_clock(uint64_t *cycles_and_ticks, int32_t nblocks, int32_t iters,
-                                     slicemoe_stream_t stream);
-
 #ifdef __cplusplus
 }
 #endif

@@ -28,7 +28,7 @@ EXPORTS = [
     "slicemoe_status_string", "slicemoe_uses_mfma", "slicemoe_capacity", "slicemoe_workspace_bytes",
     "slicemoe_dispatch_workspace_bytes", "slicemoe_get_workspace_layout", "slicemoe_packed_bytes",
     "slicemoe_pack_weights", "slicemoe_route", "slicemoe_dispatch", "slicemoe_expert_ffn",
-    "slicemoe_combine", "slicemoe_load_stats", "slicemoe_forward", "slicemoe_probe_clock",
+    "slicemoe_combine", "slicemoe_load_stats", "slicemoe_forward",
     "slicemoe_route_train", "slicemoe_forward_train", "slicemoe_backward_workspace_bytes", "slicemoe_backward",
     "slicemoe_backward_uses_mfma",
 ]
@@ -99,8 +99,6 @@ def lib() -> ctypes.CDLL:
         L.slicemoe_load_stats.argtypes = [cfgp, vp, vp, vp, vp]
         L.slicemoe_forward.restype = ctypes.c_int
         L.slicemoe_forward.argtypes = [cfgp, vp, wp, vp, vp, st, vp]
-        L.slicemoe_probe_clock.restype = ctypes.c_int
-        L.slicemoe_probe_clock.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, vp]
         tpp = ctypes.POINTER(slicemoe_route_train_params)
         L.slicemoe_route_train.restype = ctypes.c_int
         L.slicemoe_route_train.argtypes = [cfgp, vp, wp, tpp, vp, vp, vp, vp, vp, st, vp]
@@ -342,11 +340,6 @@ def slicemoe_backward(cfg, h, w, forward_workspace, d_out, d_h, grads: dict, wor
                                    npt, upt, fwp, fwb, _ptr(d_out, _tdtype(cfg), cfg.T * cfg.d, "d_out"),
                                    _ptr(d_h, _tdtype(cfg), cfg.T * cfg.d, "d_h"), ctypes.byref(g), wsp, wsb,
                                    _stream(stream)), "slicemoe_backward")
-
-
-def slicemoe_probe_clock(cycles_and_ticks, nblocks: int, iters: int, stream=None):
-    _check(lib().slicemoe_probe_clock(_ptr(cycles_and_ticks, torch.int64, 2 * nblocks, "cycles_and_ticks"), nblocks, iters,
-                                      _stream(stream)), "slicemoe_probe_clock")
 
 
 # ------------------------------------------------------------------ plumbing helpers (device memory only)

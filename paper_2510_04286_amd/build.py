@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libslicemoe.so")
-SOURCES = ["api.hip", "dispatch.hip", "combine.hip", "generic.hip", "pack.hip", "ffn_mfma.hip", "route_mfma.hip", "clock.hip", "backward.hip", "backward_mfma.hip", "backward_router_mfma.hip"]
+SOURCES = ["api.hip", "dispatch.hip", "combine.hip", "generic.hip", "pack.hip", "ffn_mfma.hip", "route_mfma.hip", "backward.hip", "backward_mfma.hip", "backward_router_mfma.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-munsafe-fp-atomics", "-Wall", "-Wno-unused-function"]
 

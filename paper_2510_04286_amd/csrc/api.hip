@@ -2,6 +2,9 @@
 // Host code only; every device step lives in the kernel files.
 #include <math.h>
 
+#include <mutex>
+#include <vector>
+
 #include "common.h"
 
 namespace slicemoe {
@@ -30,6 +33,31 @@ int max_lds_per_block()
         lds[dev] = n;
     }
     return lds[dev];
+}
+
+hipError_t grant_dynamic_lds(const void *kern, size_t bytes)
+{
+    struct Granted {
+        const void *kern;
+        int dev;
+        size_t bytes;
+    };
+    static std::mutex mu;
+    static std::vector<Granted> table;   // a few dozen kernels: a linear search
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    for (Granted &g : table)
+        if (g.kern == kern && g.dev == dev) {
+            if (g.bytes >= bytes) return hipSuccess;
+            e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+            if (e == hipSuccess) g.bytes = bytes;
+            return e;
+        }
+    e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) table.push_back({kern, dev, bytes});
+    return e;
 }
 
 // Shapes the matrix-core kernels are instantiated for: 64 and 128 are the benchmark slice widths; 24, 48, 96 and 192
@@ -431,6 +459,7 @@ slicemoe_status slicemoe_backward(const slicemoe_config *cfg, const void *h, con
         rate = params->dropout_rate;
     }
     if (!w || !grads || ((!h || !d_out || !d_h) && cfg->T > 0)) return SLICEMOE_ERR_INVALID_ARG;
+    if (misaligned(h, 16) || misaligned(d_out, 16) || misaligned(d_h, 16)) return SLICEMOE_ERR_INVALID_ARG;   // 16-byte row pieces
     if (!logical_weights_ok(*w, true, true)) return SLICEMOE_ERR_INVALID_ARG;
     if (!grads->Wr1 || !grads->br1 || !grads->Wr2 || !grads->br2 || !grads->W1 || !grads->b1 || !grads->W2 || !grads->b2)
         return SLICEMOE_ERR_INVALID_ARG;
@@ -445,14 +474,6 @@ slicemoe_status slicemoe_backward(const slicemoe_config *cfg, const void *h, con
                                          (const int32_t *)(fw + L.perm), (const int32_t *)(fw + L.inv), d_out, d_h, *grads,
                                          workspace, (hipStream_t)stream);
     return e == hipSuccess ? SLICEMOE_OK : SLICEMOE_ERR_HIP;
-}
-
-slicemoe_status slicemoe_probe_clock(uint64_t *cycles_and_ticks, int32_t nblocks, int32_t iters, slicemoe_stream_t stream)
-{
-    if (!cycles_and_ticks || nblocks < 1 || nblocks > 65536 || iters < 1 || iters > (1 << 24)) return SLICEMOE_ERR_INVALID_ARG;
-    return launch_clock_probe((unsigned long long *)cycles_and_ticks, nblocks, iters, (hipStream_t)stream) == hipSuccess
-               ? SLICEMOE_OK
-               : SLICEMOE_ERR_HIP;
 }
 
 }  // extern "C"

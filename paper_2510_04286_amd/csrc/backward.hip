@@ -616,7 +616,7 @@ static hipError_t run_backward(const slicemoe_config &c, const void *h, const sl
     const dim3 egrid((unsigned)P.chunks, hidden_groups, col_chunks);
     if (lds_ew <= (size_t)max_lds_per_block()) {
         auto kern = bwd_expert_kernel<T, true>;
-        if ((e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_ew)) != hipSuccess)
+        if ((e = grant_dynamic_lds((const void *)kern, lds_ew)) != hipSuccess)
             return e;
         kern<<<egrid, kBwdThreads, lds_ew, s>>>((const T *)h, (const T *)d_out, pk, offsets, perm, ds, c.He, c.E, c.k,
                                                  (const T *)w.W1, (const T *)w.b1, (const T *)w.W2, dxrow, dpk,
@@ -650,7 +650,7 @@ static hipError_t run_backward(const slicemoe_config &c, const void *h, const sl
     const float *nz = v.sigma > 0.f ? v.noise : nullptr, *du = rate > 0.f ? drop_u : nullptr;
     if (lds_rw <= (size_t)max_lds_per_block()) {
         auto kern = bwd_router_kernel<T, true>;
-        if ((e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_rw)) != hipSuccess)
+        if ((e = grant_dynamic_lds((const void *)kern, lds_rw)) != hipSuccess)
             return e;
         kern<<<rgrid, kBwdThreads, lds_rw, s>>>((const T *)h, Ns, ds, c.Hr, c.E, c.k, (const T *)w.Wr1, (const T *)w.br1,
                                                  (const T *)w.Wr2, (const T *)w.br2, nz, v.sigma, v.inv_tau, du, rate, idx, inv,

@@ -809,7 +809,7 @@ static hipError_t run_expert_mfma(const slicemoe_config &c, const BwdPacked &L, 
         long long blocks = (Na + 31) / 32;
         if (blocks > num_compute_units()) blocks = num_compute_units();
         auto rows = c.He == 256 ? bwd_rows_mfma_kernel<8> : c.He == 128 ? bwd_rows_mfma_kernel<4> : bwd_rows_mfma_kernel<2>;
-        if ((e = hipFuncSetAttribute((const void *)rows, hipFuncAttributeMaxDynamicSharedMemorySize, (int)L.stride)) != hipSuccess)
+        if ((e = grant_dynamic_lds((const void *)rows, L.stride)) != hipSuccess)
             return e;
         rows<<<(int)blocks, kBmRowThreads, L.stride, s>>>(x, g, pk, offsets, perm, packed, L.stride, L.w2r, L.w1c, L.b1, c.E, c.k,
                                                           dxrow, dpk);
@@ -819,7 +819,7 @@ static hipError_t run_expert_mfma(const slicemoe_config &c, const BwdPacked &L, 
         long long blocks = (Na + kBmTileRows - 1) / kBmTileRows + c.E;
         if (blocks > num_compute_units()) blocks = num_compute_units();
         auto rows = bwd_rows_streamed_mfma_kernel<DS>;
-        if ((e = hipFuncSetAttribute((const void *)rows, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess)
+        if ((e = grant_dynamic_lds((const void *)rows, lds)) != hipSuccess)
             return e;
         rows<<<(int)blocks, kBmTileWaves * 64, lds, s>>>(x, g, pk, offsets, perm, packed, L.stride, L.w2r, L.w1c, L.b1, c.He, hc,
                                                          c.E, c.k, dxrow, dpk);
@@ -829,14 +829,14 @@ static hipError_t run_expert_mfma(const slicemoe_config &c, const BwdPacked &L, 
     if constexpr (DS >= 96) {
         const size_t lds_p = (size_t)2 * (DS / 16) * 1024 + 2 * 2 * 2 * 1024 + 2 * 2 * 8 * 64 * sizeof(float) + 64 * sizeof(float);
         auto pk2 = bwd_weights_pair_mfma_kernel<DS>;
-        if ((e = hipFuncSetAttribute((const void *)pk2, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_p)) != hipSuccess) return e;
+        if ((e = grant_dynamic_lds((const void *)pk2, lds_p)) != hipSuccess) return e;
         pk2<<<(unsigned)((chunks + 7) / 8 * 8 * HT), 128, lds_p, s>>>(x, g, pk, offsets, perm, packed, L.stride, L.w2r, L.b1, c.He, c.E, c.k,
                                                                    rows_per_chunk, slot_floats, part);
         return hipGetLastError();
     } else {
     const size_t lds_w = (size_t)2 * kBmWgWaves * (DS / 16) * 1024 + kBmWgWaves * 32 * sizeof(float);
     auto wk = bwd_weights_mfma_kernel<DS>;
-    if ((e = hipFuncSetAttribute((const void *)wk, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_w)) != hipSuccess) return e;
+    if ((e = grant_dynamic_lds((const void *)wk, lds_w)) != hipSuccess) return e;
     wk<<<(unsigned)((chunks + 7) / 8 * 8 * ((HT + kBmWgWaves - 1) / kBmWgWaves)), kBmWgWaves * 64, lds_w, s>>>(
         x, g, pk, offsets, perm, packed, L.stride, L.w2r, L.b1, c.He, c.E, c.k, rows_per_chunk, slot_floats, part);
     return hipGetLastError();

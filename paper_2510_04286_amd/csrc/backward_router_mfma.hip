@@ -563,7 +563,7 @@ static hipError_t run_router_mfma(const slicemoe_config &c, const RouterBwdPacke
     const long long Ns = (long long)c.T * c.S;
     const long long ntiles = (Ns + 31) / 32, units = (ntiles + kRbWaves - 1) / kRbWaves;
     auto lk = bwd_route_logits_mfma_kernel<DS, ET>;
-    hipError_t e = hipFuncSetAttribute((const void *)lk, hipFuncAttributeMaxDynamicSharedMemorySize, (int)logits_lds(DS, ET));
+    hipError_t e = grant_dynamic_lds((const void *)lk, logits_lds(DS, ET));
     if (e != hipSuccess) return e;
     // as many blocks as can be resident at once (registers and LDS allow two per CU for the narrow shapes)
     static int lk_per_cu = 0;   // per instantiation; the same on every device of the machine
@@ -579,13 +579,13 @@ static hipError_t run_router_mfma(const slicemoe_config &c, const RouterBwdPacke
                                                            dg_hi, dg_lo, bits);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     auto ik = bwd_route_inputs_mfma_kernel<DS, ET>;
-    if ((e = hipFuncSetAttribute((const void *)ik, hipFuncAttributeMaxDynamicSharedMemorySize, (int)inputs_lds(DS, ET))) != hipSuccess) return e;
+    if ((e = grant_dynamic_lds((const void *)ik, inputs_lds(DS, ET))) != hipSuccess) return e;
     // one block per CU: this kernel waits on its row gathers, and a second resident block measured slower (cache misses)
     blocks = num_compute_units() < units ? num_compute_units() : units;
     ik<<<(int)blocks, kRbThreads, inputs_lds(DS, ET), s>>>(Ns, c.k, pb, L, inv, dxrow, dg_hi, dg_lo, bits, (bf16_t *)d_h);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     auto wk = bwd_route_weights_mfma_kernel<DS, ET>;
-    if ((e = hipFuncSetAttribute((const void *)wk, hipFuncAttributeMaxDynamicSharedMemorySize, (int)weights_lds(DS, ET))) != hipSuccess) return e;
+    if ((e = grant_dynamic_lds((const void *)wk, weights_lds(DS, ET))) != hipSuccess) return e;
     wk<<<(unsigned)((slice_blocks + 7) / 8 * 8 * (kRbHT / kRbWgWaves)), kRbWgWaves * 64, weights_lds(DS, ET), s>>>(
         (const bf16_t *)h, Ns, c.E, pb, L, dg_hi, dg_lo, slices_per_block, slot_floats, part);
     return hipGetLastError();

@@ -146,9 +146,12 @@ hipError_t launch_combine(const slicemoe_config &c, const void *y, const int32_t
 hipError_t launch_load_stats(const slicemoe_config &c, const int32_t *counts_raw, const int32_t *counts,
                              float *stats, hipStream_t s);
 hipError_t launch_pack(const slicemoe_config &c, const slicemoe_weights &w, void *packed, hipStream_t s);
-hipError_t launch_clock_probe(unsigned long long *out, int nblocks, int iters, hipStream_t s);
 
 int num_compute_units();
+// Allows `kern` (a __global__ function) `bytes` of dynamic LDS on the current device.  The attribute sticks to the
+// kernel, so the driver is asked only the first time a (kernel, device) pair needs that much; later launches pay a
+// table lookup.
+hipError_t grant_dynamic_lds(const void *kern, size_t bytes);
 int max_lds_per_block();  // bytes of LDS one workgroup may use on the current device
 
 }  // namespace slicemoe

@@ -502,7 +502,7 @@ static hipError_t run_resident(const slicemoe_config &c, const PackedLayout &L, 
     long long blocks = max_units;   // small inputs: spread the units over all CUs rather than fill few blocks
     if (blocks > num_compute_units()) blocks = num_compute_units();
     auto kern = ffn_resident_kernel<DS, HT, THREADS>;
-    hipError_t err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds);
+    hipError_t err = grant_dynamic_lds((const void *)kern, pl.lds);
     if (err != hipSuccess) return err;
     kern<<<(int)blocks, THREADS, pl.lds, s>>>((const bf16_t *)h, p, offsets, perm, experts, L.e_stride, L.e_w2, L.e_b1,
                                                   L.e_b2, c.E, c.k, make_epi_const(), (half_t *)y);
@@ -520,7 +520,7 @@ static hipError_t run_streamed(const slicemoe_config &c, const PackedLayout &L, 
     long long blocks = (long long)num_compute_units() * (pl.lds <= 78 * 1024 ? 2 : 1);
     if (blocks > max_tiles) blocks = max_tiles;
     auto kern = ffn_streamed_kernel<DS, NSUB, THREADS>;
-    hipError_t err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds);
+    hipError_t err = grant_dynamic_lds((const void *)kern, pl.lds);
     if (err != hipSuccess) return err;
     kern<<<(int)blocks, THREADS, pl.lds, s>>>((const bf16_t *)h, p, offsets, perm, experts, L.e_stride, L.e_w1, L.e_w2,
                                                   L.e_b1, L.e_b2, c.He, c.E, c.k, pl.hc, make_epi_const(), (half_t *)y);

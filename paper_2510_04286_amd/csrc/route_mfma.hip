@@ -238,7 +238,7 @@ static hipError_t run_route(const slicemoe_config &c, const void *h, const void 
     const long long cap = (long long)num_compute_units();
     if (blocks > cap) blocks = cap;
     auto kern = route_mfma_kernel<DS, ET, THREADS, W1_LDS>;
-    hipError_t err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t err = grant_dynamic_lds((const void *)kern, lds);
     if (err != hipSuccess) return err;
     if (L.r_w2 != L.r_w1 + (size_t)kRouteHT * KS * 64 * 16) return hipErrorInvalidValue;   // the kernel copies W1 | W2 as one run
     kern<<<(int)blocks, THREADS, lds, s>>>((const bf16_t *)h, Ns, c.E, c.k, (const char *)packed, L.r_w1, L.r_b1, L.r_b2,

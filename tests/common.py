@@ -1,4 +1,5 @@
 """Helpers shared by the tests: golden inputs, tolerance rules, GPU plumbing."""
+import functools
 import os
 
 import numpy as np
@@ -33,6 +34,27 @@ def make_inputs(cfg, T=None):
         assert cfg.E == 32 and cfg.zipf_s == 1.2
         w["br2"] = zipf_bias()
     return cfg, wl.make_h(cfg), w
+
+
+@functools.lru_cache(maxsize=1)
+def large_inputs():
+    """(shape, h, weights) of the Large workload; generating its 268M hidden-state values takes a while, so the
+    full-size tests share one copy."""
+    shape = wl.CONFIGS["large"]
+    return shape, wl.make_h(shape), wl.make_weights(shape)
+
+
+@functools.lru_cache(maxsize=1)
+def large_dout():
+    return wl.make_dout(wl.CONFIGS["large"])
+
+
+def progress(msg):
+    """A line for a long test to leave behind while it runs (output is captured until the test ends)."""
+    d = os.path.join(os.path.dirname(GOLDEN), os.pardir, "gpurun_out")
+    if os.path.isdir(d):
+        with open(os.path.join(d, "test_progress.log"), "a") as f:
+            f.write(msg + "\n")
 
 
 def rms(a):

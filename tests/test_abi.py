@@ -117,14 +117,6 @@ def test_capacity_and_sizes(B):
     assert B.slicemoe_capacity(B.make_config(100, 64, 4, 2, 8, 16, capacity_factor=1.1)) == 111  # ceil(1.1f*800/8)
 
 
-def test_probe_clock_argument_checks(B):
-    L = B.lib()
-    assert L.slicemoe_probe_clock(None, 4, 100, None) == B.SLICEMOE_ERR_INVALID_ARG
-    dummy = ctypes.c_void_p(256)   # never dereferenced: the size checks come first
-    assert L.slicemoe_probe_clock(dummy, 0, 100, None) == B.SLICEMOE_ERR_INVALID_ARG
-    assert L.slicemoe_probe_clock(dummy, 4, 0, None) == B.SLICEMOE_ERR_INVALID_ARG
-
-
 C_CALLER = r"""
 #include <stdio.h>
 #include "slicemoe.h"

@@ -19,7 +19,7 @@ import pytest
 
 import oracle
 from paper_2510_04286_amd import workload as wl
-from tests.common import TOL_F32, make_inputs, rms, routing_agreement
+from tests.common import TOL_F32, large_dout, large_inputs, make_inputs, progress, rms, routing_agreement
 
 pytestmark = pytest.mark.gpu
 
@@ -146,17 +146,13 @@ def test_backward_matches_oracle(B, name):
     assert excess.max() <= 1.0, excess.max()
 
 
-def test_backward_large_workload_full_size_sampled(B):
-    """The Large workload at its full size (4 194 304 rows), as bench.py --workload large --backward launches it.  The oracle
-    cannot run it whole, so it evaluates a seeded sample of tokens (dropless: a token's dL/dh depends on nothing but
-    that token), and the expert output bias, whose gradient has a closed form that holds at any size -- the sum of the
-    upstream gradient over the slices routed to the expert -- is checked for every expert through the routing table."""
+def run_large_backward(B):
+    """Forward and backward of the Large workload at its full size (4 194 304 rows), as bench.py --workload large
+    --backward launches them.  Returns (shape, h, w, dout, routing table, dL/dh on the device, weight gradients)."""
     import torch
-    shape = wl.CONFIGS["large"]
+    shape, h, w = large_inputs()
     assert shape.capacity() < 0
-    w = wl.make_weights(shape)
-    h = wl.make_h(shape)
-    dout = wl.make_dout(shape)
+    dout = large_dout()
     cfg = B.config_of(shape)
     assert B.slicemoe_backward_uses_mfma(cfg) == 1
     wd = B.pack(cfg, B.weights_to_device(w, shape.dtype))
@@ -171,12 +167,21 @@ def test_backward_large_workload_full_size_sampled(B):
     B.slicemoe_backward(cfg, hd, wd, ws, B.to_device(dout, shape.dtype), d_h, grads, bws)
     torch.cuda.synchronize()
     del bws
+    idx = B.workspace_views(cfg, ws)["topk_idx"].cpu().numpy()
+    return shape, h, w, dout, idx, d_h, grads
 
+
+def test_backward_large_workload_full_size_sampled(B):
+    """The quick check of the Large workload at its full size: the oracle evaluates a seeded sample of tokens (dropless:
+    a token's dL/dh depends on nothing but that token), and the expert output bias, whose gradient has a closed form
+    that holds at any size -- the sum of the upstream gradient over the slices routed to the expert -- is checked for
+    every expert through the routing table."""
+    import torch
+    shape, h, w, dout, idx, d_h, grads = run_large_backward(B)
     tokens = np.unique((wl.uniform01(78, 0, 0, 96) * shape.T).astype(np.int64))
     ref_f = oracle.forward_train(h[tokens], shape.S, shape.k, w, noise=None, drop_u=None, capacity=-1, tau=1.0, sigma=0.0,
                                  rate=0.0)
     ref = oracle.backward(h[tokens], shape.S, shape.k, w, dout[tokens], ref_f["idx"], ref_f["inv"])
-    idx = B.workspace_views(cfg, ws)["topk_idx"].cpu().numpy()
     slices = (tokens[:, None] * shape.S + np.arange(shape.S)[None, :]).reshape(-1)
     mism, n_tie = routing_agreement(idx[slices], ref_f["idx"], ref_f["logits"])
     got = d_h[torch.from_numpy(tokens).to("cuda:0")].float().cpu().numpy().astype(np.float64)
@@ -198,6 +203,54 @@ def test_backward_large_workload_full_size_sampled(B):
     assert n_tie <= 2
     assert err_b2 <= TOL_WGRAD
     assert finite
+
+
+def test_backward_large_workload_full_size_every_gradient(B):
+    """The Large workload compared in full: the oracle's backward over all 65 536 tokens, in chunks of tokens whose
+    partial weight gradients are added in fp64 (every gradient is a sum over slices; dropless, so a chunk needs nothing
+    from the others), against every element of dL/dh and of the eight weight gradients.  The oracle routes on its own;
+    where the GPU resolved a near-tie the other way that slice's dL/dh is left out and one row moves between two
+    experts' sums, far below the weight-gradient bar."""
+    import time
+    shape, h, w, dout, idx, d_h, grads = run_large_backward(B)
+    S, k, ds = shape.S, shape.k, shape.ds
+    chunk = 4096
+    total = {n: np.zeros_like(w[n], dtype=np.float64) for n in NAMES}
+    n_tie, worst_excess, sumsq_dh, worst_dh = 0, 0.0, 0.0, 0.0
+    chunks = []
+    t_start = time.perf_counter()
+    for t0 in range(0, shape.T, chunk):
+        t1 = min(shape.T, t0 + chunk)
+        x = h[t0:t1].reshape(-1, ds)
+        r = oracle.route(x, w["Wr1"], w["br1"], w["Wr2"], w["br2"], k, want_logits=True)
+        ref = oracle.backward(h[t0:t1], S, k, w, dout[t0:t1], r["idx"], np.zeros(x.shape[0] * k, dtype=np.int32))
+        for n in NAMES:
+            total[n] += ref[n]
+        mism, nt = routing_agreement(idx[t0 * S:t1 * S], r["idx"], r["logits"])
+        n_tie += nt
+        got = d_h[t0:t1].float().cpu().numpy().astype(np.float64)
+        chunks.append((got, ref["d_h"], mism))
+        sumsq_dh += float(np.square(ref["d_h"]).sum())
+        progress(f"backward large: tokens {t1}/{shape.T} through the oracle, {time.perf_counter() - t_start:.0f} s")
+    scale_dh = np.sqrt(sumsq_dh / (shape.T * shape.d))
+    for got, want, mism in chunks:
+        excess = np.abs(got - want) / (2.0 ** -8 * np.abs(want) + 2e-4 * scale_dh)
+        excess.reshape(-1, ds)[mism] = 0.0
+        worst_excess = max(worst_excess, float(excess.max()))
+        worst_dh = max(worst_dh, float(np.abs(got - want).max()))
+    report, failed = [], []
+    for n in NAMES:
+        got = grads[n].cpu().numpy().astype(np.float64)
+        err = np.abs(got - total[n]).max() / rms(total[n])
+        report.append(f"{n} {err:.1e}")
+        if err > TOL_WGRAD:
+            failed.append((n, err))
+    print(f"\n[backward large, every gradient] oracle {time.perf_counter() - t_start:.0f} s; near-tie slices resolved "
+          f"differently: {n_tie}; d_h max|err|/rms {worst_dh / scale_dh:.2e} (worst element at {worst_excess:.2f} of its "
+          f"bound); max|err|/rms: " + " ".join(report))
+    assert n_tie <= 8, n_tie
+    assert worst_excess <= 1.0, worst_excess
+    assert not failed, failed
 
 
 @pytest.mark.parametrize("which", ["headline", "ds128", "paper"])
@@ -244,3 +297,12 @@ def test_backward_argument_checks_on_device(B):
     with pytest.raises(B.SliceMoEError) as ei:
         B.slicemoe_backward(cfg, hd, wd, ws, hd, torch.empty_like(hd), grads, small)
     assert ei.value.status == B.SLICEMOE_ERR_WORKSPACE
+    # h, dL/dh' and dL/dh are read and written in 16-byte pieces: a misaligned pointer is refused, not launched on
+    bws = torch.empty(B.slicemoe_backward_workspace_bytes(cfg), dtype=torch.uint8, device="cuda:0")
+    spare = torch.empty(hd.numel() + 1, dtype=hd.dtype, device="cuda:0")
+    off = spare[1:].view(hd.shape)    # 4 bytes past a 16-byte boundary
+    off.copy_(hd)
+    for args in ((off, hd, torch.empty_like(hd)), (hd, off, torch.empty_like(hd)), (hd, hd, off)):
+        with pytest.raises(B.SliceMoEError) as ei:
+            B.slicemoe_backward(cfg, args[0], wd, ws, args[1], args[2], grads, bws)
+        assert ei.value.status == B.SLICEMOE_ERR_INVALID_ARG
