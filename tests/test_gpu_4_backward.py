@@ -205,50 +205,77 @@ def test_backward_large_workload_full_size_sampled(B):
     assert finite
 
 
+NEAR_KINK = 1e-6
+
+
 def test_backward_large_workload_full_size_every_gradient(B):
     """The Large workload compared in full: the oracle's backward over all 65 536 tokens, in chunks of tokens whose
     partial weight gradients are added in fp64 (every gradient is a sum over slices; dropless, so a chunk needs nothing
-    from the others), against every element of dL/dh and of the eight weight gradients.  The oracle routes on its own;
-    where the GPU resolved a near-tie the other way that slice's dL/dh is left out and one row moves between two
-    experts' sums, far below the weight-gradient bar."""
+    from the others), against every element of dL/dh and of the eight weight gradients.
+
+    Two kinds of slices, a handful among 2 097 152, sit on a discontinuity of what is differentiated, and the fp32
+    arithmetic of the kernels may land on the other side of it than the oracle's fp64:
+      - near-ties of the routing (checked by the forward's rule: logit gap below 1e-6).  The routing is held fixed in the
+        backward, so the oracle is given the expert the GPU took for such a slice and everything is compared;
+      - near-kinks of the router's ReLU: a hidden unit of the router whose pre-activation is within 1e-6 of zero (the
+        rounding of an fp32 sum of 128 products; the units seen are below 2e-8) may be gated either way, which changes
+        that slice's dL/dh through the router path by one unit's term c * Wr1[:, unit], and the unit's entry of dbr1 and
+        column of dWr1 by c and c * x.  A slice over its dL/dh bound is accepted only if it has such a unit; these
+        are counted, reported and left out, and so are those units' entry of dbr1 and column of dWr1 (a term large
+        enough to show in dL/dh is 1e-3 of the RMS of these sums; one too small to show there is below 2e-5 of it, well
+        inside the bar).  Every other element of every gradient is compared."""
     import time
     shape, h, w, dout, idx, d_h, grads = run_large_backward(B)
     S, k, ds = shape.S, shape.k, shape.ds
+    Wr1, br1 = w["Wr1"].astype(np.float64), w["br1"].astype(np.float64)
     chunk = 4096
     total = {n: np.zeros_like(w[n], dtype=np.float64) for n in NAMES}
-    n_tie, worst_excess, sumsq_dh, worst_dh = 0, 0.0, 0.0, 0.0
+    n_tie, n_kink, sumsq_dh = 0, 0, 0.0
+    kink_units = set()
     chunks = []
     t_start = time.perf_counter()
     for t0 in range(0, shape.T, chunk):
         t1 = min(shape.T, t0 + chunk)
         x = h[t0:t1].reshape(-1, ds)
         r = oracle.route(x, w["Wr1"], w["br1"], w["Wr2"], w["br2"], k, want_logits=True)
-        ref = oracle.backward(h[t0:t1], S, k, w, dout[t0:t1], r["idx"], np.zeros(x.shape[0] * k, dtype=np.int32))
-        for n in NAMES:
-            total[n] += ref[n]
         mism, nt = routing_agreement(idx[t0 * S:t1 * S], r["idx"], r["logits"])
         n_tie += nt
-        got = d_h[t0:t1].float().cpu().numpy().astype(np.float64)
-        chunks.append((got, ref["d_h"], mism))
+        routed = np.where(mism[:, None], idx[t0 * S:t1 * S], r["idx"])    # near-ties as the GPU resolved them
+        ref = oracle.backward(h[t0:t1], S, k, w, dout[t0:t1], routed, np.zeros(x.shape[0] * k, dtype=np.int32))
+        for n in NAMES:
+            total[n] += ref[n]
+        chunks.append((t0, d_h[t0:t1].float().cpu().numpy().astype(np.float64), ref["d_h"]))
         sumsq_dh += float(np.square(ref["d_h"]).sum())
         progress(f"backward large: tokens {t1}/{shape.T} through the oracle, {time.perf_counter() - t_start:.0f} s")
     scale_dh = np.sqrt(sumsq_dh / (shape.T * shape.d))
-    for got, want, mism in chunks:
-        excess = np.abs(got - want) / (2.0 ** -8 * np.abs(want) + 2e-4 * scale_dh)
-        excess.reshape(-1, ds)[mism] = 0.0
+    worst_excess = 0.0
+    for t0, got, want in chunks:
+        excess = (np.abs(got - want) / (2.0 ** -8 * np.abs(want) + 2e-4 * scale_dh)).reshape(-1, ds)
+        over = np.nonzero(excess.max(axis=1) > 1.0)[0]
+        if over.size:
+            u = h[t0:t0 + got.shape[0]].reshape(-1, ds)[over].astype(np.float64) @ Wr1 + br1
+            kink = np.abs(u).min(axis=1) < NEAR_KINK
+            assert np.all(kink), (f"slice {t0 * S + over[~kink][0]} is {excess[over[~kink][0]].max():.1f} times over its "
+                                  f"dL/dh bound and has no router unit near its kink")
+            n_kink += int(over.size)
+            kink_units.update(int(v) for v in np.abs(u).argmin(axis=1))
+            excess[over] = 0.0
         worst_excess = max(worst_excess, float(excess.max()))
-        worst_dh = max(worst_dh, float(np.abs(got - want).max()))
     report, failed = [], []
     for n in NAMES:
         got = grads[n].cpu().numpy().astype(np.float64)
-        err = np.abs(got - total[n]).max() / rms(total[n])
+        diff = np.abs(got - total[n])
+        if n in ("Wr1", "br1") and kink_units:
+            diff[..., sorted(kink_units)] = 0.0
+        err = diff.max() / rms(total[n])
         report.append(f"{n} {err:.1e}")
         if err > TOL_WGRAD:
             failed.append((n, err))
     print(f"\n[backward large, every gradient] oracle {time.perf_counter() - t_start:.0f} s; near-tie slices resolved "
-          f"differently: {n_tie}; d_h max|err|/rms {worst_dh / scale_dh:.2e} (worst element at {worst_excess:.2f} of its "
-          f"bound); max|err|/rms: " + " ".join(report))
+          f"differently: {n_tie}; near-kink slices left out of dL/dh: {n_kink} (router units {sorted(kink_units)}); dL/dh worst element at {worst_excess:.2f} "
+          f"of its bound; max|err|/rms: " + " ".join(report))
     assert n_tie <= 8, n_tie
+    assert n_kink <= 32, n_kink
     assert worst_excess <= 1.0, worst_excess
     assert not failed, failed
 
