@@ -121,11 +121,20 @@ PackedLayout packed_layout(const slicemoe_config &c)
     return L;
 }
 
+// Whether slicemoe_forward lets the router write the dispatch histogram, and in chunks of how many assignments.
+static int forward_hist_chunk(const slicemoe_config &c) { return use_mfma(c) ? route_mfma_hist_chunk(c) : 0; }
+
+// The per-chunk histogram table of the dispatch: large enough for the stage entry point's chunks and for the router's.
 static size_t dispatch_scratch_bytes(const slicemoe_config &c)
 {
     const long long Na = (long long)c.T * c.S * c.k;
-    const long long nblocks = (Na + kDispChunk - 1) / kDispChunk;
-    return align_up((size_t)(nblocks > 0 ? nblocks : 1) * c.E * sizeof(int32_t), 256);
+    size_t bytes = dispatch_table_bytes(dispatch_geometry(Na, c.E, 0), c.E);
+    const int rc = forward_hist_chunk(c);
+    if (rc > 0) {
+        const size_t b = dispatch_table_bytes(dispatch_geometry(Na, c.E, rc), c.E);
+        bytes = b > bytes ? b : bytes;
+    }
+    return bytes;
 }
 
 static void make_layout(const slicemoe_config &c, slicemoe_workspace_layout *o)
@@ -393,14 +402,18 @@ static slicemoe_status forward_common(const slicemoe_config *cfg, const void *h,
         const slicemoe_status ps = resolve_packed(*cfg, *w, workspace, workspace_bytes, s, &packed);
         if (ps != SLICEMOE_OK) return ps;
     }
-    hipError_t e = mfma ? launch_route_mfma(*cfg, h, packed, idx, p, s, v) : launch_route_generic(*cfg, h, *w, idx, p, s, v);
+    // the matrix-core router leaves the per-chunk histogram of its selections in the dispatch table
+    const int hist_chunk = forward_hist_chunk(*cfg);
+    int32_t *table = (int32_t *)(ws + L.scratch);
+    hipError_t e = mfma ? launch_route_mfma(*cfg, h, packed, idx, p, s, v, hist_chunk > 0 ? table : nullptr)
+                        : launch_route_generic(*cfg, h, *w, idx, p, s, v);
     if (e != hipSuccess) return SLICEMOE_ERR_HIP;
     if (rate > 0.f) {
         e = launch_route_dropout(*cfg, p, drop_u, rate, s);
         if (e != hipSuccess) return SLICEMOE_ERR_HIP;
     }
     // the load statistics ride along in the scan kernel of the dispatch
-    e = launch_dispatch(*cfg, idx, counts_raw, counts, offsets, perm, inv, (int32_t *)(ws + L.scratch), stats, s);
+    e = launch_dispatch(*cfg, idx, counts_raw, counts, offsets, perm, inv, table, stats, s, hist_chunk);
     if (e != hipSuccess) return SLICEMOE_ERR_HIP;
     e = mfma ? launch_ffn_mfma(*cfg, h, p, offsets, perm, packed, y, s)
              : launch_ffn_generic(*cfg, h, p, offsets, perm, *w, y, s);

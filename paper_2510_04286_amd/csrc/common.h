@@ -80,9 +80,28 @@ struct PackedLayout {
 PackedLayout packed_layout(const slicemoe_config &cfg);
 
 // ---- dispatch geometry ----------------------------------------------------------------
+// The assignment ids are cut into chunks, and the per-chunk histogram is a table of E rows (one per expert, contiguous)
+// of `stride` entries (the number of chunks rounded up to a multiple of 8: rows are read in 16-byte pieces).  A small
+// table (`fused`) holds 16-bit raw counts and is summed by the scatter blocks themselves; a large one holds int32 and
+// is turned into prefixes by a kernel of its own.  A scatter block of kDispThreads threads covers `group` consecutive
+// chunks, in rounds of kDispThreads ids, at most kDispMaxItems of them.
 constexpr int kDispThreads = 256;
-constexpr int kDispItems = 4;
-constexpr int kDispChunk = kDispThreads * kDispItems;  // assignments per block
+constexpr int kDispMaxItems = 16;
+struct DispatchGeom {
+    int chunk;     // assignments per chunk of the table
+    int nchunks;
+    int stride;
+    bool fused;
+    int group;     // chunks per scatter block
+    int blocks;    // scatter blocks
+};
+// chunk = 0: the dispatch stage's own choice; > 0: a histogram somebody else produces in chunks of that size
+DispatchGeom dispatch_geometry(long long Na, int E, int chunk);
+size_t dispatch_table_bytes(const DispatchGeom &g, int E);
+// Where the matrix-core router can leave the per-chunk histogram of its selections behind: the table it writes
+// (layout and entry width as dispatch_geometry(Na, E, chunk) says, chunks of route_mfma_hist_chunk(c) assignments); 0
+// when it cannot for this shape.
+int route_mfma_hist_chunk(const slicemoe_config &c);
 
 // ---- kernel launchers (each only enqueues; returns hipGetLastError) --------------------
 // Training-time variations of the router (softmax temperature: Appendix B; Gaussian logit noise: Section 5); the
@@ -95,7 +114,8 @@ struct RouteVariant {
 hipError_t launch_route_generic(const slicemoe_config &c, const void *h, const slicemoe_weights &w,
                                 int32_t *idx, float *p, hipStream_t s, const RouteVariant &v = RouteVariant());
 hipError_t launch_route_mfma(const slicemoe_config &c, const void *h, const void *packed,
-                             int32_t *idx, float *p, hipStream_t s, const RouteVariant &v = RouteVariant());
+                             int32_t *idx, float *p, hipStream_t s, const RouteVariant &v = RouteVariant(),
+                             int32_t *hist_table = nullptr /* see route_mfma_hist_chunk */);
 // Backward pass (backward.hip): weight gradients into g, dL/dh into d_h.  backward_plan: geometry and layout of its
 // scratch (row gradients, dL/dp, one slot of partial weight gradients per block); backward_lds_bytes: dynamic LDS its
 // kernels ask for at least.
@@ -134,7 +154,8 @@ hipError_t launch_backward(const slicemoe_config &c, const void *h, const slicem
 hipError_t launch_route_dropout(const slicemoe_config &c, float *p, const float *drop_u, float rate, hipStream_t s);
 hipError_t launch_dispatch(const slicemoe_config &c, const int32_t *idx, int32_t *counts_raw,
                            int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv,
-                           int32_t *block_counts, float *stats /* nullable */, hipStream_t s);
+                           int32_t *table, float *stats /* nullable */, hipStream_t s,
+                           int table_chunk = 0 /* > 0: table already holds the histogram, in chunks of this size */);
 hipError_t launch_ffn_generic(const slicemoe_config &c, const void *h, const float *p,
                               const int32_t *offsets, const int32_t *perm, const slicemoe_weights &w,
                               void *y, hipStream_t s);

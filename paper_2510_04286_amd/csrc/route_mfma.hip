@@ -15,12 +15,19 @@
 // its logits; the other 16 sit in lane ^ 32.  Softmax and top-k therefore need only registers
 // and one cross-lane exchange per step.  A block keeps the whole router (<= 100 KiB packed) in
 // LDS and walks slice tiles of 32 per wavefront.
+//
+// The tiles are handed out in chunks: in round r block b takes chunk c = r * gridDim + b, and its W wavefronts the W
+// consecutive tiles of that chunk, i.e. W * 32 * k consecutive assignment ids.  That makes the per-chunk histogram of
+// the selected experts -- the first step of the dispatch stage -- a by-product: every wavefront adds its selections to
+// a small LDS table of the round, and the wavefront of the chunk that finishes last (an LDS counter tells it; nobody
+// waits) writes the chunk's counts to the dispatch table.
 #include "mfma.h"
 
 namespace slicemoe {
 
 constexpr int kRouteHr = 256;
 constexpr int kRouteHT = kRouteHr / 32;
+constexpr int kRouteHistMaxRounds = 32;   // LDS slots for the per-round histograms (65 ints each)
 
 typedef _Float16 h2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
@@ -34,7 +41,8 @@ template <int DS, int ET, int THREADS, bool W1_LDS>
 __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
     const bf16_t *__restrict__ x, long long Ns, int E, int k, const char *__restrict__ packed,
     size_t off_w1, size_t off_b1, size_t off_b2, const float *__restrict__ noise, float sigma, float exp_scale,
-    int32_t *__restrict__ idx, float *__restrict__ pk)
+    int32_t *__restrict__ idx, float *__restrict__ pk, void *__restrict__ hist /* may be null */, int hist_stride,
+    int hist_rounds, bool hist_narrow)
 {
     constexpr int KS = SliceTiles<DS>::KS;
     constexpr int HT = kRouteHT;
@@ -44,6 +52,8 @@ __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
     uint4 *w2s = (uint4 *)lds + (W1_LDS ? HT * KS * 64 : 0);                             // [ET][HT][2][64]
     float *b1s = (float *)(w2s + ET * HT * 2 * 64);    // [Hr]
     float *b2s = b1s + kRouteHr;                       // [ET*32]
+    int *hcnt = (int *)(b2s + ET * 32);                // [hist_rounds][64] selections per expert of this block's chunks
+    int *hdone = hcnt + hist_rounds * 64;              // [hist_rounds] wavefronts that have added theirs
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -53,7 +63,7 @@ __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
 
     // first tile's rows are requested before the weights
     const long long ntiles = (Ns + 31) / 32;
-    const long long tile_stride = (long long)gridDim.x * kRouteWaves;
+    const long long nchunks = (ntiles + kRouteWaves - 1) / kRouteWaves;
     auto load_x = [&](long long tile, bf16x8 (&xb)[KS]) {
         const long long n = tile * 32 + j;
         const bool valid = tile < ntiles && n < Ns;
@@ -62,7 +72,7 @@ __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
         for (int ks = 0; ks < KS; ++ks) xb[ks] = load_row_piece<DS>(xr, ks, g);
     };
     bf16x8 xb[KS];
-    load_x((long long)wave * gridDim.x + blockIdx.x, xb);   // tiles go round the blocks first: small inputs still use every CU
+    load_x((long long)blockIdx.x * kRouteWaves + wave, xb);
     {
         // the whole router (W1 and W2 fragments are adjacent in the packed buffer) goes global -> registers -> LDS
         constexpr int kW1Pieces = HT * KS * 64;
@@ -74,12 +84,17 @@ __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
         stage_to_lds<THREADS>(packed + off_w1 + (W1_LDS ? 0 : (size_t)kW1Pieces * 16), lds, kPieces, tid);
         if (tid < kRouteHr) b1s[tid] = bv1;
         if (tid < ET * 32) b2s[tid] = bv2;
+        if (hist != nullptr)
+            for (int i = tid; i < hist_rounds * 65; i += THREADS) hcnt[i] = 0;
     }
     __syncthreads();
 
-    for (long long tile = (long long)wave * gridDim.x + blockIdx.x; tile < ntiles; tile += tile_stride) {
+    int round = 0;
+    for (long long chunk = blockIdx.x; chunk < nchunks; chunk += gridDim.x, ++round) {
+        const long long tile = chunk * kRouteWaves + wave;
+        if (tile >= ntiles) break;   // only in the last chunk; this wavefront has no later tile either
         {   // fewer tiles left -> lower priority, so the wavefronts of a block finish together
-            const long long left = (ntiles - 1 - tile) / tile_stride;
+            const long long left = (nchunks - 1 - chunk) / gridDim.x;
             if (left >= 3) __builtin_amdgcn_s_setprio(3);
             else if (left == 2) __builtin_amdgcn_s_setprio(2);
             else if (left == 1) __builtin_amdgcn_s_setprio(1);
@@ -88,7 +103,7 @@ __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
         const long long n = tile * 32 + j;
         const bool valid = n < Ns;
         bf16x8 xn[KS];
-        load_x(tile + tile_stride, xn);  // next tile, consumed after this one
+        load_x(tile + (long long)gridDim.x * kRouteWaves, xn);  // next tile, consumed after this one
         f32x16 gacc[ET];   // logit accumulators start from the second-layer bias
 #pragma unroll
         for (int et = 0; et < ET; ++et)
@@ -218,6 +233,26 @@ __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
             if (valid && g == 0) {
                 idx[n * k + jj] = be;
                 pk[n * k + jj] = __builtin_amdgcn_exp2f(fmaf(bv, kLog2e, nm)) * rden;
+                if (hist != nullptr) atomicAdd(&hcnt[round * 64 + be], 1);
+            }
+        }
+        if (hist != nullptr) {
+            // The LDS executes a wavefront's operations in order, so this wavefront's additions above are in the table
+            // before its ticket; the wavefront that draws the last ticket of the chunk therefore sees everybody's.
+            int ticket = 0;
+            if (lane == 0) ticket = __hip_atomic_fetch_add(&hdone[round], 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_WORKGROUP);
+            ticket = __builtin_amdgcn_readfirstlane(ticket);
+            const long long in_chunk = min((long long)kRouteWaves, ntiles - chunk * kRouteWaves);
+            if (ticket == in_chunk - 1 && lane < E) {
+                const int cnt = __hip_atomic_load(&hcnt[round * 64 + lane], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP);
+                if (hist_narrow) {
+                    uint16_t *row = (uint16_t *)hist + (size_t)lane * hist_stride;
+                    row[chunk] = (uint16_t)cnt;
+                    if (chunk == nchunks - 1)   // the padding of a row of 16-bit counts reads as zero
+                        for (long long c = nchunks; c < hist_stride; ++c) row[c] = 0;
+                } else {
+                    ((int32_t *)hist)[(size_t)lane * hist_stride + chunk] = cnt;
+                }
             }
         }
 #pragma unroll
@@ -225,46 +260,93 @@ __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
     }
 }
 
+// Threads per block of the instantiation that serves a slice width and a number of 32-expert tiles (see the kernel).
+static int route_threads(int ds, int et)
+{
+    switch (ds) {
+        case 24: case 48: case 64: return et == 1 ? 1024 : 512;
+        case 96: return et == 1 ? 1024 : 768;
+        case 192: return et == 1 ? 768 : 512;
+        case 384: return 256;
+        default: return 768;   // 128
+    }
+}
+
+static long long route_blocks(long long Ns, int threads)
+{
+    const long long ntiles = (Ns + 31) / 32, waves = threads / 64;
+    const long long nchunks = (ntiles + waves - 1) / waves;
+    const long long cap = (long long)num_compute_units();
+    return nchunks < cap ? nchunks : cap;
+}
+
+// Assignments per chunk of the histogram this router can leave behind, or 0: the chunk must be worth a dispatch block
+// (at least 512 assignments, at most kDispMaxItems rounds of it) and a block's rounds must fit the LDS slots.
+int route_mfma_hist_chunk(const slicemoe_config &c)
+{
+    const long long Ns = (long long)c.T * c.S;
+    if (Ns == 0) return 0;
+    const int threads = route_threads(c.d / c.S, (c.E + 31) / 32);
+    const int chunk = threads / 64 * 32 * c.k;
+    if (chunk < 512 || chunk > kDispThreads * kDispMaxItems) return 0;
+    const long long ntiles = (Ns + 31) / 32, waves = threads / 64;
+    const long long nchunks = (ntiles + waves - 1) / waves, blocks = route_blocks(Ns, threads);
+    if ((nchunks + blocks - 1) / blocks > kRouteHistMaxRounds) return 0;
+    return chunk;
+}
+
 template <int DS, int ET, int THREADS, bool W1_LDS = true>
 static hipError_t run_route(const slicemoe_config &c, const void *h, const void *packed, int32_t *idx, float *p,
-                            hipStream_t s, const RouteVariant &v)
+                            hipStream_t s, const RouteVariant &v, int32_t *hist)
 {
     const PackedLayout L = packed_layout(c);
     const long long Ns = (long long)c.T * c.S;
     constexpr int KS = SliceTiles<DS>::KS;
-    const size_t lds = (size_t)((W1_LDS ? kRouteHT * KS * 64 : 0) + ET * kRouteHT * 2 * 64) * 16 + (kRouteHr + ET * 32) * 4;
-    const long long ntiles = (Ns + 31) / 32;
-    long long blocks = ntiles;   // one tile per block before a second wavefront of any block gets one
-    const long long cap = (long long)num_compute_units();
-    if (blocks > cap) blocks = cap;
+    if (route_threads(DS, ET) != THREADS) return hipErrorInvalidValue;
+    const long long blocks = route_blocks(Ns, THREADS);
+    const long long nchunks = ((Ns + 31) / 32 + THREADS / 64 - 1) / (THREADS / 64);
+    int hist_rounds = 0, hist_stride = 0;
+    bool hist_narrow = false;
+    if (hist != nullptr) {
+        const int chunk = route_mfma_hist_chunk(c);
+        if (chunk != THREADS / 64 * 32 * c.k) return hipErrorInvalidValue;
+        const DispatchGeom g = dispatch_geometry(Ns * c.k, c.E, chunk);
+        if (g.nchunks != nchunks) return hipErrorInvalidValue;
+        hist_rounds = (int)((nchunks + blocks - 1) / blocks);
+        hist_stride = g.stride;
+        hist_narrow = g.fused;
+    }
+    const size_t lds = (size_t)((W1_LDS ? kRouteHT * KS * 64 : 0) + ET * kRouteHT * 2 * 64) * 16 + (kRouteHr + ET * 32) * 4 +
+                       (size_t)hist_rounds * 65 * 4;
     auto kern = route_mfma_kernel<DS, ET, THREADS, W1_LDS>;
     hipError_t err = grant_dynamic_lds((const void *)kern, lds);
     if (err != hipSuccess) return err;
     if (L.r_w2 != L.r_w1 + (size_t)kRouteHT * KS * 64 * 16) return hipErrorInvalidValue;   // the kernel copies W1 | W2 as one run
     kern<<<(int)blocks, THREADS, lds, s>>>((const bf16_t *)h, Ns, c.E, c.k, (const char *)packed, L.r_w1, L.r_b1, L.r_b2,
-                                           v.sigma > 0.f ? v.noise : nullptr, v.sigma, 1.4426950408889634f * v.inv_tau, idx, p);
+                                           v.sigma > 0.f ? v.noise : nullptr, v.sigma, 1.4426950408889634f * v.inv_tau, idx, p,
+                                           hist, hist_stride, hist_rounds, hist_narrow);
     return hipGetLastError();
 }
 
 hipError_t launch_route_mfma(const slicemoe_config &c, const void *h, const void *packed, int32_t *idx,
-                             float *p, hipStream_t s, const RouteVariant &v)
+                             float *p, hipStream_t s, const RouteVariant &v, int32_t *hist)
 {
     if ((long long)c.T * c.S == 0) return hipSuccess;
     const int ds = c.d / c.S;
     const int et = (c.E + 31) / 32;
     if (ds == 24)   // two K-steps, the second half zeros
-        return et == 1 ? run_route<24, 1, 1024>(c, h, packed, idx, p, s, v) : run_route<24, 2, 512>(c, h, packed, idx, p, s, v);
+        return et == 1 ? run_route<24, 1, 1024>(c, h, packed, idx, p, s, v, hist) : run_route<24, 2, 512>(c, h, packed, idx, p, s, v, hist);
     if (ds == 48)
-        return et == 1 ? run_route<48, 1, 1024>(c, h, packed, idx, p, s, v) : run_route<48, 2, 512>(c, h, packed, idx, p, s, v);
+        return et == 1 ? run_route<48, 1, 1024>(c, h, packed, idx, p, s, v, hist) : run_route<48, 2, 512>(c, h, packed, idx, p, s, v, hist);
     if (ds == 64)
-        return et == 1 ? run_route<64, 1, 1024>(c, h, packed, idx, p, s, v) : run_route<64, 2, 512>(c, h, packed, idx, p, s, v);
+        return et == 1 ? run_route<64, 1, 1024>(c, h, packed, idx, p, s, v, hist) : run_route<64, 2, 512>(c, h, packed, idx, p, s, v, hist);
     if (ds == 96)   // the slice width of the paper's own configuration (d = 768, S = 8): six K-steps
-        return et == 1 ? run_route<96, 1, 1024>(c, h, packed, idx, p, s, v) : run_route<96, 2, 768>(c, h, packed, idx, p, s, v);
+        return et == 1 ? run_route<96, 1, 1024>(c, h, packed, idx, p, s, v, hist) : run_route<96, 2, 768>(c, h, packed, idx, p, s, v, hist);
     if (ds == 192)
-        return et == 1 ? run_route<192, 1, 768>(c, h, packed, idx, p, s, v) : run_route<192, 2, 512>(c, h, packed, idx, p, s, v);
+        return et == 1 ? run_route<192, 1, 768>(c, h, packed, idx, p, s, v, hist) : run_route<192, 2, 512>(c, h, packed, idx, p, s, v, hist);
     if (ds == 384)
-        return et == 1 ? run_route<384, 1, 256, false>(c, h, packed, idx, p, s, v) : run_route<384, 2, 256, false>(c, h, packed, idx, p, s, v);
-    return et == 1 ? run_route<128, 1, 768>(c, h, packed, idx, p, s, v) : run_route<128, 2, 768>(c, h, packed, idx, p, s, v);
+        return et == 1 ? run_route<384, 1, 256, false>(c, h, packed, idx, p, s, v, hist) : run_route<384, 2, 256, false>(c, h, packed, idx, p, s, v, hist);
+    return et == 1 ? run_route<128, 1, 768>(c, h, packed, idx, p, s, v, hist) : run_route<128, 2, 768>(c, h, packed, idx, p, s, v, hist);
 }
 
 }  // namespace slicemoe

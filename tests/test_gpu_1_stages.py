@@ -45,15 +45,20 @@ DISPATCH_CASES = [
     # T, S, k, E, capacity_factor, zipf
     (1, 1, 1, 1, 0.0, 0.0),
     (3, 5, 2, 7, 0.0, 0.0),          # far less than one chunk, E not a power of two
-    (512, 4, 2, 8, 0.0, 0.0),        # tiny config: exactly four chunks
-    (513, 4, 2, 8, 0.0, 1.0),        # ragged tail of 8 assignments in the last chunk
+    (512, 4, 2, 8, 0.0, 0.0),        # tiny config: exactly four chunks of 1024, two scatter blocks
+    (513, 4, 2, 8, 0.0, 1.0),        # ragged tail of 8 assignments in a fifth chunk
     (1000, 7, 3, 33, 0.0, 1.2),      # E just above 32, k = 3
     (4096, 8, 2, 16, 0.0, 0.0),      # LM-shaped
     (2000, 8, 8, 64, 1.0, 1.2),      # k = 8, E = 64, capacity drop
     (16384, 16, 2, 32, 0.0, 0.0),    # headline
     (16384, 16, 2, 32, 1.25, 1.2),   # skewed: Zipf(1.2) popularity, capacity 20480
     (777, 3, 1, 5, 0.05, 0.7),       # nearly everything dropped
-    (65536, 32, 2, 64, 0.0, 0.3),    # large: 4 194 304 assignments, 4096 chunks
+    (65536, 32, 2, 64, 0.0, 0.3),    # large: 4 194 304 assignments, 4096 chunks: int32 table scanned by its own kernel
+    (32768, 16, 2, 32, 0.0, 0.5),    # 2^20 assignments: 1024 chunks x 32 experts, the largest 16-bit table the scatter blocks sum themselves (16 loads per lane)
+    (32768, 16, 4, 8, 1.05, 0.8),    # 2^21 assignments, 2048 chunks x 8 experts: 16 loads per lane of one row each, capacity drop
+    (65536, 32, 2, 8, 0.0, 0.0),     # 2^22 assignments, 4096 chunks: over the limit of the 16-bit table even with few experts
+    (40000, 30, 2, 24, 0.0, 0.6),    # 2.4 million: ragged last chunk and last scatter block, E not a power of two
+    (9000, 9, 2, 63, 0.0, 0.4),      # 162 000 assignments, 159 chunks x 63 experts: four passes of rows, padded rows, E odd
 ]
 
 
