@@ -184,6 +184,21 @@ slicemoe_status slicemoe_dispatch(const slicemoe_config *cfg, const int32_t *top
                                   void *workspace, size_t workspace_bytes, slicemoe_stream_t stream);
 
 /*
+ * slicemoe_dispatch for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation.  Same arguments, outputs and bits as
+ * slicemoe_dispatch, minus the workspace: the per-chunk histogram table lives in a fixed 1 MiB array inside the
+ * library's device image (one copy per GPU, held until the process ends).  The call allocates and frees nothing.
+ *   Limit: the table, E rows of ceil(T*S*k / chunk) entries (rounded up to a multiple of 8; chunk = 1024 assignments
+ *   below 2^19 of them, 2048 below 2^21, 4096 from there on), must fit 262144 entries: any config with
+ *   T*S*k <= 16 777 216.  Beyond it the call returns SLICEMOE_ERR_WORKSPACE and launches nothing.
+ *   All calls on one GPU share the array: calls that overlap in time on one GPU (different streams) race on it.
+ *   Nothing in it has to be cleared between calls; it keeps the last call's table.
+ */
+slicemoe_status slicemoe_dispatch_noalloc(const slicemoe_config *cfg, const int32_t *topk_idx,
+                                          int32_t *counts_raw, int32_t *counts, int32_t *offsets,
+                                          int32_t *perm, int32_t *inv, slicemoe_stream_t stream);
+
+/*
  * Expert FFN on the stacked batch (Eq. 1, Section 3.1 expert, Section 3.4 grouping): for every
  * kept row r < offsets[E], with a = perm[r], n = a / k and e the expert whose range holds r,
  *   y[r, :] = GELU((topk_p[a] * x[n, :]) W1[e] + b1[e]) W2[e] + b2[e]

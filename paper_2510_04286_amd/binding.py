@@ -30,7 +30,7 @@ EXPORTS = [
     "slicemoe_pack_weights", "slicemoe_route", "slicemoe_dispatch", "slicemoe_expert_ffn",
     "slicemoe_combine", "slicemoe_load_stats", "slicemoe_forward",
     "slicemoe_route_train", "slicemoe_forward_train", "slicemoe_backward_workspace_bytes", "slicemoe_backward",
-    "slicemoe_backward_uses_mfma",
+    "slicemoe_backward_uses_mfma", "slicemoe_dispatch_noalloc",
 ]
 
 
@@ -104,6 +104,8 @@ def lib() -> ctypes.CDLL:
         L.slicemoe_route_train.argtypes = [cfgp, vp, wp, tpp, vp, vp, vp, vp, vp, st, vp]
         L.slicemoe_forward_train.restype = ctypes.c_int
         L.slicemoe_forward_train.argtypes = [cfgp, vp, wp, tpp, vp, vp, vp, vp, st, vp]
+        L.slicemoe_dispatch_noalloc.restype = ctypes.c_int
+        L.slicemoe_dispatch_noalloc.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp]
         L.slicemoe_backward_uses_mfma.restype = ctypes.c_int
         L.slicemoe_backward_uses_mfma.argtypes = [cfgp]
         L.slicemoe_backward_workspace_bytes.restype = ctypes.c_size_t
@@ -237,6 +239,16 @@ def slicemoe_dispatch(cfg, topk_idx, counts_raw, counts, offsets, perm, inv, wor
                                    _ptr(offsets, torch.int32, cfg.E + 1, "offsets"),
                                    _ptr(perm, torch.int32, Na, "perm"), _ptr(inv, torch.int32, Na, "inv"),
                                    wsp, wsb, _stream(stream)), "slicemoe_dispatch")
+
+
+def slicemoe_dispatch_noalloc(cfg, topk_idx, counts_raw, counts, offsets, perm, inv, stream=None):
+    Na = cfg.T * cfg.S * cfg.k
+    _check(lib().slicemoe_dispatch_noalloc(ctypes.byref(cfg), _ptr(topk_idx, torch.int32, Na, "topk_idx"),
+                                           _ptr(counts_raw, torch.int32, cfg.E, "counts_raw"),
+                                           _ptr(counts, torch.int32, cfg.E, "counts"),
+                                           _ptr(offsets, torch.int32, cfg.E + 1, "offsets"),
+                                           _ptr(perm, torch.int32, Na, "perm"), _ptr(inv, torch.int32, Na, "inv"),
+                                           _stream(stream)), "slicemoe_dispatch_noalloc")
 
 
 def slicemoe_expert_ffn(cfg, h, topk_p, offsets, perm, w, y, workspace=None, stream=None):

@@ -333,6 +333,19 @@ slicemoe_status slicemoe_dispatch(const slicemoe_config *cfg, const int32_t *top
                : SLICEMOE_ERR_HIP;
 }
 
+slicemoe_status slicemoe_dispatch_noalloc(const slicemoe_config *cfg, const int32_t *topk_idx, int32_t *counts_raw,
+                                          int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv,
+                                          slicemoe_stream_t stream)
+{
+    const slicemoe_status st = validate(cfg);
+    if (st != SLICEMOE_OK) return st;
+    if (!topk_idx || !counts_raw || !counts || !offsets || !perm || !inv) return SLICEMOE_ERR_INVALID_ARG;
+    if (!dispatch_static_fits(*cfg)) return SLICEMOE_ERR_WORKSPACE;
+    return launch_dispatch_static(*cfg, topk_idx, counts_raw, counts, offsets, perm, inv, (hipStream_t)stream) == hipSuccess
+               ? SLICEMOE_OK
+               : SLICEMOE_ERR_HIP;
+}
+
 slicemoe_status slicemoe_expert_ffn(const slicemoe_config *cfg, const void *h, const float *topk_p,
                                     const int32_t *offsets, const int32_t *perm, const slicemoe_weights *w, void *y,
                                     void *workspace, size_t workspace_bytes, slicemoe_stream_t stream)

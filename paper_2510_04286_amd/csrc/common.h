@@ -156,6 +156,11 @@ hipError_t launch_dispatch(const slicemoe_config &c, const int32_t *idx, int32_t
                            int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv,
                            int32_t *table, float *stats /* nullable */, hipStream_t s,
                            int table_chunk = 0 /* > 0: table already holds the histogram, in chunks of this size */);
+// The same dispatch with its table in the library's own fixed device array (for callers that cannot allocate);
+// dispatch_static_fits: whether the table of this config fits that array.
+bool dispatch_static_fits(const slicemoe_config &c);
+hipError_t launch_dispatch_static(const slicemoe_config &c, const int32_t *idx, int32_t *counts_raw, int32_t *counts,
+                                  int32_t *offsets, int32_t *perm, int32_t *inv, hipStream_t s);
 hipError_t launch_ffn_generic(const slicemoe_config &c, const void *h, const float *p,
                               const int32_t *offsets, const int32_t *perm, const slicemoe_weights &w,
                               void *y, hipStream_t s);

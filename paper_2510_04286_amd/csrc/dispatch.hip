@@ -19,6 +19,8 @@
 // Stability needs ranks in ascending a.  A block walks its chunk in rounds of 256 consecutive ids; inside a wavefront
 // the rank among equal experts comes from ballots (one per bit of the expert id gives every lane the mask of lanes
 // holding the same expert), across wavefronts and rounds from a small LDS table scanned in (round, wavefront) order.
+#include <mutex>
+
 #include "common.h"
 
 namespace slicemoe {
@@ -486,6 +488,52 @@ hipError_t launch_dispatch(const slicemoe_config &c, const int32_t *idx, int32_t
     run_scatter<false>(g.blocks + ((stats || g.blocks == 0) ? 1 : 0), s, idx, (int)Na, c.E, nbits, cap, g, table, offsets, perm,
                        inv, counts_raw, counts, stats);
     return hipGetLastError();
+}
+
+// ---- the dispatch for callers that cannot allocate -------------------------------------------
+// Same kernels, with the per-chunk histogram table in a fixed array of the library's own device image instead of a
+// caller's workspace.  Every GPU holds its own copy of the array at its own address: the address is looked up once
+// per device, with that device current, and from then on that pointer -- never the array's name, which in host code
+// is only a handle for the lookup -- is what the kernels are given.
+constexpr size_t kStaticTableInts = 262144;   // 1 MiB
+static __device__ __align__(256) int32_t scratch[kStaticTableInts];
+
+static hipError_t static_table(int32_t **out)
+{
+    static std::mutex mu;
+    static int32_t *ptr[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (ptr[dev] == nullptr) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (p == nullptr) return hipErrorInvalidSymbol;
+        ptr[dev] = (int32_t *)p;
+    }
+    *out = ptr[dev];
+    return hipSuccess;
+}
+
+bool dispatch_static_fits(const slicemoe_config &c)
+{
+    const DispatchGeom g = dispatch_geometry((long long)c.T * c.S * c.k, c.E, 0);
+    return (size_t)g.stride * c.E <= kStaticTableInts;
+}
+
+// The table is written in full by the histogram kernel before anything reads it, so nothing has to be cleared; calls
+// that overlap on one GPU (two streams) would share it and race.
+hipError_t launch_dispatch_static(const slicemoe_config &c, const int32_t *idx, int32_t *counts_raw, int32_t *counts,
+                                  int32_t *offsets, int32_t *perm, int32_t *inv, hipStream_t s)
+{
+    if (!dispatch_static_fits(c)) return hipErrorInvalidValue;
+    int32_t *table = nullptr;
+    const hipError_t e = static_table(&table);
+    if (e != hipSuccess) return e;
+    return launch_dispatch(c, idx, counts_raw, counts, offsets, perm, inv, table, nullptr, s, 0);
 }
 
 // ---- load statistics on their own (Eq. 2 statistic, ELE of Section 4) ---------------------
