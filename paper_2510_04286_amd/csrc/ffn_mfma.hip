@@ -28,13 +28,16 @@
 // roundings are replayed on the CPU in tests/test_gelu_poly.py).
 // Hidden activations beyond +-65504 / kappa would overflow fp16.
 //
-// Two variants:
-//   resident  a whole expert (W1, W2, biases) fits in LDS (ds = 64, He <= 256).  One block of 16
-//             wavefronts per CU (four per SIMD, so that one wavefront's matrix work overlaps
-//             another's vector work); stacked rows are split evenly over the blocks regardless of
-//             expert boundaries; a block re-stages weights only when its range crosses into
-//             another expert.  Wavefront priority follows the number of units a wavefront still
-//             has to do, which keeps the 16 wavefronts finishing together.
+// Three variants:
+//   pipelined a whole expert fits in LDS twice over (ds = 64, He <= 256: the benchmark shapes).  One block of
+//             eight wavefronts per CU holds the images of up to two experts; stacked rows are split evenly over
+//             the blocks regardless of expert boundaries; inside a wavefront the stages of consecutive hidden
+//             tiles overlap in time (see the kernel).
+//   resident  the same row split with one expert image and a plain tile loop, for the slice widths of the paper's
+//             own layer (24, 48, 96), whose tile counts or register needs do not fit the pipelined form: 12 or 16
+//             wavefronts, one wavefront's matrix work overlapping another's vector work; a block re-stages
+//             weights when its range crosses into another expert; wavefront priority follows the number of units
+//             a wavefront still has to do, which keeps them finishing together.
 //   streamed  larger experts (ds = 128, He = 512: 256 KiB; ds = 96, He = 384 of the paper's own shape:
 //             144 KiB): a block walks tiles of one expert and streams the weights through LDS in chunks
 //             of hidden tiles, per row tile.
@@ -180,43 +183,50 @@ __device__ __forceinline__ uint32_t pack_half2(float a, float b)
 // y rows as fp16.  Per output tile a lane holds features 8q + 4g + (0..3) of its own row, i.e. half
 // of each 16-byte piece; lanes j and j + 32 trade halves (v_permlane32_swap) so that lane (j, g)
 // ends up with the whole pieces q = 2*qp + g and stores them with one 16-byte write each.
-template <int DS, int NSUB>
+// One call stores the two pieces 2*qp, 2*qp + 1 of output tile ot of the row (row < 0: nothing is written); BIAS: the
+// second-layer bias is added here (it is already in the accumulators when they started from it).
+template <int DS, bool BIAS>
+__device__ __forceinline__ void store_row_pieces(int row, const f32x16 &acc, int ot, int qp, const float *__restrict__ b2s,
+                                                 half_t *__restrict__ y, int g)
+{
+    if (ot * 4 + 2 * qp >= SliceTiles<DS>::P) return;   // padding columns of the last tile
+    half_t *yr = y + (size_t)(row < 0 ? 0 : row) * DS;
+    uint32_t lo[2], hi[2];  // lo: piece q = 2qp, hi: piece q = 2qp + 1 (this lane's half of each)
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const int q = 2 * qp + t;
+        f32x4 bb = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (BIAS) bb = *(const f32x4 *)(b2s + ot * 32 + 8 * q + 4 * g);
+        const uint32_t d0 = pack_half2(acc[4 * q + 0] + bb[0], acc[4 * q + 1] + bb[1]);
+        const uint32_t d1 = pack_half2(acc[4 * q + 2] + bb[2], acc[4 * q + 3] + bb[3]);
+        if (t == 0) {
+            lo[0] = d0;
+            lo[1] = d1;
+        } else {
+            hi[0] = d0;
+            hi[1] = d1;
+        }
+    }
+    // after the swaps: lanes 0-31 hold (own lo, partner's lo) = piece 2qp; lanes 32-63 hold
+    // (partner's hi, own hi) = piece 2qp + 1, both in feature order
+    const auto s0 = __builtin_amdgcn_permlane32_swap(lo[0], hi[0], false, false);
+    const auto s1 = __builtin_amdgcn_permlane32_swap(lo[1], hi[1], false, false);
+    if (row >= 0 && ot * 4 + 2 * qp + g < SliceTiles<DS>::P) {
+        const uint4 v = make_uint4(s0[0], s1[0], s0[1], s1[1]);
+        *(uint4 *)(yr + ot * 32 + 8 * (2 * qp + g)) = v;
+    }
+}
+
+template <int DS, int NSUB, bool BIAS = true>
 __device__ __forceinline__ void store_rows(const RowUnit<DS, NSUB> &u, const f32x16 (&yacc)[NSUB][SliceTiles<DS>::OT],
                                            const float *__restrict__ b2s, half_t *__restrict__ y, int g)
 {
 #pragma unroll
-    for (int sub = 0; sub < NSUB; ++sub) {
-        half_t *yr = y + (size_t)(u.row[sub] < 0 ? 0 : u.row[sub]) * DS;
+    for (int sub = 0; sub < NSUB; ++sub)
 #pragma unroll
         for (int ot = 0; ot < SliceTiles<DS>::OT; ++ot)
 #pragma unroll
-            for (int qp = 0; qp < 2; ++qp) {
-                if (ot * 4 + 2 * qp >= SliceTiles<DS>::P) continue;   // padding columns of the last tile
-                uint32_t lo[2], hi[2];  // lo: piece q = 2qp, hi: piece q = 2qp + 1 (this lane's half of each)
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    const int q = 2 * qp + t;
-                    const f32x4 bb = *(const f32x4 *)(b2s + ot * 32 + 8 * q + 4 * g);
-                    const uint32_t d0 = pack_half2(yacc[sub][ot][4 * q + 0] + bb[0], yacc[sub][ot][4 * q + 1] + bb[1]);
-                    const uint32_t d1 = pack_half2(yacc[sub][ot][4 * q + 2] + bb[2], yacc[sub][ot][4 * q + 3] + bb[3]);
-                    if (t == 0) {
-                        lo[0] = d0;
-                        lo[1] = d1;
-                    } else {
-                        hi[0] = d0;
-                        hi[1] = d1;
-                    }
-                }
-                // after the swaps: lanes 0-31 hold (own lo, partner's lo) = piece 2qp; lanes 32-63 hold
-                // (partner's hi, own hi) = piece 2qp + 1, both in feature order
-                const auto s0 = __builtin_amdgcn_permlane32_swap(lo[0], hi[0], false, false);
-                const auto s1 = __builtin_amdgcn_permlane32_swap(lo[1], hi[1], false, false);
-                if (u.row[sub] >= 0 && ot * 4 + 2 * qp + g < SliceTiles<DS>::P) {
-                    const uint4 v = make_uint4(s0[0], s1[0], s0[1], s1[1]);
-                    *(uint4 *)(yr + ot * 32 + 8 * (2 * qp + g)) = v;
-                }
-            }
-    }
+            for (int qp = 0; qp < 2; ++qp) store_row_pieces<DS, BIAS>(u.row[sub], yacc[sub][ot], ot, qp, b2s, y, g);
 }
 
 template <int DS, int NSUB>
@@ -249,12 +259,12 @@ __device__ __forceinline__ void unit_rows(int base, int end, bool unit_ok, int j
 template <int DS, int NSUB>
 __device__ __forceinline__ void load_rows(RowUnit<DS, NSUB> &u, const int (&a)[NSUB], const int (&row)[NSUB],
                                           const bf16_t *__restrict__ x, const float *__restrict__ pk, int k, int g,
-                                          float (&p)[NSUB])
+                                          float (&p)[NSUB], int kshift = -1 /* log2(k) when k is a power of two */)
 {
 #pragma unroll
     for (int sub = 0; sub < NSUB; ++sub) {
         u.row[sub] = row[sub];
-        const long long n = a[sub] / k;
+        const long long n = kshift >= 0 ? (long long)(a[sub] >> kshift) : (long long)(a[sub] / k);
         const uint4 *xr = (const uint4 *)(x + n * DS);
 #pragma unroll
         for (int ks = 0; ks < SliceTiles<DS>::KS; ++ks) u.xb[sub][ks] = load_row_piece<DS>(xr, ks, g);
@@ -356,6 +366,291 @@ __global__ __launch_bounds__(THREADS) void ffn_resident_kernel(
             q_c = q_n;
         }
         r = seg_end;
+    }
+}
+
+// ------------------------------------------------------------------------------ resident, software-pipelined
+// The same row split as the resident kernel, with the three stages of a hidden tile -- GEMM1, activation, GEMM2 --
+// taken apart in time inside every wavefront: in one step the wavefront issues GEMM1 of tile t, the activation of tile
+// t-1 and GEMM2 of tile t-2, which do not depend on each other, so its matrix instructions and its vector instructions
+// interleave one to nine without waiting for one another (in the plain loop the activation waits for the matrix
+// instructions just issued, and a wavefront's vector work only overlaps other wavefronts' matrix work).  The steps run
+// on across the units of a wavefront: the first two steps of a unit finish the previous unit (its last activation and
+// GEMM2s, then its rows are stored), and one more pair of steps after the last unit drains the pipeline.  Weight
+// fragments come from LDS through a ring of four register sets, each requested four matrix instructions ahead.
+// Every matrix instruction is followed by half of the activation of two pairs of hidden units (nine packed
+// instructions from two independent chains); scheduling fences keep that order.  HT even (accumulator and activation
+// buffers alternate by tile parity) and a multiple of four matrix instructions per step (the ring position of a
+// fragment is then fixed).
+// The LDS holds TWO experts: a block whose rows straddle an expert boundary stages both and its wavefronts walk
+// the units of both in one pipeline (a unit names its expert's slot), instead of draining, synchronising and
+// re-staging at the boundary with a ragged last round of units on either side.  Eight wavefronts, two per SIMD: the
+// pipeline needs 160 registers, and eight divide the 64 units of a headline block evenly.
+struct PairChains {
+    h2 s[2], v[2], Q[2];
+};
+// The activation of two pairs of hidden units at once, cut in two halves of nine packed instructions: the two
+// dependent chains alternate, so no instruction waits for the one just before it.
+__device__ __forceinline__ void activation_first_half(PairChains &c, const float (&a)[4], h2 p2, h2 bias0, h2 bias1, const EpiConst &K)
+{
+    static_assert(kGeluM == 4, "the split below is written for a degree-4 polynomial");
+    const h2 A0 = __builtin_bit_cast(h2, __builtin_amdgcn_cvt_pkrtz(a[0], a[1]));
+    const h2 A1 = __builtin_bit_cast(h2, __builtin_amdgcn_cvt_pkrtz(a[2], a[3]));
+    c.s[0] = pk_fma(A0, p2, bias0);
+    c.s[1] = pk_fma(A1, p2, bias1);
+    c.v[0] = pk_fma(c.s[0], c.s[0], as_h2(K.neg_w0));
+    c.v[1] = pk_fma(c.s[1], c.s[1], as_h2(K.neg_w0));
+    c.Q[0] = pk_fma(c.v[0], as_h2(K.q[4]), as_h2(K.q[3]));
+    c.Q[1] = pk_fma(c.v[1], as_h2(K.q[4]), as_h2(K.q[3]));
+    c.Q[0] = pk_fma(c.Q[0], c.v[0], as_h2(K.q[2]));
+}
+__device__ __forceinline__ void activation_second_half(PairChains &c, const EpiConst &K, uint32_t &out0, uint32_t &out1)
+{
+    c.Q[1] = pk_fma(c.Q[1], c.v[1], as_h2(K.q[2]));
+    c.Q[0] = pk_fma(c.Q[0], c.v[0], as_h2(K.q[1]));
+    c.Q[1] = pk_fma(c.Q[1], c.v[1], as_h2(K.q[1]));
+    c.Q[0] = pk_fma(c.Q[0], c.v[0], as_h2(K.q[0]));
+    c.Q[1] = pk_fma(c.Q[1], c.v[1], as_h2(K.q[0]));
+    const h2 F0 = pk_fma_clamp01(c.s[0], c.Q[0], as_h2(K.half));
+    const h2 F1 = pk_fma_clamp01(c.s[1], c.Q[1], as_h2(K.half));
+    out0 = __builtin_bit_cast(uint32_t, c.s[0] * F0);
+    out1 = __builtin_bit_cast(uint32_t, c.s[1] * F1);
+}
+
+template <int DS, int HT>
+struct PipeState {
+    static constexpr int KS = SliceTiles<DS>::KS, OT = SliceTiles<DS>::OT;
+    static constexpr int NM = KS + 2 * OT;   // matrix instructions per step
+    static_assert(HT % 2 == 0 && NM % 4 == 0 && NM >= 8 && HT >= 2, "see the kernel's comment");
+    bf16x8 xb[KS];          // rows of the unit whose GEMM1 is running
+    f32x16 acc[2];          // GEMM1 results, by tile parity
+    uint32_t hb[2][8];      // activations as fp16 pairs, by tile parity: [s * 4 + i] is register i of K-step s of GEMM2
+    f32x16 yacc[1][OT];
+    f32x16 b2acc[OT];       // second-layer bias of the current unit's expert in accumulator layout: GEMM2 starts from it
+    uint4 ring[4];          // weight fragments in flight
+    uint4 bias[2][2];       // first-layer biases of the tile being activated, by tile parity
+};
+
+// The experts' LDS images of three consecutive units of a wavefront, as offsets in 16-byte pieces: the unit whose
+// rows are being finished, the one whose GEMM1 runs, and the one after it.
+struct PipeSlots {
+    int prev, cur, next;
+};
+
+// Fragment (offset in 16-byte pieces inside an expert's LDS image) of matrix instruction m of the step whose GEMM1 tile
+// is t: m < KS is K-step m of W1's tile t; the rest are W2's fragments (s, ot) of tile t - 2.
+template <int DS, int HT>
+__device__ __forceinline__ constexpr int pipe_frag(int t, int m, int w2_piece0)
+{
+    constexpr int KS = SliceTiles<DS>::KS, OT = SliceTiles<DS>::OT;
+    if (m < KS) return (t * KS + m) * 64;
+    const int t2 = (t + HT - 2) % HT, i = m - KS;
+    return w2_piece0 + ((t2 * 2 + i / OT) * OT + i % OT) * 64;
+}
+
+// One step: GEMM1 of tile T of the current unit, activation of the tile before (scale p2_act), GEMM2 of the tile before
+// that.  Each matrix instruction takes its fragment from the ring and refills the slot with the fragment four matrix
+// instructions ahead, from the LDS image of the expert that instruction's unit belongs to.
+template <int DS, int HT, int T>
+__device__ __forceinline__ void pipe_step(PipeState<DS, HT> &S, const uint4 *__restrict__ lds16, const PipeSlots &E,
+                                          int w2_piece0, int b1_piece0, int lane, int g, h2 p2_act, const EpiConst &K)
+{
+    constexpr int KS = SliceTiles<DS>::KS, OT = SliceTiles<DS>::OT, NM = KS + 2 * OT;
+    constexpr int TA = (T + HT - 1) % HT;   // tile being activated
+    constexpr int T2 = (T + HT - 2) % HT;   // tile whose GEMM2 runs
+    // biases of the tile the NEXT step activates (tile T of the current unit), requested a step ahead
+    S.bias[T & 1][0] = lds16[E.cur + b1_piece0 + (T * 2 + g) * 2 + 0];
+    S.bias[T & 1][1] = lds16[E.cur + b1_piece0 + (T * 2 + g) * 2 + 1];
+    const uint4 bq0 = S.bias[TA & 1][0], bq1 = S.bias[TA & 1][1];
+    const uint32_t bw[8] = {bq0.x, bq0.y, bq0.z, bq0.w, bq1.x, bq1.y, bq1.z, bq1.w};
+    PairChains chains;
+#pragma unroll
+    for (int m = 0; m < NM; ++m) {
+        const uint4 frag = S.ring[m & 3];
+        if (m < KS) {
+            const bf16x8 a1 = __builtin_bit_cast(bf16x8, frag);
+            if (m == 0) {
+                f32x16 zero;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) zero[r] = 0.f;
+                S.acc[T & 1] = mfma_bf16(a1, S.xb[m], zero);
+            } else {
+                S.acc[T & 1] = mfma_bf16(a1, S.xb[m], S.acc[T & 1]);
+            }
+        } else {
+            const int i = m - KS, s = i / OT, ot = i % OT;
+            const f16x8 a2 = __builtin_bit_cast(f16x8, frag);
+            const f16x8 b2v = __builtin_bit_cast(f16x8, make_uint4(S.hb[T & 1][s * 4 + 0], S.hb[T & 1][s * 4 + 1],
+                                                                  S.hb[T & 1][s * 4 + 2], S.hb[T & 1][s * 4 + 3]));
+            if (T2 == 0 && s == 0) {
+                S.yacc[0][ot] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a2, b2v, S.b2acc[ot], 0, 0, 0);
+            } else {
+                S.yacc[0][ot] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a2, b2v, S.yacc[0][ot], 0, 0, 0);
+            }
+        }
+        // refill the slot: the fragment of matrix instruction m + 4 (of the next step when that runs past this one).
+        // A GEMM1 fragment belongs to the unit whose GEMM1 runs then (the next unit after this unit's last step); a
+        // GEMM2 fragment to the unit of the tile two steps back (the previous unit during a unit's first two steps).
+        {
+            const int mn = m + 4;
+            int piece;
+            if (mn < NM) {
+                piece = pipe_frag<DS, HT>(T, mn, w2_piece0) + (mn < KS ? E.cur : (T >= 2 ? E.cur : E.prev));
+            } else {
+                constexpr int TN = (T + 1) % HT;
+                const int mm = mn - NM;
+                if (mm < KS) piece = pipe_frag<DS, HT>(TN, mm, w2_piece0) + (T + 1 < HT ? E.cur : E.next);
+                else piece = pipe_frag<DS, HT>(TN, mm, w2_piece0) + ((T + 1 >= 2 || T + 1 == HT) ? E.cur : E.prev);
+            }
+            S.ring[m & 3] = lds16[piece + lane];
+        }
+        // behind every matrix instruction half of the activation of two pairs of hidden units (eight pairs per tile)
+        if (m < 8) {
+            const int pp = m & ~1;   // the two pairs pp, pp + 1
+            if ((m & 1) == 0) {
+                const float a[4] = {S.acc[TA & 1][2 * pp], S.acc[TA & 1][2 * pp + 1], S.acc[TA & 1][2 * pp + 2], S.acc[TA & 1][2 * pp + 3]};
+                activation_first_half(chains, a, p2_act, as_h2(bw[pp]), as_h2(bw[pp + 1]), K);
+            } else {
+                activation_second_half(chains, K, S.hb[TA & 1][pp], S.hb[TA & 1][pp + 1]);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// Steps T .. HT-1 of a unit.
+template <int DS, int HT, int T>
+__device__ __forceinline__ void pipe_steps_from(PipeState<DS, HT> &S, const uint4 *__restrict__ lds16, const PipeSlots &E,
+                                                int w2_piece0, int b1_piece0, int lane, int g, h2 p2_act, const EpiConst &K)
+{
+    if constexpr (T < HT) {
+        pipe_step<DS, HT, T>(S, lds16, E, w2_piece0, b1_piece0, lane, g, p2_act, K);
+        pipe_steps_from<DS, HT, T + 1>(S, lds16, E, w2_piece0, b1_piece0, lane, g, p2_act, K);
+    }
+}
+
+// The second-layer bias of the expert whose LDS image starts at piece `image`, in accumulator layout.
+template <int DS, int HT>
+__device__ __forceinline__ void load_b2acc(PipeState<DS, HT> &S, const char *lds, int image, size_t off_b2, int g)
+{
+    const float *b2s = (const float *)(lds + (size_t)image * 16 + off_b2);
+#pragma unroll
+    for (int ot = 0; ot < SliceTiles<DS>::OT; ++ot)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const f32x4 bb = *(const f32x4 *)(b2s + ot * 32 + 8 * q + 4 * g);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) S.b2acc[ot][4 * q + c] = bb[c];
+        }
+}
+
+template <int DS, int HT, int THREADS>
+__global__ __launch_bounds__(THREADS) void ffn_pipelined_kernel(
+    const bf16_t *__restrict__ x, const float *__restrict__ pk, const int32_t *__restrict__ offsets,
+    const int32_t *__restrict__ perm, const char *__restrict__ experts, size_t e_stride, size_t off_w2,
+    size_t off_b1, size_t off_b2, int E, int k, EpiConst K, half_t *__restrict__ y)
+{
+    constexpr int kWaves = THREADS / 64;
+    constexpr int KS = SliceTiles<DS>::KS;
+    extern __shared__ __align__(16) char lds[];             // two expert images of e_stride bytes each
+    const uint4 *lds16 = (const uint4 *)lds;                // in an image: W1 fragments [HT][KS][64] from piece 0
+    const int w2_piece0 = (int)(off_w2 / 16);               // W2 fragments [HT][2][OT][64]
+    const int b1_piece0 = (int)(off_b1 / 16);               // b1 [HT][2][16] fp16
+    const int image = (int)(e_stride / 16);                 // pieces per image
+
+    const int tid = threadIdx.x, lane = tid & 63, j = lane & 31, g = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kshift = (k & (k - 1)) == 0 ? __ffs(k) - 1 : -1;   // slice of an assignment: a shift when k is a power of two
+
+    // lane e keeps the end of expert e's row range: expert lookups are one ballot, not a chain of loads
+    const int off_hi = offsets[min(lane + 1, E)];
+    const int n_kept = __builtin_amdgcn_readfirstlane(__shfl(off_hi, E - 1));
+    const int units_total = (n_kept + kResU - 1) / kResU;
+    const int units_per_block = (units_total + gridDim.x - 1) / gridDim.x;
+    const int vblock = gridDim.x % 8 == 0 ? (int)(blockIdx.x % 8) * (int)(gridDim.x / 8) + (int)(blockIdx.x / 8) : (int)blockIdx.x;
+    const long long r_begin = (long long)vblock * units_per_block * kResU;
+    const int r_end = (int)min((long long)n_kept, r_begin + (long long)units_per_block * kResU);
+
+    int r = (int)min(r_begin, (long long)n_kept);
+    while (r < r_end) {
+        // up to two experts per pass: rows [r, end0) of expert e0 in image 0, rows [end0, end1) of expert e1 in image 1
+        const int e0 = __builtin_amdgcn_readfirstlane(__popcll(__ballot(lane < E && off_hi <= r)));
+        const int end0 = min(__builtin_amdgcn_readfirstlane(__shfl(off_hi, e0)), r_end);
+        const int e1 = __builtin_amdgcn_readfirstlane(__popcll(__ballot(lane < E && off_hi <= end0)));   // == E past the last row
+        const int end1 = end0 < r_end ? min(__builtin_amdgcn_readfirstlane(__shfl(off_hi, min(e1, E - 1))), r_end) : end0;
+        const int n0 = (end0 - r + kResU - 1) / kResU, n1 = (end1 - end0 + kResU - 1) / kResU;
+        const int mine = wave < n0 + n1 ? (n0 + n1 - wave + kWaves - 1) / kWaves : 0;   // units wave, wave + kWaves, ...
+        // unit q of the pass: its rows, and the LDS image of its expert
+        auto unit_base = [&](int q) { return q < n0 ? r + q * kResU : end0 + (q - n0) * kResU; };
+        auto unit_end = [&](int q) { return q < n0 ? end0 : end1; };
+        auto unit_image = [&](int q) { return q < n0 ? 0 : image; };
+
+        __syncthreads();  // everyone is done with the previous pass's weights
+        int row_c[1], a_c[1], row_n[1], a_n[1], row_nn[1], a_nn[1];
+        float p_c[1], p_n[1];
+        unit_rows<1>(unit_base(wave), unit_end(wave), mine > 0, j, perm, row_c, a_c);
+        unit_rows<1>(unit_base(wave + kWaves), unit_end(wave + kWaves), mine > 1, j, perm, row_n, a_n);
+        stage_to_lds<THREADS>(experts + (size_t)e0 * e_stride, lds, image, tid);
+        if (n1 > 0) stage_to_lds<THREADS>(experts + (size_t)e1 * e_stride, lds + e_stride, image, tid);
+        RowUnit<DS, 1> cur, nxt;
+        load_rows<DS, 1>(cur, a_c, row_c, x, pk, k, g, p_c, kshift);
+        set_p<DS, 1>(cur, p_c);
+        __syncthreads();
+
+        if (mine > 0) {
+            PipeState<DS, HT> S;
+            PipeSlots slots;
+            slots.prev = slots.cur = unit_image(wave);
+            slots.next = unit_image(wave + kWaves);
+            load_b2acc<DS, HT>(S, lds, slots.cur, off_b2, g);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) S.xb[ks] = cur.xb[0][ks];
+#pragma unroll
+            for (int m = 0; m < 4; ++m) S.ring[m] = lds16[slots.cur + pipe_frag<DS, HT>(0, m, w2_piece0) + lane];
+            // the stages that lag behind start on nothing: whatever they compute before the first unit's tiles reach
+            // them is overwritten (accumulators start from zero at a unit's first tile) and never stored (row -1)
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+#pragma unroll
+                for (int r16 = 0; r16 < 16; ++r16) S.acc[b][r16] = 0.f;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) S.hb[b][i] = 0u;
+                S.bias[b][0] = S.bias[b][1] = make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int ot = 0; ot < SliceTiles<DS>::OT; ++ot)
+#pragma unroll
+                for (int r16 = 0; r16 < 16; ++r16) S.yacc[0][ot][r16] = 0.f;
+            h2 p2_prev = cur.p2[0];
+            RowUnit<DS, 1> done;   // the unit whose rows are stored next (only its row id is used)
+            done.row[0] = -1;
+            for (int ui = 0; ui <= mine; ++ui) {
+                // the rows of the next unit are requested now, a whole unit ahead; its row index came a unit earlier
+                // still, and the one after next is requested here
+                const int q_nn = wave + (ui + 2) * kWaves;
+                unit_rows<1>(unit_base(q_nn), unit_end(q_nn), ui + 2 < mine, j, perm, row_nn, a_nn);
+                load_rows<DS, 1>(nxt, a_n, row_n, x, pk, k, g, p_n, kshift);
+                // steps 0 and 1 finish the previous unit (its accumulators started from the second-layer bias)
+                pipe_step<DS, HT, 0>(S, lds16, slots, w2_piece0, b1_piece0, lane, g, p2_prev, K);
+                pipe_step<DS, HT, 1>(S, lds16, slots, w2_piece0, b1_piece0, lane, g, cur.p2[0], K);
+                store_rows<DS, 1, false>(done, S.yacc, nullptr, y, g);
+                if (ui == mine) break;   // that was the drain after the last unit
+                pipe_steps_from<DS, HT, 2>(S, lds16, slots, w2_piece0, b1_piece0, lane, g, cur.p2[0], K);
+                p2_prev = cur.p2[0];
+                done.row[0] = cur.row[0];
+                cur = nxt;
+                set_p<DS, 1>(cur, p_n);
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) S.xb[ks] = cur.xb[0][ks];
+                row_n[0] = row_nn[0];
+                a_n[0] = a_nn[0];
+                slots.prev = slots.cur;
+                slots.cur = slots.next;
+                slots.next = unit_image(wave + (ui + 2) * kWaves);
+                if (slots.cur != slots.prev) load_b2acc<DS, HT>(S, lds, slots.cur, off_b2, g);   // the next unit is another expert's
+            }
+        }
+        r = end1;
     }
 }
 
@@ -509,6 +804,26 @@ static hipError_t run_resident(const slicemoe_config &c, const PackedLayout &L, 
     return hipGetLastError();
 }
 
+constexpr int kPipeThreads = 512;   // eight wavefronts, two per SIMD
+
+template <int DS, int HT, int THREADS>
+static hipError_t run_pipelined(const slicemoe_config &c, const PackedLayout &L, const FfnPlan &pl, const void *h,
+                                const float *p, const int32_t *offsets, const int32_t *perm, const char *experts,
+                                void *y, hipStream_t s)
+{
+    const long long Na = (long long)c.T * c.S * c.k;
+    const long long max_units = (Na + kResU - 1) / kResU;
+    long long blocks = max_units;   // small inputs: spread the units over all CUs rather than fill few blocks
+    if (blocks > num_compute_units()) blocks = num_compute_units();
+    auto kern = ffn_pipelined_kernel<DS, HT, THREADS>;
+    const size_t lds = 2 * L.e_stride;   // two expert images
+    hipError_t err = grant_dynamic_lds((const void *)kern, lds);
+    if (err != hipSuccess) return err;
+    kern<<<(int)blocks, THREADS, lds, s>>>((const bf16_t *)h, p, offsets, perm, experts, L.e_stride, L.e_w2, L.e_b1,
+                                                  L.e_b2, c.E, c.k, make_epi_const(), (half_t *)y);
+    return hipGetLastError();
+}
+
 template <int DS, int NSUB, int THREADS = 512>
 static hipError_t run_streamed(const slicemoe_config &c, const PackedLayout &L, const FfnPlan &pl, const void *h,
                                const float *p, const int32_t *offsets, const int32_t *perm, const char *experts,
@@ -540,9 +855,9 @@ hipError_t launch_ffn_mfma(const slicemoe_config &c, const void *h, const float 
         if (L.ds == 24) return run_resident<24, 3, 1024>(c, L, pl, h, p, offsets, perm, experts, y, s);
         if (L.ds == 48) return run_resident<48, 6, 1024>(c, L, pl, h, p, offsets, perm, experts, y, s);
         if (L.ds == 96) return run_resident<96, 12, 768>(c, L, pl, h, p, offsets, perm, experts, y, s);
-        if (L.He == 256) return run_resident<64, 8, 1024>(c, L, pl, h, p, offsets, perm, experts, y, s);
-        if (L.He == 128) return run_resident<64, 4, 1024>(c, L, pl, h, p, offsets, perm, experts, y, s);
-        return run_resident<64, 2, 1024>(c, L, pl, h, p, offsets, perm, experts, y, s);
+        if (L.He == 256) return run_pipelined<64, 8, kPipeThreads>(c, L, pl, h, p, offsets, perm, experts, y, s);
+        if (L.He == 128) return run_pipelined<64, 4, kPipeThreads>(c, L, pl, h, p, offsets, perm, experts, y, s);
+        return run_pipelined<64, 2, kPipeThreads>(c, L, pl, h, p, offsets, perm, experts, y, s);
     }
     if (L.ds == 24) return run_streamed<24, 2>(c, L, pl, h, p, offsets, perm, experts, y, s);
     if (L.ds == 48) return run_streamed<48, 2>(c, L, pl, h, p, offsets, perm, experts, y, s);
