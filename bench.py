@@ -222,7 +222,9 @@ def main():
     t_ffn = stage_ms["expert_ffn"] * 1e-3
     achieved = flops["expert_ffn"] / t_ffn / 1e12
     resident = (shape.ds, shape.He) in ((64, 64), (64, 128), (64, 256), (96, 384), (48, 192), (24, 96))  # as the library plans
-    kernel = "ffn_generic_kernel" if not B.slicemoe_uses_mfma(cfg) else "ffn_resident_kernel" if resident else "ffn_streamed_kernel"
+    pipelined = shape.ds == 64 and shape.He in (64, 128, 256)
+    kernel = ("ffn_generic_kernel" if not B.slicemoe_uses_mfma(cfg) else "ffn_pipelined_kernel" if pipelined
+              else "ffn_resident_kernel" if resident else "ffn_streamed_kernel")
     roofline = {"kernel": kernel, "bound": "mfma", "achieved": round(achieved, 2),
                 "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_BF16_TFLOPS, 4),
                 "traffic": FFN_TRAFFIC_BYTES.get(args.workload, {}).get("bytes"),
@@ -288,6 +290,8 @@ def main():
         "slices_per_s": round(Ns / (ms_per_step * 1e-3), 1),
         "stages": stages,
         "stage_sum_us": round(sum(stage_ms.values()) * 1e3, 2),
+        "stages_note": "each stage through its own entry point; inside slicemoe_forward the router leaves the per-chunk "
+                       "histogram behind, so its dispatch is the scatter kernel alone (see profiles/)",
         "load": {"cv2": round(stats[0], 5), "ele": round(stats[1], 5), "drop_fraction": round(stats[2], 5)},
         "roofline": roofline,
         "cpu_baseline": cpu,

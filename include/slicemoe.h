@@ -26,6 +26,18 @@
  *   - Limits: 1 <= k <= min(E, 8), E <= 64, d % S == 0, T*S*k < 2^31.  The matrix-core
  *     (MFMA) kernels need dtype = bf16, Hr = 256, ds in {24, 48, 64, 96, 128, 192, 384}, He % 32 == 0; any
  *     other shape runs on slower generic kernels unless SLICEMOE_FLAG_REQUIRE_MFMA is set.
+ *   - Numeric range of the bf16 (matrix-core) path; nothing checks it and a value beyond it changes results without
+ *     an error code.  Inputs and weights are arbitrary bf16; the limits are on intermediate values:
+ *       expert layer 1   the accumulator x W1 of a hidden unit is converted to fp16 before it is scaled by p:
+ *                        |x W1| <= 65504 (beyond that the unit saturates);
+ *       expert output    the stacked rows y are stored as fp16: |y| <= 65504;
+ *       router layer 1   a hidden activation u = ReLU(x Wr1 + br1) enters the second layer as two fp16 terms:
+ *                        u < 2048 keeps 22 significant bits (what makes the selected experts agree with an fp32
+ *                        reference except on near-ties), 2048 <= u <= 65504 keeps 11, larger u saturates;
+ *       router layer 2   Wr2 is used as fp16: its bf16 values convert exactly when |Wr2| is in [6.2e-5, 65504] or 0
+ *                        (smaller magnitudes lose bits to fp16's subnormal range).
+ *     With unit-variance activations and weights of the usual initialisations all of these hold with orders of
+ *     magnitude to spare; activations that are not normalised may need SLICEMOE_FLAG_FORCE_GENERIC (fp32 arithmetic).
  *   - Errors are return codes; nothing aborts or throws across this boundary.
  */
 #ifndef SLICEMOE_H
@@ -189,7 +201,7 @@ slicemoe_status slicemoe_dispatch(const slicemoe_config *cfg, const int32_t *top
  * slicemoe_dispatch, minus the workspace: the per-chunk histogram table lives in a fixed 1 MiB array inside the
  * library's device image (one copy per GPU, held until the process ends).  The call allocates and frees nothing.
  *   Limit: the table, E rows of ceil(T*S*k / chunk) entries (rounded up to a multiple of 8; chunk = 1024 assignments
- *   below 2^19 of them, 2048 below 2^21, 4096 from there on), must fit 262144 entries: any config with
+ *   while that gives at most 4096 chunks, else 2048, else 4096), must fit 262144 entries: any config with
  *   T*S*k <= 16 777 216.  Beyond it the call returns SLICEMOE_ERR_WORKSPACE and launches nothing.
  *   All calls on one GPU share the array: calls that overlap in time on one GPU (different streams) race on it.
  *   Nothing in it has to be cleared between calls; it keeps the last call's table.

@@ -72,7 +72,7 @@ struct PackedLayout {
     int dsK, dsN;                // ds rounded up to whole K-steps (16) and whole output tiles (32); padding is zeros
     size_t r_w1, r_w2, r_b1, r_b2;  // router: Wr1 frags, Wr2 frags, br1 (f32), br2 (f32, Epad)
     size_t experts;                 // start of expert 0
-    size_t e_w1, e_w2, e_b1, e_b2;  // offsets inside one expert block: W1 frags (bf16), W2 frags (fp16, times 1/kappa),
+    size_t e_w1, e_w2, e_b1, e_b2;  // offsets inside one expert block: W1 frags (bf16, times kappa), W2 frags (fp16, times 1/kappa),
                                     // b1 (fp16, times kappa, accumulator order per hidden tile), b2 (f32)
     size_t e_stride;                // bytes per expert
     size_t total;

@@ -16,8 +16,8 @@
 // Activation stage (the part that bounds this kernel: with ds = 64 every hidden element is fed
 // by only 16 matrix-core cycles per lane, so the vector ALU work per element decides the speed).
 // It runs entirely on packed fp16 instructions, two hidden elements per instruction:
-//   A  = cvt_pkrtz(acc0, acc1)                 fp32 accumulators -> fp16 pair
-//   s  = A * (kappa p) + kappa b1              s = kappa z, kappa = 1/4           (Eq. 1 scale + bias)
+//   A  = cvt_pkrtz(acc0, acc1)                 fp32 accumulators kappa (x W1) -> fp16 pair; kappa = 1/4 sits in the packed W1
+//   s  = A * p + kappa b1                      s = kappa z                        (Eq. 1 scale + bias)
 //   v  = s * s - w0
 //   Q  = Horner in v, degree kGeluM            s Q(v) ~ Phi(z) - 1/2 on |z| <= zc, and > 1/2 beyond
 //   F  = clamp01(s * Q + 1/2)                  ~ Phi(z): the instruction's own [0,1] clamp saturates it
@@ -26,7 +26,7 @@
 // mantissa bits than the bf16 storage type; evaluated this way the activation error is of the
 // size of a bf16 rounding: at most 2^-8 (rms below 8e-4) of the larger of |z| and |p a| (the same
 // roundings are replayed on the CPU in tests/test_gelu_poly.py).
-// Hidden activations beyond +-65504 / kappa would overflow fp16.
+// Range: |x W1| beyond 65504 / kappa saturates the conversion, |z| beyond that overflows fp16.
 //
 // Three variants:
 //   pipelined a whole expert fits in LDS twice over (ds = 64, He <= 256: the benchmark shapes).  One block of
@@ -105,7 +105,7 @@ __device__ __forceinline__ void activation_tile(const f32x16 &acc, h2 p2, const 
 
 template <int DS, int NSUB> struct RowUnit {
     bf16x8 xb[NSUB][SliceTiles<DS>::KS];
-    h2 p2[NSUB];   // (kappa p, kappa p), zero for a lane without a row
+    h2 p2[NSUB];   // (p, p), zero for a lane without a row
     int row[NSUB]; // -1: no row
 };
 
@@ -277,7 +277,7 @@ __device__ __forceinline__ void set_p(RowUnit<DS, NSUB> &u, const float (&p)[NSU
 {
 #pragma unroll
     for (int sub = 0; sub < NSUB; ++sub) {
-        const float pv = u.row[sub] >= 0 ? p[sub] * kGeluKappa : 0.f;
+        const float pv = u.row[sub] >= 0 ? p[sub] : 0.f;
         u.p2[sub] = __builtin_bit_cast(h2, __builtin_amdgcn_cvt_pkrtz(pv, pv));
     }
 }

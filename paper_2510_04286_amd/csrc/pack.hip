@@ -5,7 +5,7 @@
 // Router   W1 frags [Hr/32][ds/16][64 lanes]      lane (i, g), slot m: Wr1[16*ks + 8*g + m][32*ht + i]
 //          (ds/16 and ds/32 rounded up: rows and columns past ds are zeros)
 //          W2 frags [Epad/32][Hr/32][2][64]       lane (i, g), slot m: Wr2[32*ht + chain_feature(s,g,m)][32*et + i], as fp16
-// Expert e W1 frags [He/32][ds/16][64]            W1[e][16*ks + 8*g + m][32*ht + i]
+// Expert e W1 frags [He/32][ds/16][64]            kappa * W1[e][16*ks + 8*g + m][32*ht + i]   (kappa = 1/4: exact in bf16)
 //          W2 frags [He/32][2][ds/32][64]         W2[e][32*ht + chain_feature(s,g,m)][32*ot + i] / kappa, as fp16
 //          b1       [He/32][2 lane groups][16]    kappa * b1[e][32*ht + acc_feature(r, g)], as fp16
 //          b2       [ds rounded up to 32] fp32
@@ -26,9 +26,10 @@ __device__ __forceinline__ void store_frag(char *dst, const bf16_t v[8])
     *(uint4 *)dst = u;
 }
 
-// Fragments of a first-layer matrix W[K, N] (row-major), A operand of the transposed GEMM1.
+// Fragments of a first-layer matrix W[K, N] (row-major), A operand of the transposed GEMM1, times `scale` (a power of
+// two: the product is again a bf16 value, exactly, unless it falls into the subnormal range below 2^-126).
 __global__ void pack_layer1_kernel(const bf16_t *__restrict__ W, int K, int Kpad, int N, size_t src_stride,
-                                   char *__restrict__ dst, size_t dst_stride, int nmat)
+                                   char *__restrict__ dst, size_t dst_stride, int nmat, float scale)
 {
     const int KS = Kpad / 16;   // rows K..Kpad-1 are zeros
     const long long per = (long long)(N / 32) * KS * 64;
@@ -45,7 +46,7 @@ __global__ void pack_layer1_kernel(const bf16_t *__restrict__ W, int K, int Kpad
     bf16_t v[8];
     for (int m = 0; m < 8; ++m) {
         const int kk = 16 * ks + 8 * g + m;
-        v[m] = kk < K ? src[(size_t)kk * N + 32 * ht + i] : (bf16_t)0;
+        v[m] = kk < K ? f32_to_bf16(bf16_to_f32(src[(size_t)kk * N + 32 * ht + i]) * scale) : (bf16_t)0;
     }
     store_frag(dst + (size_t)mat * dst_stride + (size_t)(f - (long long)mat * per) * 16, v);
 }
@@ -128,7 +129,7 @@ hipError_t launch_pack(const slicemoe_config &c, const slicemoe_weights &w, void
     // router
     const int dsK = L.dsK, dsN = L.dsN;
     pack_layer1_kernel<<<blocks_for((long long)(Hr / 32) * (dsK / 16) * 64), 256, 0, s>>>(
-        (const bf16_t *)w.Wr1, ds, dsK, Hr, 0, base + L.r_w1, 0, 1);
+        (const bf16_t *)w.Wr1, ds, dsK, Hr, 0, base + L.r_w1, 0, 1, 1.f);
     pack_layer2_kernel<<<blocks_for((long long)(Hr / 32) * 2 * (Epad / 32) * 64), 256, 0, s>>>(
         (const bf16_t *)w.Wr2, Hr, E, Epad, 0, base + L.r_w2, 0, 1, true, true, 1.f);
     pack_bias_kernel<<<blocks_for(Hr), 256, 0, s>>>((const bf16_t *)w.br1, Hr, Hr, 0, base + L.r_b1, 0, 1);
@@ -136,7 +137,7 @@ hipError_t launch_pack(const slicemoe_config &c, const slicemoe_weights &w, void
     // experts
     char *eb = base + L.experts;
     pack_layer1_kernel<<<blocks_for((long long)E * (He / 32) * (dsK / 16) * 64), 256, 0, s>>>(
-        (const bf16_t *)w.W1, ds, dsK, He, (size_t)ds * He, eb + L.e_w1, L.e_stride, E);
+        (const bf16_t *)w.W1, ds, dsK, He, (size_t)ds * He, eb + L.e_w1, L.e_stride, E, kGeluKappa);
     pack_layer2_kernel<<<blocks_for((long long)E * (He / 32) * 2 * (dsN / 32) * 64), 256, 0, s>>>(
         (const bf16_t *)w.W2, He, ds, dsN, (size_t)He * ds, eb + L.e_w2, L.e_stride, E, false, true, 1.f / kGeluKappa);
     pack_bias_f16_kernel<<<blocks_for((long long)E * He), 256, 0, s>>>((const bf16_t *)w.b1, He, He, eb + L.e_b1,

@@ -25,15 +25,16 @@ def zipf_bias():
     return b
 
 
-def make_inputs(cfg, T=None):
-    """(cfg', h, weights) of a workload, optionally with fewer tokens."""
+def make_inputs(cfg, T=None, seed=0):
+    """(cfg', h, weights) of a workload, optionally with fewer tokens; seed: weights from `seed`, hidden states from
+    `seed + 1` (0 gives the workload's own inputs, the ones bench.py runs)."""
     if T is not None and T != cfg.T:
         cfg = cfg.scaled(T)
-    w = wl.make_weights(cfg)
+    w = wl.make_weights(cfg, seed=seed)
     if cfg.zipf_s > 0:
         assert cfg.E == 32 and cfg.zipf_s == 1.2
         w["br2"] = zipf_bias()
-    return cfg, wl.make_h(cfg), w
+    return cfg, wl.make_h(cfg, seed=seed + 1), w
 
 
 @functools.lru_cache(maxsize=1)

@@ -4,9 +4,20 @@ The kernel evaluates GELU(z) = z Phi(z) for z = p * a + b (Eq. 1 scale of the GE
 plus the expert bias) with fp16 multiply-adds and a polynomial for Phi.  This test re-runs exactly
 that sequence of roundings in numpy (one rounding per fused multiply-add, round-toward-zero for the
 fp32 -> fp16 conversions) with the coefficients of csrc/gelu_poly.h, and compares with the erf
-definition of Section 3.1's expert activation.  It pins the coefficient table and the claim that
-the activation error is of the size of a bf16 rounding: at most 2^-8 (3.4e-3 observed), rms below 8e-4, of the
-larger of |z| and |p a|.
+definition of Section 3.1's expert activation.  It pins the coefficient table and the error bound of
+the activation, which is derived from the arithmetic and not fitted to what is observed:
+
+  eps = 2^-11 (fp16 round to nearest), 2 eps (round toward zero), kappa = 1/4, s = kappa z.
+  Input of the polynomial: A = rtz(kappa a), p2 = rtz(p), beta = rn(kappa b), s^ = rn(A p2 + beta), so
+      |s^ / kappa - z| <= 4 eps |p a| + eps |b| + eps |z|                                   =: dz.
+  Phi: the table's fit error 5.3e-4 (exact arithmetic, generated header) plus the Horner roundings; the last of them
+  dominates, eps |Q| with |Q| <= 1.6 = phi(0) / kappa, and enters F = s Q + 1/2 times |s| <= 0.825 (the fitted interval;
+  beyond it the instruction's clamp makes F exactly 0 or 1); with the earlier steps (half as much again) and the
+  rounding of F itself (eps / 2):            |F^ - Phi(z)| <= 5.3e-4 + 0.825 * 1.5 * 1.6 eps + eps / 2 < 1.75e-3 =: dF.
+  Result g^ = rn(s^ F^):  |g^ / kappa - GELU(z)| <= max|GELU'| dz + |z| dF + eps |z|,  max|GELU'| = 1.13:
+      <= 2.21e-3 |p a| + 5.6e-4 |b| + 2.8e-3 |z|   (+ 1e-6 for fp16 subnormals),
+  i.e. about one bf16 rounding (2^-8 = 3.9e-3) of the larger of |z| and |p a|.  The worst case observed is 3.4e-3 of that;
+  the rms, 6e-4 to 8e-4 over the spans below, is kept under 1e-3 as a regression guard (not a derived bound).
 """
 import math
 import os
@@ -47,8 +58,8 @@ def _kernel_gelu(acc, p, b):
     """kappa-scaled fp16 pipeline of activation_tile(); returns GELU(z) (the kernel's 1/kappa sits in W2)."""
     m, kappa, w0, q = _consts()
     qh = [float(np.float16(c)) for c in q]
-    A = _rtz(np.float32(acc))
-    p2 = _rtz(np.float32(p) * np.float32(kappa))
+    A = _rtz(np.float32(acc) * np.float32(kappa))   # the packed W1 carries kappa: the accumulator is kappa (x W1)
+    p2 = _rtz(np.float32(p))
     bias = _rne(np.float32(b) * np.float32(kappa))
     s = _rne(A * p2 + bias)
     v = _rne(s * s - float(np.float16(w0)))
@@ -81,14 +92,17 @@ def test_fp16_activation_error_is_one_bf16_rounding():
         p = rng.uniform(0.02, 1.0, n)
         b = rng.uniform(-0.125, 0.125, n)
         acc = (z_target - b) / p
-        z = np.float64(np.float32(p)) * np.float64(np.float32(acc)) + np.float64(np.float32(b))
+        pa = np.float64(np.float32(p)) * np.float64(np.float32(acc))
+        z = pa + np.float64(np.float32(b))
         got = _kernel_gelu(acc, p, b)
         err = np.abs(got - _gelu(z))
-        # the accumulator is rounded to fp16 before the bias is added, so the bound is relative to the larger of
-        # the result and the scaled accumulator (a sum that cancels keeps the rounding of its terms)
-        scale = np.maximum(np.maximum(np.abs(z), np.abs(p * acc)), 0.05)
-        assert np.max(err / scale) < 2.0 ** -8, (span, float(np.max(err / scale)))
-        assert np.sqrt(np.mean((err / scale) ** 2)) < 8e-4
+        # the bound derived in the header; the accumulator is rounded to fp16 before the bias is added, so a sum that
+        # cancels keeps the rounding of its terms
+        bound = 2.21e-3 * np.abs(pa) + 5.6e-4 * np.abs(b) + 2.8e-3 * np.abs(z) + 1e-6
+        worst = float(np.max(err / bound))
+        scale = np.maximum(np.maximum(np.abs(z), np.abs(pa)), 0.05)
+        assert worst < 1.0, (span, worst, float(np.max(err / scale)))
+        assert np.sqrt(np.mean((err / scale) ** 2)) < 1e-3, (span, float(np.sqrt(np.mean((err / scale) ** 2))))
 
 
 def test_saturation_and_zero():
