@@ -544,6 +544,64 @@ __device__ __forceinline__ void load_b2acc(PipeState<DS, HT> &S, const char *lds
         }
 }
 
+// ---- Which rows a block takes.
+// Cutting the stacked rows into equal runs would be simplest, but a run that starts in the middle of an expert's 32-row
+// units makes both neighbours pad a partial unit, and a run that holds a whole small expert plus parts of its two
+// neighbours needs a second pass over the LDS images.  So the cut is made in UNITS counted from each expert's first
+// row, on an axis where an expert is at least as long as one block's share: expert e occupies max(units_e, W) of it, W
+// the share itself (the smallest W with  sum_e max(units_e, W) <= W * blocks, found by a few rounds of a fixed-point
+// iteration: each round is one wavefront sum).  A block's share of that axis then touches at most two experts; inside
+// a stretched (small) expert positions map back to units proportionally.  Lane e holds expert e (E <= 64).
+template <int CTRL> __device__ __forceinline__ int lane_move(int v) { return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true); }
+
+__device__ __forceinline__ int wavefront_sum(int v)
+{
+    v += lane_move<0xB1>(v);    // quad_perm [1, 0, 3, 2]
+    v += lane_move<0x4E>(v);    // quad_perm [2, 3, 0, 1]
+    v += lane_move<0x141>(v);   // row_half_mirror
+    v += lane_move<0x140>(v);   // row_mirror: every lane now holds the sum of its row of 16
+    return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) + __builtin_amdgcn_readlane(v, 32) +
+           __builtin_amdgcn_readlane(v, 48);
+}
+
+__device__ __forceinline__ int wavefront_exclusive_scan(int v, int lane)
+{
+    int s = v;
+    s += lane_move<0x111>(s);   // row_shr 1, 2, 4, 8 with zero fill: inclusive scan inside a row of 16
+    s += lane_move<0x112>(s);
+    s += lane_move<0x114>(s);
+    s += lane_move<0x118>(s);
+    const int r0 = __builtin_amdgcn_readlane(s, 15), r1 = __builtin_amdgcn_readlane(s, 31), r2 = __builtin_amdgcn_readlane(s, 47);
+    const int row = lane >> 4;
+    return s - v + (row == 0 ? 0 : row == 1 ? r0 : row == 2 ? r0 + r1 : r0 + r1 + r2);
+}
+
+__device__ __forceinline__ void block_row_range(int lane, int E, int off_lo, int off_hi, int n_kept, int blocks, int vblock,
+                                                int &r_begin, int &r_end)
+{
+    const int rows = lane < E ? off_hi - off_lo : 0;
+    const int units = (rows + kResU - 1) / kResU;
+    int W = max(1, (wavefront_sum(units) + blocks - 1) / blocks);
+    int C = wavefront_sum(lane < E ? max(units, W) : 0);
+    for (int it = 0; it < 3; ++it) {   // uniform: all operands are wavefront sums
+        const int Wn = (C + blocks - 1) / blocks;
+        if (Wn <= W) break;
+        W = Wn;
+        C = wavefront_sum(lane < E ? max(units, W) : 0);
+    }
+    const int cost = lane < E ? max(units, W) : 0;
+    const int cb = wavefront_exclusive_scan(cost, lane);
+    auto row_at = [&](long long c) {   // stacked row at position c of the axis
+        const bool own = lane < E && c >= cb && c < (long long)cb + cost;
+        const int u = own ? (int)(((c - cb) * units) / cost) : 0;
+        const int rr = off_lo + min(rows, kResU * u);
+        const unsigned long long m = __ballot(own);
+        return m == 0 ? n_kept : __builtin_amdgcn_readlane(rr, __builtin_ctzll(m));
+    };
+    r_begin = row_at((long long)vblock * C / blocks);
+    r_end = row_at((long long)(vblock + 1) * C / blocks);
+}
+
 template <int DS, int HT, int THREADS>
 __global__ __launch_bounds__(THREADS) void ffn_pipelined_kernel(
     const bf16_t *__restrict__ x, const float *__restrict__ pk, const int32_t *__restrict__ offsets,
@@ -563,15 +621,14 @@ __global__ __launch_bounds__(THREADS) void ffn_pipelined_kernel(
     const int kshift = (k & (k - 1)) == 0 ? __ffs(k) - 1 : -1;   // slice of an assignment: a shift when k is a power of two
 
     // lane e keeps the end of expert e's row range: expert lookups are one ballot, not a chain of loads
+    const int off_lo = offsets[min(lane, E)];
     const int off_hi = offsets[min(lane + 1, E)];
-    const int n_kept = __builtin_amdgcn_readfirstlane(__shfl(off_hi, E - 1));
-    const int units_total = (n_kept + kResU - 1) / kResU;
-    const int units_per_block = (units_total + gridDim.x - 1) / gridDim.x;
+    const int n_kept = __builtin_amdgcn_readlane(off_hi, 63);   // lanes past the last expert read offsets[E]
     const int vblock = gridDim.x % 8 == 0 ? (int)(blockIdx.x % 8) * (int)(gridDim.x / 8) + (int)(blockIdx.x / 8) : (int)blockIdx.x;
-    const long long r_begin = (long long)vblock * units_per_block * kResU;
-    const int r_end = (int)min((long long)n_kept, r_begin + (long long)units_per_block * kResU);
+    int r_begin, r_end;
+    block_row_range(lane, E, off_lo, off_hi, n_kept, (int)gridDim.x, vblock, r_begin, r_end);
 
-    int r = (int)min(r_begin, (long long)n_kept);
+    int r = r_begin;
     while (r < r_end) {
         // up to two experts per pass: rows [r, end0) of expert e0 in image 0, rows [end0, end1) of expert e1 in image 1
         const int e0 = __builtin_amdgcn_readfirstlane(__popcll(__ballot(lane < E && off_hi <= r)));
