@@ -28,8 +28,9 @@
  *     other shape runs on slower generic kernels unless SLICEMOE_FLAG_REQUIRE_MFMA is set.
  *   - Numeric range of the bf16 (matrix-core) path; nothing checks it and a value beyond it changes results without
  *     an error code.  Inputs and weights are arbitrary bf16; the limits are on intermediate values:
- *       expert layer 1   the accumulator x W1 of a hidden unit is converted to fp16 before it is scaled by p:
- *                        |x W1| <= 65504 (beyond that the unit saturates);
+ *       expert layer 1   the accumulator of a hidden unit, (x W1) / 4 with the factor folded into the packed W1, is
+ *                        converted to fp16 before it is scaled by p: |x W1| <= 262016 (beyond that the unit
+ *                        saturates), and |p x W1 + b1| <= 262016;
  *       expert output    the stacked rows y are stored as fp16: |y| <= 65504;
  *       router layer 1   a hidden activation u = ReLU(x Wr1 + br1) enters the second layer as two fp16 terms:
  *                        u < 2048 keeps 22 significant bits (what makes the selected experts agree with an fp32
