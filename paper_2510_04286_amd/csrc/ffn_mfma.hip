@@ -195,10 +195,15 @@ __device__ __forceinline__ void store_row_pieces(int row, const f32x16 &acc, int
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
         const int q = 2 * qp + t;
-        f32x4 bb = {0.f, 0.f, 0.f, 0.f};
-        if constexpr (BIAS) bb = *(const f32x4 *)(b2s + ot * 32 + 8 * q + 4 * g);
-        const uint32_t d0 = pack_half2(acc[4 * q + 0] + bb[0], acc[4 * q + 1] + bb[1]);
-        const uint32_t d1 = pack_half2(acc[4 * q + 2] + bb[2], acc[4 * q + 3] + bb[3]);
+        uint32_t d0, d1;
+        if constexpr (BIAS) {
+            const f32x4 bb = *(const f32x4 *)(b2s + ot * 32 + 8 * q + 4 * g);
+            d0 = pack_half2(acc[4 * q + 0] + bb[0], acc[4 * q + 1] + bb[1]);
+            d1 = pack_half2(acc[4 * q + 2] + bb[2], acc[4 * q + 3] + bb[3]);
+        } else {   // (an addition of zero would still be an instruction: it can change the sign of a zero)
+            d0 = pack_half2(acc[4 * q + 0], acc[4 * q + 1]);
+            d1 = pack_half2(acc[4 * q + 2], acc[4 * q + 3]);
+        }
         if (t == 0) {
             lo[0] = d0;
             lo[1] = d1;
@@ -682,6 +687,15 @@ __global__ __launch_bounds__(THREADS) void ffn_pipelined_kernel(
             RowUnit<DS, 1> done;   // the unit whose rows are stored next (only its row id is used)
             done.row[0] = -1;
             for (int ui = 0; ui <= mine; ++ui) {
+                {   // The SIMD serves its oldest wavefront first, which then finishes a third of the kernel earlier than
+                    // its partner and leaves it alone on the SIMD, where a lone wavefront overlaps less.  Priority by
+                    // units left keeps the two within two units of each other.
+                    const int left = mine - ui;
+                    if (left >= 6) __builtin_amdgcn_s_setprio(3);
+                    else if (left >= 4) __builtin_amdgcn_s_setprio(2);
+                    else if (left >= 2) __builtin_amdgcn_s_setprio(1);
+                    else __builtin_amdgcn_s_setprio(0);
+                }
                 // the rows of the next unit are requested now, a whole unit ahead; its row index came a unit earlier
                 // still, and the one after next is requested here
                 const int q_nn = wave + (ui + 2) * kWaves;
@@ -695,10 +709,10 @@ __global__ __launch_bounds__(THREADS) void ffn_pipelined_kernel(
                 pipe_steps_from<DS, HT, 2>(S, lds16, slots, w2_piece0, b1_piece0, lane, g, cur.p2[0], K);
                 p2_prev = cur.p2[0];
                 done.row[0] = cur.row[0];
-                cur = nxt;
+                cur.row[0] = nxt.row[0];   // (the rows themselves go straight into the pipeline's operand registers)
                 set_p<DS, 1>(cur, p_n);
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) S.xb[ks] = cur.xb[0][ks];
+                for (int ks = 0; ks < KS; ++ks) S.xb[ks] = nxt.xb[0][ks];
                 row_n[0] = row_nn[0];
                 a_n[0] = a_nn[0];
                 slots.prev = slots.cur;
