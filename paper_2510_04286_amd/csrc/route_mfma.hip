@@ -214,7 +214,8 @@ __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
         // {own, other} in an order that max / min / + do not care about.
         // (the maximum as a median with +infinity: the median instruction takes its operands as they are, while a
         // floating-point maximum would first spend an instruction on quieting each of them)
-        const float kInf = INFINITY;
+        float kInf;   // (opaque to the compiler, which would otherwise turn the medians back into maxima)
+        asm("v_mov_b32 %0, 0x7f800000" : "=v"(kInf));
         float m = v[0], second = -INFINITY;
 #pragma unroll
         for (int i = 1; i < ET * 16; ++i) {
@@ -226,7 +227,7 @@ __global__ __launch_bounds__(THREADS) void route_mfma_kernel(
             const auto ss = __builtin_amdgcn_permlane32_swap(__float_as_uint(second), __float_as_uint(second), false, false);
             const float m0 = __uint_as_float(sm[0]), m1 = __uint_as_float(sm[1]);
             m = __builtin_amdgcn_fmed3f(m0, m1, kInf);
-            const float lower = __builtin_amdgcn_fmed3f(m0, m1, -kInf);   // the smaller of the two maxima
+            const float lower = __builtin_amdgcn_fmed3f(m0, m1, -kInf);   // the smaller of the two maxima (the negation is an operand modifier)
             second = __builtin_amdgcn_fmed3f(__builtin_amdgcn_fmed3f(__uint_as_float(ss[0]), __uint_as_float(ss[1]), kInf), lower, kInf);
         }
         // softmax denominator: exp((v - m) / tau) = exp2(v * c - m * c) with c = log2(e) / tau, one multiply-add and
