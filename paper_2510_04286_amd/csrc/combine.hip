@@ -60,7 +60,9 @@ template <> struct RowAdd<half_t, 8> {
     }
 };
 
-template <typename T, typename YT, int V>
+// K = 2: the common top-2 case with both row indices read by one 8-byte load and both rows requested before either is
+// used (a dropped assignment reads row 0 and is not added); K = 0: any k, one row after the other.
+template <typename T, typename YT, int V, int K>
 __global__ __launch_bounds__(256) void combine_kernel(const YT *__restrict__ y, const int32_t *__restrict__ inv,
                                                       T *__restrict__ out, long long n_vec, int ds, int k)
 {
@@ -72,10 +74,24 @@ __global__ __launch_bounds__(256) void combine_kernel(const YT *__restrict__ y, 
         float acc[V];
 #pragma unroll
         for (int v = 0; v < V; ++v) acc[v] = 0.f;
-        for (int j = 0; j < k; ++j) {
-            const int r = inv[n * k + j];
-            if (r < 0) continue;
-            RowAdd<YT, V>::add(y + (size_t)r * ds + c0, acc);
+        if constexpr (K == 2) {
+            const int2 r = *(const int2 *)(inv + n * 2);
+            float a0[V], a1[V];
+#pragma unroll
+            for (int v = 0; v < V; ++v) a0[v] = a1[v] = 0.f;
+            RowAdd<YT, V>::add(y + (size_t)(r.x < 0 ? 0 : r.x) * ds + c0, a0);
+            RowAdd<YT, V>::add(y + (size_t)(r.y < 0 ? 0 : r.y) * ds + c0, a1);
+#pragma unroll
+            for (int v = 0; v < V; ++v) {   // ascending j, as in the general case
+                if (r.x >= 0) acc[v] += a0[v];
+                if (r.y >= 0) acc[v] += a1[v];
+            }
+        } else {
+            for (int j = 0; j < k; ++j) {
+                const int r = inv[n * k + j];
+                if (r < 0) continue;
+                RowAdd<YT, V>::add(y + (size_t)r * ds + c0, acc);
+            }
         }
         OutVec<T, V>::store(out + (size_t)n * ds + c0, acc);
     }
@@ -91,7 +107,10 @@ static hipError_t run(const slicemoe_config &c, const void *y, const int32_t *in
     long long blocks = (n_vec + 255) / 256;
     const long long cap = (long long)num_compute_units() * 64;
     if (blocks > cap) blocks = cap;
-    combine_kernel<T, YT, V><<<(int)blocks, 256, 0, s>>>((const YT *)y, inv, (T *)h_out, n_vec, ds, c.k);
+    if (c.k == 2 && ((uintptr_t)inv & 7) == 0)
+        combine_kernel<T, YT, V, 2><<<(int)blocks, 256, 0, s>>>((const YT *)y, inv, (T *)h_out, n_vec, ds, c.k);
+    else
+        combine_kernel<T, YT, V, 0><<<(int)blocks, 256, 0, s>>>((const YT *)y, inv, (T *)h_out, n_vec, ds, c.k);
     return hipGetLastError();
 }
 
