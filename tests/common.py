@@ -51,10 +51,11 @@ def large_dout():
 
 
 def progress(msg):
-    """A line for a long test to leave behind while it runs (output is captured until the test ends)."""
-    d = os.path.join(os.path.dirname(GOLDEN), os.pardir, "gpurun_out")
-    if os.path.isdir(d):
-        with open(os.path.join(d, "test_progress.log"), "a") as f:
+    """A line for a long test to leave behind while it runs (output is captured until the test ends): appended to the
+    file that the environment variable SLICEMOE_PROGRESS_LOG names, if it is set."""
+    path = os.environ.get("SLICEMOE_PROGRESS_LOG")
+    if path:
+        with open(path, "a") as f:
             f.write(msg + "\n")
 
 
