@@ -227,6 +227,40 @@ def test_expert_ffn_large_preactivations(B, name, T):
     assert err <= TOL_BF16, err
 
 
+def test_expert_ffn_beyond_the_fp16_range_saturates(B):
+    """The numeric range the header states for the bf16 path: a hidden unit's |x W1| up to 4 * 65504 is exact work, beyond
+    it the fp16 conversion saturates (round toward zero never produces an infinity).  First-layer weights scaled by 2^17
+    push about a third of the rows past the limit: every output must stay finite, and the rows whose units all stay inside
+    the range must still match the oracle."""
+    import torch
+    shape = wl.CONFIGS["headline"].scaled(64)  # 1024 slices
+    w = dict(wl.make_weights(shape))
+    h = wl.make_h(shape)
+    w["W1"] = (w["W1"] * 2.0 ** 17).astype(w["W1"].dtype)    # powers of two: still exact bf16 values
+    w["W2"] = (w["W2"] * 2.0 ** -8).astype(w["W2"].dtype)     # keeps |y| in the hundreds, and W2 / kappa a normal fp16
+    x = h.reshape(-1, shape.ds)
+    r = oracle.route(x, w["Wr1"], w["br1"], w["Wr2"], w["br2"], shape.k)
+    pk = np.ones_like(r["pk"])
+    d = oracle.dispatch(r["idx"], shape.E, -1)
+    ref = oracle.expert_rows(x, r["idx"], pk, d["perm"], shape.Na, w["W1"], w["b1"], w["W2"], w["b2"])
+    a = d["perm"]                                              # assignment of every stacked row
+    pre = np.einsum("rd,rdh->rh", x[a // shape.k].astype(np.float64), w["W1"][r["idx"].reshape(-1)[a]].astype(np.float64))
+    inside = np.abs(pre).max(axis=1) < 0.9 * 4 * 65504
+    assert 0.02 < 1.0 - inside.mean() < 0.9, inside.mean()    # the case does reach past the limit, and not everywhere
+    cfg = B.config_of(shape)
+    assert B.slicemoe_uses_mfma(cfg) == 1
+    wd = B.pack(cfg, B.weights_to_device(w, shape.dtype))
+    y = torch.zeros((shape.Na, shape.ds), dtype=B.y_dtype(cfg), device="cuda:0")
+    B.slicemoe_expert_ffn(cfg, B.to_device(h, shape.dtype), dev(pk.astype(np.float32).reshape(-1)), dev(d["offsets"]),
+                          dev(d["perm"]), wd, y)
+    got = y.float().cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got))
+    err = np.abs(got[inside] - ref[inside]).max() / rms(ref[inside])
+    print(f"\n[ffn range] rows past the limit: {int((~inside).sum())} of {inside.size}; inside max|err|/rms={err:.3e}")
+    assert err <= TOL_BF16, err
+    assert np.abs(got[~inside]).max() <= 2.0 * np.abs(ref[~inside]).max()   # saturated, not blown up
+
+
 # ------------------------------------------------------------------ router
 ROUTE_CASES = [("tiny", 512, 0), ("lm", 4096, 0), ("headline", 4096, 0), ("skewed", 4096, 0), ("large", 1024, 0),
                ("paper", 2048, 0), ("paper_S4_k2", 1000, 0), ("paper_S16_k2", 500, 0), ("paper_S32_k2", 250, 0), ("paper_S2_k2", 3000, 0),
