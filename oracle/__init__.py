@@ -224,9 +224,26 @@ def forward_train(h, S: int, k: int, weights: dict, tau: float = 1.0, sigma: flo
     return res
 
 
+def capacity_surrogate(idx, pk, E: int, alpha: float):
+    """The differentiable reading of the capacity loss (Section 3.2, Eq. 2): counts replaced by the sums of the final
+    probabilities routed to each expert, c_e = sum over assignments a with idx[a] == e of pk[a].
+    Returns dict(sums[E], value = alpha * CV^2(c) with the population variance, grad[E] = d value / d c_e)."""
+    idx = _i32(idx).reshape(-1)
+    pk = _f64(pk).reshape(-1)
+    assert idx.shape == pk.shape
+    c = np.zeros(E, dtype=np.float64)
+    for e in range(E):
+        c[e] = pk[idx == e].sum()
+    total, squares = c.sum(), np.square(c).sum()
+    value = alpha * (E * squares / total ** 2 - 1.0)           # var / mean^2 = E sum c^2 / (sum c)^2 - 1
+    grad = alpha * (2.0 * E / total ** 2) * (c - squares / total)
+    return {"sums": c, "value": float(value), "grad": grad}
+
+
 def backward(h, S: int, k: int, weights: dict, d_out, idx, inv, tau: float = 1.0, sigma: float = 0.0, noise=None,
-             rate: float = 0.0, drop_u=None):
+             rate: float = 0.0, drop_u=None, capg=None):
     """Gradients of a loss with dL/dh' = d_out[T, d], given the forward pass's idx[Ns,k] and inv[Ns*k].
+    capg[E] (optional): d L_cap / d c_e of capacity_surrogate(), added to dL/dp of every assignment of expert e.
     Returns dict(d_h[T,d], Wr1, br1, Wr2, br2, W1, b1, W2, b2) in the logical layouts, fp64."""
     h = _f64(h)
     T, d = h.shape
@@ -241,6 +258,8 @@ def backward(h, S: int, k: int, weights: dict, d_out, idx, inv, tau: float = 1.0
     assert idx.shape == (Ns, k) and inv.shape == (Ns * k,)
     noise = None if noise is None else _f64(noise)
     drop_u = None if drop_u is None else _f64(drop_u)
+    capg = None if capg is None else _f64(capg)
+    assert capg is None or capg.shape == (E,)
     out = {"d_h": np.empty((T, d), dtype=np.float64)}
     for n in ("Wr1", "br1", "Wr2", "br2", "W1", "b1", "W2", "b2"):
         out[n] = np.empty_like(w[n])
@@ -248,7 +267,7 @@ def backward(h, S: int, k: int, weights: dict, d_out, idx, inv, tau: float = 1.0
                                _p(w["Wr1"]), _p(w["br1"]), _p(w["Wr2"]), _p(w["br2"]),
                                _p(w["W1"]), _p(w["b1"]), _p(w["W2"]), _p(w["b2"]),
                                ctypes.c_double(tau), ctypes.c_double(sigma), _p(noise), ctypes.c_double(rate),
-                               _p(drop_u), _p(idx), _p(inv), _p(G), _p(out["d_h"]),
+                               _p(drop_u), _p(idx), _p(inv), _p(G), _p(capg), _p(out["d_h"]),
                                _p(out["Wr1"]), _p(out["br1"]), _p(out["Wr2"]), _p(out["br2"]),
                                _p(out["W1"]), _p(out["b1"]), _p(out["W2"]), _p(out["b2"]))
     _check(rc, "oracle_backward")

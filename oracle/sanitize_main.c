@@ -28,8 +28,8 @@ int oracle_forward(const double *, int64_t, int, int, int, int, int, int, int64_
                    double *, int32_t *, double *, double *, int32_t *, int32_t *, int32_t *, int32_t *, int32_t *);
 int oracle_backward(const double *, int64_t, int, int, int, int, int, const double *, const double *, const double *,
                     const double *, const double *, const double *, const double *, const double *, double, double,
-                    const double *, double, const double *, const int32_t *, const int32_t *, const double *, double *,
-                    double *, double *, double *, double *, double *, double *, double *, double *);
+                    const double *, double, const double *, const int32_t *, const int32_t *, const double *,
+                    const double *, double *, double *, double *, double *, double *, double *, double *, double *, double *);
 int oracle_load_stats(const int32_t *, int, double *, double *, double *);
 double oracle_gelu(double);
 
@@ -120,7 +120,11 @@ static void one_layer(int64_t T, int d, int S, int Hr, int E, int k, int He, int
     double *dbr2 = new_f64((size_t)E), *dW1 = new_f64((size_t)E * ds * He), *db1 = new_f64((size_t)E * He);
     double *dW2 = new_f64((size_t)E * He * ds), *db2 = new_f64((size_t)E * ds);
     CHECK(oracle_backward(h, Ns, ds, Hr, E, k, He, Wr1, br1, Wr2, br2, W1, b1, W2, b2, 0.7, sigma, noise, rate, drop_u, idx2,
-                          inv, G, dx, dWr1, dbr1, dWr2, dbr2, dW1, db1, dW2, db2) == 0);
+                          inv, G, NULL, dx, dWr1, dbr1, dWr2, dbr2, dW1, db1, dW2, db2) == 0);
+    double *capg = new_f64((size_t)E);
+    CHECK(oracle_backward(h, Ns, ds, Hr, E, k, He, Wr1, br1, Wr2, br2, W1, b1, W2, b2, 0.7, sigma, noise, rate, drop_u, idx2,
+                          inv, G, capg, dx, dWr1, dbr1, dWr2, dbr2, dW1, db1, dW2, db2) == 0);
+    free(capg);
     double cv_pop, cv_sample, ele;
     CHECK(oracle_load_stats(counts_raw, E, &cv_pop, &cv_sample, &ele) == 0);
     CHECK(ele >= -1e-12 && ele <= 1.0 + 1e-12 && cv_pop >= 0.0);

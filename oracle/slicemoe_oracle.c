@@ -425,8 +425,17 @@ int oracle_forward(const double *h, int64_t T, int d, int S, int Hr, int E, int 
  *     dL/dp_j = (dL/dpk'_j - sum_i dL/dpk'_i pk'_i) / s for kept j, 0 for dropped j.
  *   - softmax with temperature: dL/dg_e = (1/tau) sum_j dL/dp_j p_j ([e == e_j] - p_e); the noise
  *     is an additive constant.
- *   - the capacity loss of Eq. 2 is a function of integer counts and has zero gradient; it is
- *     not part of this function.
+ *   - the capacity loss of Eq. 2 is a function of integer counts and has zero gradient as
+ *     written.  Section 3.1 says the router is trained with it and Section 3.2 speaks of its
+ *     gradients, so its authors differentiate something the paper does not state.  The reading
+ *     offered here (off unless the caller passes capg) is the usual one for a count-based
+ *     balance loss: the count of expert e is replaced by the sum of the final probabilities of
+ *     the assignments routed to it, c_e = sum_{a: e(a) = e} p_a, and the loss by
+ *     alpha * CV^2(c_1..c_E) (population variance).  Then dL_cap/dp_a = capg[e(a)], with
+ *     capg[e] = alpha * (2E / S^2) (c_e - Q / S), S = sum c, Q = sum c^2, which the caller
+ *     computes from the forward pass's probabilities.  Every assignment carries it, also one
+ *     that a capacity limit dropped (it still counts as assigned); one that the dropout zeroed
+ *     has a constant probability of zero and passes nothing on.
  * idx[Ns,k] and inv[Ns*k] are the forward pass's (oracle_route_train / oracle_dispatch); the
  * probabilities are recomputed here.  Outputs (all overwritten): dx[Ns, ds] and one array per
  * weight tensor in its logical layout.  Returns 0, or -1 on bad arguments / allocation failure.
@@ -441,7 +450,7 @@ int oracle_backward(const double *x, int64_t Ns, int ds, int Hr, int E, int k, i
                     const double *Wr1, const double *br1, const double *Wr2, const double *br2,
                     const double *W1, const double *b1, const double *W2, const double *b2,
                     double tau, double sigma, const double *noise, double rate, const double *drop_u,
-                    const int32_t *idx, const int32_t *inv, const double *G,
+                    const int32_t *idx, const int32_t *inv, const double *G, const double *capg,
                     double *dx, double *dWr1, double *dbr1, double *dWr2, double *dbr2,
                     double *dW1, double *db1, double *dW2, double *db2)
 {
@@ -504,10 +513,10 @@ int oracle_backward(const double *x, int64_t Ns, int ds, int Hr, int E, int k, i
                 }
                 /* experts */
                 for (int j = 0; j < k; ++j) {
-                    dpf[j] = 0.0;
                     int64_t a = n * k + j;
-                    if (inv[a] < 0) continue;
                     int e = idx[a];
+                    dpf[j] = capg ? capg[e] : 0.0;
+                    if (inv[a] < 0) continue;
                     const double *w1 = W1 + (size_t)e * ds * He, *w2 = W2 + (size_t)e * He * ds;
                     double p = pf[j];
                     for (int h = 0; h < He; ++h) u[h] = 0.0;

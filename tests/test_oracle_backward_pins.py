@@ -135,3 +135,79 @@ def test_backward_is_linear_in_the_upstream_gradient():
     c = oracle.backward(h, S, k, w, 2.0 * R - 0.5 * R2, f["idx"], f["inv"], **kw)
     for name in NAMES + ("d_h",):
         np.testing.assert_allclose(c[name], 2.0 * a[name] - 0.5 * b[name], rtol=1e-11, atol=1e-13)
+
+
+# ---- the differentiable reading of the capacity loss (Section 3.2, Eq. 2): gate sums in place of counts
+
+def test_capacity_surrogate_closed_forms():
+    rng = np.random.default_rng(21)
+    E, alpha = 6, 0.1
+    idx = rng.integers(0, E, size=(40, 2)).astype(np.int32)
+    # probabilities of one: the sums are the counts, and the value is Eq. 2 on the counts
+    ones = oracle.capacity_surrogate(idx, np.ones(idx.shape), E, alpha)
+    counts = np.bincount(idx.ravel(), minlength=E)
+    np.testing.assert_array_equal(ones["sums"], counts)
+    np.testing.assert_allclose(ones["value"], alpha * np.var(counts) / np.mean(counts) ** 2, rtol=1e-13)
+    np.testing.assert_allclose(ones["value"], alpha * oracle.load_stats(counts.astype(np.int32))["cv_pop"] ** 2, rtol=1e-12)
+    # equal sums: no imbalance, no gradient
+    eq = oracle.capacity_surrogate(np.arange(E, dtype=np.int32), np.full(E, 0.37), E, alpha)
+    assert abs(eq["value"]) < 1e-15 and np.all(np.abs(eq["grad"]) < 1e-15)
+    # the gradient is the derivative of the value with respect to the sums, and CV is scale-free (Euler: c . grad = 0)
+    pk = rng.uniform(0.05, 0.95, idx.shape)
+    s = oracle.capacity_surrogate(idx, pk, E, alpha)
+    np.testing.assert_allclose(np.dot(s["sums"], s["grad"]), 0.0, atol=1e-15)
+    for a in range(0, idx.size, 7):
+        vals = []
+        for sgn in (+1, -1):
+            q = pk.copy().ravel()
+            q[a] += sgn * 1e-6
+            vals.append(oracle.capacity_surrogate(idx, q.reshape(pk.shape), E, alpha)["value"])
+        np.testing.assert_allclose((vals[0] - vals[1]) / 2e-6, s["grad"][idx.ravel()[a]], rtol=0, atol=1e-10)
+    # an expert above the mean is pushed down, one below is pushed up
+    assert np.all(np.sign(s["grad"]) == np.sign(s["sums"] - np.square(s["sums"]).sum() / s["sums"].sum()))
+
+
+@pytest.mark.parametrize("vname", ["inference", "all"])
+@pytest.mark.parametrize("capacity", [-1, 3])
+def test_backward_with_capacity_surrogate_equals_finite_differences(vname, capacity):
+    """Total loss = linear functional of h' + alpha CV^2 of the gate sums.  The second term sees the router only, but
+    through every assignment: also those the capacity limit dropped (they never reach an expert)."""
+    alpha = 0.8
+    h, w, R, noise, drop_u, S, k = small_problem(seed=11)
+    E = w["Wr2"].shape[1]
+    variant = dict(VARIANTS[vname])
+    if "sigma" in variant:
+        variant["noise"] = noise
+    if "rate" in variant:
+        variant["drop_u"] = drop_u
+
+    def total(hh, ww):
+        f = oracle.forward_train(hh, S, k, ww, capacity=capacity, **variant)
+        return float(np.sum(f["h_out"] * R)) + oracle.capacity_surrogate(f["idx"], f["pk"], E, alpha)["value"], f
+
+    _, f = total(h, w)
+    assert f["margin"].min() > 1e-3
+    if capacity >= 0:
+        assert np.any(f["inv"] < 0)
+    cap = oracle.capacity_surrogate(f["idx"], f["pk"], E, alpha)
+    g = oracle.backward(h, S, k, w, R, f["idx"], f["inv"], capg=cap["grad"], **variant)
+    g0 = oracle.backward(h, S, k, w, R, f["idx"], f["inv"], **variant)
+    for name in NAMES + ("h",):
+        base = h if name == "h" else w[name]
+        fd = np.zeros_like(base)
+        it = np.nditer(base, flags=["multi_index"])
+        for _ in it:
+            i = it.multi_index
+            vals = []
+            for sgn in (+1, -1):
+                pert = base.copy()
+                pert[i] += sgn * 1e-6
+                vals.append(total(pert if name == "h" else h, w if name == "h" else {**w, name: pert})[0])
+            fd[i] = (vals[0] - vals[1]) / 2e-6
+        got = g["d_h"] if name == "h" else g[name]
+        np.testing.assert_allclose(got, fd, rtol=0, atol=2e-7 * max(1.0, np.abs(fd).max()), err_msg=f"{vname} {name}")
+    # the term reaches the router and the input, and nothing else
+    for name in ("W1", "b1", "W2", "b2"):
+        np.testing.assert_allclose(g[name], g0[name], rtol=1e-12, atol=1e-15)
+    for name in ("Wr1", "br1", "Wr2", "br2", "d_h"):
+        assert np.abs(g[name] - g0[name]).max() > 1e-4, name
