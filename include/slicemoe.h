@@ -173,6 +173,7 @@ typedef struct {
     float temperature;
     float noise_std;
     float dropout_rate;
+    float capacity_alpha;   /* read by slicemoe_backward only (see there); 0 = the capacity loss sends no gradient */
 } slicemoe_route_train_params;
 slicemoe_status slicemoe_route_train(const slicemoe_config *cfg, const void *h, const slicemoe_weights *w,
                                      const slicemoe_route_train_params *params, const float *noise,
@@ -270,8 +271,15 @@ slicemoe_status slicemoe_forward_train(const slicemoe_config *cfg, const void *h
  * The routing decisions -- which experts a slice selected, which assignments the capacity limit dropped, which the
  * dropout zeroed -- are piecewise constant and held fixed.  The router receives gradient through the selected
  * probabilities, which weight the expert inputs (z = p (x W1) + b1, so dL/dp = sum over the hidden units of
- * dL/dz (x W1)); with dropout the renormalisation is differentiated; the noise is an additive constant.  The capacity
- * loss of Eq. 2 is a function of integer counts, has zero gradient, and is not part of this call.
+ * dL/dz (x W1)); with dropout the renormalisation is differentiated; the noise is an additive constant.
+ * The capacity loss (Section 3.2, Eq. 2) is a function of integer counts and has zero gradient as written, although
+ * Section 3.1 trains the router with it; its value is alpha * stats[0] of slicemoe_load_stats.  With
+ * params->capacity_alpha = alpha != 0 this call adds the gradient of a differentiable stand-in, the usual one for a
+ * count-based balance loss: the count of expert e is replaced by the sum c_e of the final probabilities (topk_p, after
+ * dropout) of the assignments routed to e, the loss by alpha * CV^2(c_1..c_E) with the population variance, so that
+ * dL_cap/dp_a = alpha (2E / S^2) (c_e(a) - Q / S) with S = sum c, Q = sum c^2 is added to dL/dp of every assignment,
+ * also of those the capacity limit dropped (they still count as assigned); it reaches the router's weights and dL/dh.
+ * The sums are accumulated as 64-bit integers (p * 2^38), so this term too is the same bits on every run.
  *   h, w                 as given to the forward call (w: the LOGICAL tensors are read, w->packed is ignored)
  *   params, noise, drop_u as given to slicemoe_forward_train; params == NULL after slicemoe_forward
  *   forward_workspace    the workspace that forward call filled (routing tables and probabilities are read from it)

@@ -51,7 +51,8 @@ class slicemoe_weights(ctypes.Structure):
 
 
 class slicemoe_route_train_params(ctypes.Structure):
-    _fields_ = [("temperature", ctypes.c_float), ("noise_std", ctypes.c_float), ("dropout_rate", ctypes.c_float)]
+    _fields_ = [("temperature", ctypes.c_float), ("noise_std", ctypes.c_float), ("dropout_rate", ctypes.c_float),
+                ("capacity_alpha", ctypes.c_float)]
 
 
 class slicemoe_weight_grads(ctypes.Structure):
@@ -285,8 +286,8 @@ def slicemoe_forward(cfg, h, w, h_out, workspace, stream=None):
            "slicemoe_forward")
 
 
-def _train_args(cfg, temperature, noise_std, dropout_rate, noise, drop_u):
-    tp = slicemoe_route_train_params(temperature, noise_std, dropout_rate)
+def _train_args(cfg, temperature, noise_std, dropout_rate, noise, drop_u, capacity_alpha=0.0):
+    tp = slicemoe_route_train_params(temperature, noise_std, dropout_rate, capacity_alpha)
     Ns = cfg.T * cfg.S
     npt = None if noise is None else _ptr(noise, torch.float32, Ns * cfg.E, "noise")
     upt = None if drop_u is None else _ptr(drop_u, torch.float32, Ns * cfg.k, "drop_u")
@@ -333,14 +334,16 @@ def alloc_weight_grads(cfg, device="cuda:0") -> dict:
 
 def slicemoe_backward(cfg, h, w, forward_workspace, d_out, d_h, grads: dict, workspace, train: dict | None = None,
                       stream=None):
-    """train: None after slicemoe_forward, else the keyword arguments given to slicemoe_forward_train."""
+    """train: None after slicemoe_forward, else the keyword arguments given to slicemoe_forward_train, and optionally
+    capacity_alpha (weight of the capacity loss's gradient; the forward calls do not read it)."""
     fwp, fwb = _ws(forward_workspace)
     wsp, wsb = _ws(workspace)
     ws = _weights(cfg, w)
     tpp, npt, upt = None, None, None
     if train is not None:
         tp, npt, upt = _train_args(cfg, train.get("temperature", 1.0), train.get("noise_std", 0.0),
-                                   train.get("dropout_rate", 0.0), train.get("noise"), train.get("drop_u"))
+                                   train.get("dropout_rate", 0.0), train.get("noise"), train.get("drop_u"),
+                                   train.get("capacity_alpha", 0.0))
         tpp = ctypes.byref(tp)
     g = slicemoe_weight_grads()
     ds = cfg.d // cfg.S

@@ -268,9 +268,11 @@ static slicemoe_status make_route_variant(const slicemoe_route_train_params *tp,
     if (!(tp->dropout_rate >= 0.f) || !(tp->dropout_rate < 1.f)) return SLICEMOE_ERR_INVALID_ARG;
     if (tp->noise_std > 0.f && (!noise || misaligned(noise, 16))) return SLICEMOE_ERR_INVALID_ARG;
     if (tp->dropout_rate > 0.f && !drop_u) return SLICEMOE_ERR_INVALID_ARG;
+    if (!(fabsf(tp->capacity_alpha) < INFINITY)) return SLICEMOE_ERR_INVALID_ARG;   // also NaN
     v->inv_tau = 1.f / tp->temperature;
     v->sigma = tp->noise_std;
     v->noise = noise;
+    v->cap_alpha = tp->capacity_alpha;
     return SLICEMOE_OK;
 }
 

@@ -311,7 +311,8 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_router_kernel(
     const T *__restrict__ Wr1, const T *__restrict__ br1, const T *__restrict__ Wr2, const T *__restrict__ br2,
     const float *__restrict__ noise, float sigma, float inv_tau, const float *__restrict__ drop_u, float rate,
     const int32_t *__restrict__ idx, const int32_t *__restrict__ inv, const float *__restrict__ dpk,
-    const float *__restrict__ dxrow, T *__restrict__ dh, int slices_per_block, float *__restrict__ part)
+    const float *__restrict__ capg, const float *__restrict__ dxrow, T *__restrict__ dh, int slices_per_block,
+    float *__restrict__ part)
 {
     extern __shared__ float smem[];
     float *xs = smem;                      // [kBwdRB][ds]
@@ -428,7 +429,8 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_router_kernel(
                     const int ee = idx[a];
                     ej[jj] = ee < 0 ? 0 : (ee >= E ? E - 1 : ee);
                     psel[jj] = g[ej[jj]];
-                    dpf[jj] = inv[a] >= 0 ? dpk[a] : 0.f;   // a capacity-dropped assignment carries no gradient
+                    dpf[jj] = inv[a] >= 0 ? dpk[a] : 0.f;   // a capacity-dropped assignment carries no gradient from h'
+                    if (capg != nullptr) dpf[jj] += capg[ej[jj]];   // but it counts as assigned (capacity loss)
                     keep[jj] = rate > 0.f ? !(drop_u[a] < rate) : true;
                     kept += keep[jj] ? 1 : 0;
                 }
@@ -569,12 +571,54 @@ BackwardPlan backward_plan(const slicemoe_config &c)
     p.router_part = at;  at = align_up(at + (size_t)p.slice_blocks * router_slot_floats((int)ds, c.Hr, c.E) * sizeof(float), 256);
     p.packed = at;  at = align_up(at + backward_mfma_packed_bytes(c), 256);
     p.router_scratch = at;  at = align_up(at + backward_router_mfma_scratch_bytes(c), 256);
+    p.cap = at;  at = align_up(at + (size_t)c.E * (sizeof(unsigned long long) + sizeof(float)), 256);
     p.total = at + 256;
     return p;
 }
 
+// ---- The capacity loss (Section 3.2, Eq. 2) in its differentiable reading.  Eq. 2 is a function of integer counts;
+// the router can only be trained with it (Section 3.1) through a stand-in, and the one taken here is the usual one: the
+// count of expert e becomes the sum c_e of the final probabilities of the assignments routed to e, the loss
+// alpha CV^2(c) with the population variance, and dL_cap/dp_a = alpha (2E / S^2) (c_e(a) - Q / S), S = sum c, Q = sum c^2.
+// The sums are exact and the same on every run: each probability, a float in [0, 1], is added as the integer
+// p * 2^38 (at most 2^22 * k assignments: no overflow in 64 bits; bits below 2^-38 of a tiny p are rounded off).
+constexpr float kCapScale = 274877906944.f;   // 2^38
+
+__global__ __launch_bounds__(256) void bwd_cap_sums_kernel(const int32_t *__restrict__ idx, const float *__restrict__ pk,
+                                                           long long Na, int E, unsigned long long *__restrict__ sums)
+{
+    extern __shared__ unsigned long long cap_s[];
+    for (int e = threadIdx.x; e < E; e += blockDim.x) cap_s[e] = 0ull;
+    __syncthreads();
+    for (long long a = (long long)blockIdx.x * blockDim.x + threadIdx.x; a < Na; a += (long long)gridDim.x * blockDim.x) {
+        const int ee = idx[a];
+        const int e = ee < 0 ? 0 : (ee >= E ? E - 1 : ee);
+        const float p = fminf(fmaxf(pk[a], 0.f), 1.f);
+        atomicAdd(&cap_s[e], (unsigned long long)__float2ll_rn(p * kCapScale));
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += blockDim.x)
+        if (cap_s[e] != 0ull) atomicAdd(&sums[e], cap_s[e]);
+}
+
+// One block.  Every thread adds up all E sums in the same order, then writes its experts' derivatives.
+__global__ __launch_bounds__(256) void bwd_cap_coeff_kernel(const unsigned long long *__restrict__ sums, int E, float alpha,
+                                                            float *__restrict__ capg)
+{
+    double S = 0.0, Q = 0.0;
+    for (int e = 0; e < E; ++e) {
+        const double c = (double)sums[e] / (double)kCapScale;
+        S += c;
+        Q += c * c;
+    }
+    for (int e = threadIdx.x; e < E; e += blockDim.x) {
+        const double c = (double)sums[e] / (double)kCapScale;
+        capg[e] = S > 0.0 ? (float)((double)alpha * (2.0 * E / (S * S)) * (c - Q / S)) : 0.f;
+    }
+}
+
 template <typename T>
-static hipError_t run_backward(const slicemoe_config &c, const void *h, const slicemoe_weights &w, const RouteVariant &v,
+static hipError_t run_backward(const slicemoe_config &c, const void *h, const slicemoe_weights &w, const RouteVariant &v_in,
                                const float *drop_u, float rate, const int32_t *idx, const float *pk,
                                const int32_t *offsets, const int32_t *perm, const int32_t *inv, const void *d_out,
                                void *d_h, const slicemoe_weight_grads &g, void *workspace, hipStream_t s)
@@ -595,6 +639,20 @@ static hipError_t run_backward(const slicemoe_config &c, const void *h, const sl
     }
     const BackwardPlan P = backward_plan(c);
     char *ws = (char *)workspace;
+    RouteVariant v = v_in;
+    v.capg = nullptr;
+    if (v.cap_alpha != 0.f) {
+        unsigned long long *sums = (unsigned long long *)(ws + P.cap);
+        float *capg = (float *)(sums + c.E);
+        if ((e = zero_fill((float *)sums, 2 * (size_t)c.E, s)) != hipSuccess) return e;
+        long long blocks = (Na + 256 * 16 - 1) / (256 * 16);
+        if (blocks > 1024) blocks = 1024;
+        bwd_cap_sums_kernel<<<(unsigned)blocks, 256, (size_t)c.E * sizeof(unsigned long long), s>>>(idx, pk, Na, c.E, sums);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        bwd_cap_coeff_kernel<<<1, 256, 0, s>>>(sums, c.E, v.cap_alpha, capg);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        v.capg = capg;
+    }
     float *dxrow = (float *)(ws + P.dxrow), *dpk = (float *)(ws + P.dpk);
     float *epart = (float *)(ws + P.expert_part), *rpart = (float *)(ws + P.router_part);
 
@@ -654,11 +712,11 @@ static hipError_t run_backward(const slicemoe_config &c, const void *h, const sl
             return e;
         kern<<<rgrid, kBwdThreads, lds_rw, s>>>((const T *)h, Ns, ds, c.Hr, c.E, c.k, (const T *)w.Wr1, (const T *)w.br1,
                                                  (const T *)w.Wr2, (const T *)w.br2, nz, v.sigma, v.inv_tau, du, rate, idx, inv,
-                                                 dpk, dxrow, (T *)d_h, P.slices_per_block, rpart);
+                                                 dpk, v.capg, dxrow, (T *)d_h, P.slices_per_block, rpart);
     } else {
         bwd_router_kernel<T, false><<<rgrid, kBwdThreads, lds_r, s>>>(
             (const T *)h, Ns, ds, c.Hr, c.E, c.k, (const T *)w.Wr1, (const T *)w.br1, (const T *)w.Wr2, (const T *)w.br2,
-            nz, v.sigma, v.inv_tau, du, rate, idx, inv, dpk, dxrow, (T *)d_h, P.slices_per_block, rpart);
+            nz, v.sigma, v.inv_tau, du, rate, idx, inv, dpk, v.capg, dxrow, (T *)d_h, P.slices_per_block, rpart);
     }
     if ((e = hipGetLastError()) != hipSuccess) return e;
     }

@@ -62,7 +62,7 @@ __global__ __launch_bounds__(kRbThreads) void bwd_route_logits_mfma_kernel(
     const bf16_t *__restrict__ x, long long Ns, int E, int k, const char *__restrict__ packed, RouterBwdPacked L,
     const float *__restrict__ noise, float sigma, float inv_tau, const float *__restrict__ drop_u, float rate,
     const int32_t *__restrict__ idx, const int32_t *__restrict__ inv, const float *__restrict__ dpk,
-    bf16_t *__restrict__ dg_hi, bf16_t *__restrict__ dg_lo, uint32_t *__restrict__ relu_bits)
+    const float *__restrict__ capg, bf16_t *__restrict__ dg_hi, bf16_t *__restrict__ dg_lo, uint32_t *__restrict__ relu_bits)
 {
     constexpr int KS = DS / 16, EP = ET * 32;
     extern __shared__ __align__(16) char lds[];
@@ -183,7 +183,8 @@ __global__ __launch_bounds__(kRbThreads) void bwd_route_logits_mfma_kernel(
 #pragma unroll
                 for (int i = 0; i < ET * 16; ++i) mine = (i >> 4) * 32 + acc_feature(i & 15, g) == ej[jj] ? v[i] : mine;
                 psel[jj] = mine + __shfl_xor(mine, 32);   // the expert sits in one of the two halves
-                dpf[jj] = inv[a] >= 0 ? dpk[a] : 0.f;     // a capacity-dropped assignment carries no gradient
+                dpf[jj] = inv[a] >= 0 ? dpk[a] : 0.f;     // a capacity-dropped assignment carries no gradient from h'
+                if (capg != nullptr) dpf[jj] += capg[min(max(ej[jj], 0), E - 1)];   // but it counts as assigned (capacity loss)
                 keep[jj] = rate > 0.f ? !(drop_u[a] < rate) : true;
                 kept += keep[jj] ? 1 : 0;
             }
@@ -576,7 +577,7 @@ static hipError_t run_router_mfma(const slicemoe_config &c, const RouterBwdPacke
     if (blocks > units) blocks = units;
     lk<<<(int)blocks, kRbThreads, logits_lds(DS, ET), s>>>((const bf16_t *)h, Ns, c.E, c.k, pb, L, v.sigma > 0.f ? v.noise : nullptr,
                                                            v.sigma, v.inv_tau, rate > 0.f ? drop_u : nullptr, rate, idx, inv, dpk,
-                                                           dg_hi, dg_lo, bits);
+                                                           v.capg, dg_hi, dg_lo, bits);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     auto ik = bwd_route_inputs_mfma_kernel<DS, ET>;
     if ((e = grant_dynamic_lds((const void *)ik, inputs_lds(DS, ET))) != hipSuccess) return e;

@@ -110,6 +110,10 @@ struct RouteVariant {
     float inv_tau = 1.f;             // softmax of g / tau
     float sigma = 0.f;               // g += sigma * noise[n, e] before the selection and the softmax
     const float *noise = nullptr;    // [Ns, E] standard-normal draws; read only when sigma > 0
+    // backward only: weight of the capacity loss's differentiable reading (0: none), and, once the backward has
+    // computed it, the device table [E] of its derivatives with respect to each expert's probability sum
+    float cap_alpha = 0.f;
+    const float *capg = nullptr;
 };
 hipError_t launch_route_generic(const slicemoe_config &c, const void *h, const slicemoe_weights &w,
                                 int32_t *idx, float *p, hipStream_t s, const RouteVariant &v = RouteVariant());
@@ -124,7 +128,7 @@ struct BackwardPlan {
     long long chunks;              // its grid.x (an upper bound on the chunks in use)
     int slices_per_block;          // slices per block of the router kernel (its slot of partial weight gradients)
     long long slice_blocks;        // grid.x of the router kernel
-    size_t dxrow, dpk, expert_part, router_part, packed, router_scratch, total;   // byte offsets into the workspace, total size
+    size_t dxrow, dpk, expert_part, router_part, packed, router_scratch, cap, total;   // byte offsets into the workspace, total size
 };
 BackwardPlan backward_plan(const slicemoe_config &c);
 // Matrix-core expert backward (backward_mfma.hip): shapes it takes, bytes of its repacked weights, and the launch

@@ -90,13 +90,15 @@ def test_train_router_parameter_checks(B):
         assert call(None, None, None) == B.SLICEMOE_ERR_INVALID_ARG
         for bad in (P(0.0, 0.0, 0.0), P(-1.0, 0.0, 0.0), P(float("nan"), 0.0, 0.0), P(float("inf"), 0.0, 0.0),
                     P(1.0, -0.1, 0.0), P(1.0, float("nan"), 0.0), P(1.0, 0.0, 1.0), P(1.0, 0.0, -0.1),
-                    P(1.0, 0.0, float("nan"))):
+                    P(1.0, 0.0, float("nan")), P(1.0, 0.0, 0.0, float("nan")), P(1.0, 0.0, 0.0, float("inf"))):
             assert call(ctypes.byref(bad), one, one) == B.SLICEMOE_ERR_INVALID_ARG
         assert call(ctypes.byref(P(1.0, 0.5, 0.0)), None, None) == B.SLICEMOE_ERR_INVALID_ARG   # noise table missing
         assert call(ctypes.byref(P(1.0, 0.5, 0.0)), odd, None) == B.SLICEMOE_ERR_INVALID_ARG    # misaligned
         assert call(ctypes.byref(P(1.0, 0.0, 0.2)), None, None) == B.SLICEMOE_ERR_INVALID_ARG   # drop_u missing
     # valid parameters get as far as the workspace check of the whole-layer call
     assert forward(ctypes.byref(P(0.7, 0.5, 0.2)), one, one) == B.SLICEMOE_ERR_WORKSPACE
+    assert forward(ctypes.byref(P(0.7, 0.5, 0.2, -0.1)), one, one) == B.SLICEMOE_ERR_WORKSPACE   # any finite weight
+    assert ctypes.sizeof(P) == 16
     bad_cfg = B.make_config(8, 100, 3, 2, 4, 16)
     assert L.slicemoe_route_train(ctypes.byref(bad_cfg), one, ctypes.byref(w), ctypes.byref(P(1.0, 0.0, 0.0)), None, None,
                                   one, one, None, 0, None) == B.SLICEMOE_ERR_INVALID_ARG

@@ -73,6 +73,16 @@ CASES = {
     "headline_full": (wl.CONFIGS["headline"], None, None, "ties"),
     "paper_full": (wl.CONFIGS["paper"], None, dict(tau=1.0, sigma=0.0, rate=0.2), "ties"),
     "k3": (wl.SliceMoEShape("k3", T=150, d=256, S=4, E=8, k=3, He=96), None, dict(tau=0.7, sigma=0.0, rate=0.3)),
+    # with the gradient of the capacity loss's differentiable reading (Section 3.2), weighted so that it is of the size
+    # of the gradient that arrives through h': matrix-core and vector-ALU router kernels, dropout, capacity drops
+    # (a dropped assignment receives this term and no other), two expert tiles, three experts per slice
+    "headline_cap": (wl.CONFIGS["headline"], 130, dict(alpha=15.0)),
+    "headline_train_cap": (wl.CONFIGS["headline"], 96, dict(tau=1.5, sigma=0.2, rate=0.2, alpha=400.0)),
+    "skewed_cap": (wl.CONFIGS["skewed"], 256, dict(alpha=8.0)),
+    "tiny_train_cap": (wl.CONFIGS["tiny"], 61, dict(tau=0.8, sigma=0.3, rate=0.25, alpha=600.0)),
+    "E40_cap": (wl.SliceMoEShape("E40", T=700, d=256, S=4, E=40, k=2, He=128), None, dict(tau=1.3, sigma=0.2, rate=0.2, alpha=600.0)),
+    "k3_cap": (wl.SliceMoEShape("k3", T=150, d=256, S=4, E=8, k=3, He=96), None, dict(tau=0.7, sigma=0.0, rate=0.3, alpha=400.0)),
+    "headline_generic_cap": (wl.CONFIGS["headline"], 130, dict(alpha=15.0), "generic"),
 }
 
 
@@ -90,8 +100,16 @@ def test_backward_matches_oracle(B, name):
     okw = dict(tau=1.0, sigma=0.0, rate=0.0)
     if train:
         okw.update(train)
+    alpha = okw.pop("alpha", 0.0)
     ref_f = oracle.forward_train(h, shape.S, shape.k, w, noise=noise, drop_u=drop_u, capacity=shape.capacity(), **okw)
-    ref = oracle.backward(h, shape.S, shape.k, w, dout, ref_f["idx"], ref_f["inv"], noise=noise, drop_u=drop_u, **okw)
+    capg = oracle.capacity_surrogate(ref_f["idx"], ref_f["pk"], shape.E, alpha)["grad"] if alpha else None
+    ref = oracle.backward(h, shape.S, shape.k, w, dout, ref_f["idx"], ref_f["inv"], noise=noise, drop_u=drop_u, capg=capg,
+                          **okw)
+    if alpha:   # the term is a visible part of what is compared
+        ref0 = oracle.backward(h, shape.S, shape.k, w, dout, ref_f["idx"], ref_f["inv"], noise=noise, drop_u=drop_u, **okw)
+        share = {n: rms(ref[n] - ref0[n]) / rms(ref[n]) for n in ("Wr1", "br1", "Wr2", "br2", "d_h")}
+        assert min(share[n] for n in ("Wr1", "br1", "Wr2", "br2")) > 0.05 and share["d_h"] > 0.005, share
+        print(f"\n[backward {name}] share of the capacity term in the gradients: " + " ".join(f"{n} {v:.2f}" for n, v in share.items()))
 
     wd = B.pack(cfg, B.weights_to_device(w, shape.dtype))
     ws = B.alloc_workspace(cfg)
@@ -103,6 +121,8 @@ def test_backward_matches_oracle(B, name):
         tkw = dict(temperature=okw["tau"], noise_std=okw["sigma"], dropout_rate=okw["rate"], noise=dev(noise),
                    drop_u=dev(drop_u))
         B.slicemoe_forward_train(cfg, hd, wd, out, ws, **tkw)
+        if alpha:
+            tkw["capacity_alpha"] = alpha   # read by the backward only
     else:
         B.slicemoe_forward(cfg, hd, wd, out, ws)
     grads = B.alloc_weight_grads(cfg)
@@ -280,13 +300,17 @@ def test_backward_large_workload_full_size_every_gradient(B):
     assert not failed, failed
 
 
-@pytest.mark.parametrize("which", ["headline", "ds128", "paper"])
+@pytest.mark.parametrize("which", ["headline", "ds128", "paper", "headline_cap"])
 def test_backward_is_reproducible_bit_for_bit(B, which):
     """Partial weight gradients are summed in a fixed order: two calls give identical bits (width 64: one wavefront per
-    hidden tile; widths 128 and 96: the wavefront pairs that trade operands through LDS)."""
+    hidden tile; widths 128 and 96: the wavefront pairs that trade operands through LDS).  The probability sums of the
+    capacity term are added as integers: with it, too, the bits repeat, and they differ from those without it."""
     import torch
-    if which == "headline":
+    train = None
+    if which.startswith("headline"):
         shape, h, w = make_inputs(wl.CONFIGS["headline"], 1500)
+        if which == "headline_cap":
+            train = dict(capacity_alpha=5.0)
     elif which == "paper":
         shape, h, w = make_inputs(wl.CONFIGS["paper"], 700)
     else:
@@ -303,12 +327,18 @@ def test_backward_is_reproducible_bit_for_bit(B, which):
         grads = B.alloc_weight_grads(cfg)
         d_h = torch.empty_like(hd)
         bws = torch.full((B.slicemoe_backward_workspace_bytes(cfg),), 0xFF, dtype=torch.uint8, device="cuda:0")  # scratch holds junk
-        B.slicemoe_backward(cfg, hd, wd, ws, dout, d_h, grads, bws)
+        B.slicemoe_backward(cfg, hd, wd, ws, dout, d_h, grads, bws, train=train)
         torch.cuda.synchronize()
         results.append(({n: t.cpu().numpy().copy() for n, t in grads.items()}, d_h.float().cpu().numpy()))
     for n in NAMES:
         np.testing.assert_array_equal(results[0][0][n], results[1][0][n], err_msg=n)
     np.testing.assert_array_equal(results[0][1], results[1][1])
+    if train:
+        grads = B.alloc_weight_grads(cfg)
+        B.slicemoe_backward(cfg, hd, wd, ws, dout, d_h, grads, bws)
+        torch.cuda.synchronize()
+        assert np.any(grads["Wr2"].cpu().numpy() != results[0][0]["Wr2"])
+        np.testing.assert_array_equal(grads["W2"].cpu().numpy(), results[0][0]["W2"])   # the experts do not see the term
 
 
 def test_backward_argument_checks_on_device(B):
