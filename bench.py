@@ -8,7 +8,7 @@ whole-layer tokens/s, the per-stage breakdown, the roofline of the dominant kern
 grouped expert FFN, matrix-core bound) and the CPU oracle timed on this machine's host cores.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload headline|lm|skewed|large|paper [--slices S] [--topk k]]
-                  [--train-router TAU,SIGMA,RATE]
+                  [--train-router TAU,SIGMA,RATE[,ALPHA]]
 """
 import argparse
 import json
@@ -89,9 +89,10 @@ def main():
     ap.add_argument("--workload", default="headline", choices=["lm", "headline", "skewed", "large", "paper"])
     ap.add_argument("--slices", type=int, default=8, help="S of the paper workload (its Table 2 sweep)")
     ap.add_argument("--topk", type=int, default=2, help="k of the paper workload (its Table 4 sweep)")
-    ap.add_argument("--train-router", default=None, metavar="TAU,SIGMA,RATE",
+    ap.add_argument("--train-router", default=None, metavar="TAU,SIGMA,RATE[,ALPHA]",
                     help="run the layer with the training-time router: softmax temperature, logit-noise std, "
-                         "cross-slice dropout rate (e.g. 1.0,0.1,0.2); the draws are seeded inputs resident in HBM")
+                         "cross-slice dropout rate (e.g. 1.0,0.1,0.2); the draws are seeded inputs resident in HBM. "
+                         "ALPHA: weight of the capacity loss's gradient in --backward (default 0: none)")
     ap.add_argument("--backward", action="store_true",
                     help="also time slicemoe_backward after the forward (reported under \"backward\"; the metric stays the forward)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -138,9 +139,9 @@ def main():
 
     train = None
     if args.train_router:
-        tau, sigma, rate = (float(v) for v in args.train_router.split(","))
+        tau, sigma, rate, alpha = ([float(v) for v in args.train_router.split(",")] + [0.0])[:4]
         noise_h, drop_h = wl.make_router_draws(shape)
-        train = dict(temperature=tau, noise_std=sigma, dropout_rate=rate,
+        train = dict(temperature=tau, noise_std=sigma, dropout_rate=rate, capacity_alpha=alpha,
                      noise=torch.from_numpy(noise_h).to(dev), drop_u=torch.from_numpy(drop_h).to(dev))
 
     def step(i):

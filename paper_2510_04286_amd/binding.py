@@ -295,11 +295,12 @@ def _train_args(cfg, temperature, noise_std, dropout_rate, noise, drop_u, capaci
 
 
 def slicemoe_route_train(cfg, h, w, topk_idx, topk_p, temperature=1.0, noise_std=0.0, dropout_rate=0.0, noise=None,
-                         drop_u=None, workspace=None, stream=None):
+                         drop_u=None, workspace=None, stream=None, capacity_alpha=0.0):
+    """capacity_alpha travels in the parameter struct; only slicemoe_backward reads it."""
     Ns = cfg.T * cfg.S
     wsp, wsb = _ws(workspace)
     ws = _weights(cfg, w)
-    tp, npt, upt = _train_args(cfg, temperature, noise_std, dropout_rate, noise, drop_u)
+    tp, npt, upt = _train_args(cfg, temperature, noise_std, dropout_rate, noise, drop_u, capacity_alpha)
     _check(lib().slicemoe_route_train(ctypes.byref(cfg), _ptr(h, _tdtype(cfg), cfg.T * cfg.d, "h"), ctypes.byref(ws),
                                       ctypes.byref(tp), npt, upt, _ptr(topk_idx, torch.int32, Ns * cfg.k, "topk_idx"),
                                       _ptr(topk_p, torch.float32, Ns * cfg.k, "topk_p"), wsp, wsb, _stream(stream)),
@@ -307,10 +308,11 @@ def slicemoe_route_train(cfg, h, w, topk_idx, topk_p, temperature=1.0, noise_std
 
 
 def slicemoe_forward_train(cfg, h, w, h_out, workspace, temperature=1.0, noise_std=0.0, dropout_rate=0.0, noise=None,
-                           drop_u=None, stream=None):
+                           drop_u=None, stream=None, capacity_alpha=0.0):
+    """capacity_alpha travels in the parameter struct; only slicemoe_backward reads it."""
     wsp, wsb = _ws(workspace)
     ws = _weights(cfg, w)
-    tp, npt, upt = _train_args(cfg, temperature, noise_std, dropout_rate, noise, drop_u)
+    tp, npt, upt = _train_args(cfg, temperature, noise_std, dropout_rate, noise, drop_u, capacity_alpha)
     _check(lib().slicemoe_forward_train(ctypes.byref(cfg), _ptr(h, _tdtype(cfg), cfg.T * cfg.d, "h"), ctypes.byref(ws),
                                         ctypes.byref(tp), npt, upt, _ptr(h_out, _tdtype(cfg), cfg.T * cfg.d, "h_out"),
                                         wsp, wsb, _stream(stream)), "slicemoe_forward_train")
