@@ -286,8 +286,8 @@ slicemoe_status slicemoe_forward_train(const slicemoe_config *cfg, const void *h
  *   d_out [T, d] in      dL/dh', storage dtype
  *   d_h   [T, d] out     dL/dh, storage dtype (one rounding)
  *   grads       out      one fp32 DEVICE array per weight tensor, logical layout, overwritten.  Partial sums are
- *                        added in a fixed order: same inputs, bit-identical weight gradients (and dL/dh, unless
- *                        He > 256, where the hidden units are cut into groups whose parts of dL/dx are added atomically).
+ *                        added in a fixed order: same inputs, bit-identical weight gradients and dL/dh, on every
+ *                        path (no floating-point atomics anywhere in the backward).
  *   workspace            >= slicemoe_backward_workspace_bytes(cfg), 256-byte aligned
  * For bf16 storage with d/S in {64, 96, 128} and He % 32 == 0 (slicemoe_backward_uses_mfma: 1, 0, or -1 for an
  * invalid config) the expert part (row gradients, dL/dp, expert weight gradients) runs on the matrix cores, and with

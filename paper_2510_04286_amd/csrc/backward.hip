@@ -71,7 +71,7 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_expert_kernel(
     const T *__restrict__ x, const T *__restrict__ dout, const float *__restrict__ pk,
     const int32_t *__restrict__ offsets, const int32_t *__restrict__ perm, int ds, int He, int E, int k,
     const T *__restrict__ W1, const T *__restrict__ b1, const T *__restrict__ W2,
-    float *__restrict__ dxrow, float *__restrict__ dpk, int rows_per_chunk, float *__restrict__ part)
+    float *__restrict__ dxrow, float *__restrict__ dpk, int rows_per_chunk, int hidden_groups, float *__restrict__ part)
 {
     extern __shared__ float smem[];
     const int dsp = (ds + kBwdCols - 1) / kBwdCols * kBwdCols;   // LDS row stride: whole feature chunks, zero-padded
@@ -110,17 +110,21 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_expert_kernel(
     const int e = blk[0], row_begin = blk[1], row_end = blk[2];
     if (e < 0) return;   // grid is sized for the worst case; uniform over the block
 
-    const int j = (int)blockIdx.y * kBwdThreads + tid;        // hidden unit of this thread
-    const bool jok = j < He;
     const int c0 = (int)blockIdx.z * kBwdCols;                // first slice feature of this chunk
     const int ncols = min(kBwdCols, ds - c0);
-    const bool atomic_rows = gridDim.y > 1;                   // several hidden groups add into dL/dx and dL/dp
     const T *w1 = W1 + (size_t)e * ds * He;
     const T *w2 = W2 + (size_t)e * He * ds;
-    const float bias = jok ? Storage<T>::load(b1 + (size_t)e * He + j) : 0.f;
-    const int jg0 = (int)blockIdx.y * kBwdThreads;
     const int ds4 = (ds + 3) & ~3;
-    if (WLDS) {   // ordered before the first read by the barriers at the top of the row loop
+    float *slot = part + (size_t)blockIdx.x * expert_slot_floats(ds, He);
+    // The hidden units are taken in groups of one per thread, one group after the other by the same block: the parts of
+    // dL/dx and dL/dp that the groups contribute are added by the same thread in the same order on every run.
+    for (int grp = 0; grp < hidden_groups; ++grp) {
+    const int j = grp * kBwdThreads + tid;                    // hidden unit of this thread
+    const bool jok = j < He;
+    const float bias = jok ? Storage<T>::load(b1 + (size_t)e * He + j) : 0.f;
+    const int jg0 = grp * kBwdThreads;
+    if (WLDS) {   // ordered before the first read by the barriers at the top of the row loop (and after the last read of
+                  // the previous group by the barrier at its end)
         for (int t = tid; t < ds * kBwdThreads; t += kBwdThreads) {
             const int i = t / kBwdThreads, jj = t - i * kBwdThreads;
             w1s[i * w1st + jj] = jg0 + jj < He ? w1[(size_t)i * He + jg0 + jj] : (T)0;
@@ -217,34 +221,31 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_expert_kernel(
             const float part = wave_sum(dz * u[r]);   // dL/dp = sum over hidden units of dL/dz (x W1)
             if ((tid & 63) == 0) dps[tid >> 6][r] = part;   // added up below in a fixed order
         }
-        if (blockIdx.y == 0 && tid < ncols)
+        if (grp == 0 && tid < ncols)
             for (int r = 0; r < rows; ++r) ab2 += gs[r * dsp + c0 + tid];
         __syncthreads();
 
         // dL/dx of the rows, this chunk's features: p * sum over this hidden group of dL/dz W1[i, j]
-        const int jcount = min(kBwdThreads, He - (int)blockIdx.y * kBwdThreads);
+        const int jcount = min(kBwdThreads, He - grp * kBwdThreads);
         for (int t = tid; t < rows * ncols; t += kBwdThreads) {
             const int r = t / ncols, i = c0 + (t - r * ncols);
             float acc = 0.f;
 #pragma unroll 8
             for (int jj = 0; jj < jcount; ++jj) acc = fmaf(dzs[r * kBwdThreads + jj], w1_at(i, jj), acc);
-            float *dst = dxrow + (size_t)(r0 + r) * ds + i;
-            if (atomic_rows) atomicAdd(dst, ps[r] * acc);
-            else *dst = ps[r] * acc;
+            float *dst = dxrow + (size_t)(r0 + r) * ds + i;   // the same thread wrote it for the groups before
+            *dst = grp > 0 ? *dst + ps[r] * acc : ps[r] * acc;
         }
         if (blockIdx.z == 0 && tid < rows) {
             float dp = 0.f;
 #pragma unroll
             for (int wv = 0; wv < kBwdThreads / 64; ++wv) dp += dps[wv][tid];
-            if (atomic_rows) atomicAdd(dpk + as[tid], dp);
-            else dpk[as[tid]] = dp;
+            dpk[as[tid]] = grp > 0 ? dpk[as[tid]] + dp : dp;
         }
         __syncthreads();
     }
 
     // this chunk's slot: dW1 [ds][He] | dW2 [He][ds] | db1 [He] | db2 [ds]; the blocks of the chunk (hidden groups x
     // feature chunks) write disjoint parts of it, every element exactly once
-    float *slot = part + (size_t)blockIdx.x * expert_slot_floats(ds, He);
     float *pW1 = slot, *pW2 = pW1 + (size_t)ds * He, *pb1 = pW2 + (size_t)He * ds, *pb2 = pb1 + He;
     if (jok) {
 #pragma unroll
@@ -255,7 +256,8 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_expert_kernel(
             }
         if (blockIdx.z == 0) pb1[j] = ab1;
     }
-    if (blockIdx.y == 0 && tid < ncols) pb2[c0 + tid] = ab2;
+    if (grp == 0 && tid < ncols) pb2[c0 + tid] = ab2;
+    }
 }
 
 // Sum of the chunk slots of each expert in a fixed order: grid (E, pieces of 64 slot elements); a block is 64 elements
@@ -658,10 +660,6 @@ static hipError_t run_backward(const slicemoe_config &c, const void *h, const sl
 
     const int hidden_groups = (c.He + kBwdThreads - 1) / kBwdThreads;
     const int col_chunks = (ds + kBwdCols - 1) / kBwdCols;
-    if (hidden_groups > 1 && !backward_mfma_shape(c)) {   // partial sums over the hidden groups are added atomically
-        if ((e = zero_fill(dxrow, (size_t)Na * ds, s)) != hipSuccess) return e;
-        if ((e = zero_fill(dpk, (size_t)Na, s)) != hipSuccess) return e;
-    }
     const size_t eslot = expert_slot_floats(ds, c.He);
     if (backward_mfma_shape(c)) {
         e = launch_backward_expert_mfma(c, h, w, d_out, pk, offsets, perm, ws + P.packed, P.rows_per_chunk, P.chunks, eslot,
@@ -671,18 +669,18 @@ static hipError_t run_backward(const slicemoe_config &c, const void *h, const sl
     const size_t dsp = (size_t)(ds + kBwdCols - 1) / kBwdCols * kBwdCols;
     const size_t lds_e = sizeof(float) * (2 * (size_t)kBwdRB * dsp + (size_t)kBwdRB * kBwdThreads);
     const size_t lds_ew = lds_e + sizeof(T) * ((size_t)ds * (kBwdThreads + kWPad<T>) + (size_t)kBwdThreads * (ds + kWPad<T>));
-    const dim3 egrid((unsigned)P.chunks, hidden_groups, col_chunks);
+    const dim3 egrid((unsigned)P.chunks, 1, col_chunks);   // the hidden groups are a loop inside the block
     if (lds_ew <= (size_t)max_lds_per_block()) {
         auto kern = bwd_expert_kernel<T, true>;
         if ((e = grant_dynamic_lds((const void *)kern, lds_ew)) != hipSuccess)
             return e;
         kern<<<egrid, kBwdThreads, lds_ew, s>>>((const T *)h, (const T *)d_out, pk, offsets, perm, ds, c.He, c.E, c.k,
                                                  (const T *)w.W1, (const T *)w.b1, (const T *)w.W2, dxrow, dpk,
-                                                 P.rows_per_chunk, epart);
+                                                 P.rows_per_chunk, hidden_groups, epart);
     } else {
         bwd_expert_kernel<T, false><<<egrid, kBwdThreads, lds_e, s>>>(
             (const T *)h, (const T *)d_out, pk, offsets, perm, ds, c.He, c.E, c.k, (const T *)w.W1, (const T *)w.b1,
-            (const T *)w.W2, dxrow, dpk, P.rows_per_chunk, epart);
+            (const T *)w.W2, dxrow, dpk, P.rows_per_chunk, hidden_groups, epart);
     }
     if ((e = hipGetLastError()) != hipSuccess) return e;
     }

@@ -300,7 +300,7 @@ def test_backward_large_workload_full_size_every_gradient(B):
     assert not failed, failed
 
 
-@pytest.mark.parametrize("which", ["headline", "ds128", "paper", "headline_cap"])
+@pytest.mark.parametrize("which", ["headline", "ds128", "paper", "headline_cap", "generic_three_hidden_groups"])
 def test_backward_is_reproducible_bit_for_bit(B, which):
     """Partial weight gradients are summed in a fixed order: two calls give identical bits (width 64: one wavefront per
     hidden tile; widths 128 and 96: the wavefront pairs that trade operands through LDS).  The probability sums of the
@@ -313,13 +313,15 @@ def test_backward_is_reproducible_bit_for_bit(B, which):
             train = dict(capacity_alpha=5.0)
     elif which == "paper":
         shape, h, w = make_inputs(wl.CONFIGS["paper"], 700)
+    elif which == "generic_three_hidden_groups":   # vector-ALU kernels, He = 640: 256 + 256 + 128 hidden units, in turn
+        shape, h, w = make_inputs(wl.SliceMoEShape("g640", T=200, d=128, S=2, E=4, k=2, He=640, dtype="f32"), None)
     else:
         shape, h, w = make_inputs(wl.SliceMoEShape("ds128r", T=900, d=512, S=4, E=8, k=2, He=160), None)
     cfg = B.config_of(shape)
     wd = B.pack(cfg, B.weights_to_device(w, shape.dtype))
     ws = B.alloc_workspace(cfg)
     hd = B.to_device(h, shape.dtype)
-    out = torch.empty((shape.T, shape.d), dtype=torch.bfloat16, device="cuda:0")
+    out = torch.empty_like(hd)
     B.slicemoe_forward(cfg, hd, wd, out, ws)
     dout = B.to_device(wl.make_dout(shape), shape.dtype)
     results = []
