@@ -27,8 +27,8 @@ PEAK_HBM_GBS = 8000.0           # MI355X HBM3E
 # the same counter reads for a copy kernel of known size), per workload, with the summary under profiles/ that holds
 # the run; a workload without a measurement of the current kernel reports null.
 FFN_TRAFFIC_BYTES = {
-    "headline": {"bytes": 115079285, "profile": "profiles/headline_forward_backward_hbm_traffic.md"},
-    "large": {"bytes": 2602939988, "profile": "profiles/large_forward_backward_hbm_traffic.md"},
+    "headline": {"bytes": 114770875, "profile": "profiles/headline_forward_backward_hbm_traffic.md"},
+    "large": {"bytes": 2602585553, "profile": "profiles/large_forward_backward_hbm_traffic.md"},
 }
 NEAR_TIE = 1e-6   # routing differences below this logit gap (fp32) are near-ties: counted, not errors
 
