@@ -256,3 +256,53 @@ def test_forward_is_deterministic(B):
     np.testing.assert_array_equal(a, b)
     for name in ("topk_idx", "perm", "inv", "counts"):
         np.testing.assert_array_equal(wa[name], wb[name])
+
+
+def test_forward_and_backward_captured_in_a_hip_graph_replay_identically(B):
+    """The entry points only launch kernels on the caller's stream (no allocation, no memset, no host wait), so after one
+    eager call (which sets the kernels' LDS attributes) a caller may capture them in a HIP graph.  Every replay is checked
+    against the eager result for the inputs then in the captured buffers, with the program's own eager work and
+    synchronisations between the replays."""
+    import torch
+    shape, h, w = make_inputs(wl.CONFIGS["headline"], 1024)
+    cfg = B.config_of(shape)
+    wd = B.pack(cfg, B.weights_to_device(w, shape.dtype))
+    hs = [B.to_device(wl.make_h(shape, seed=s), shape.dtype) for s in (1, 5, 9, 13)]
+    douts = [B.to_device(wl.make_dout(shape, seed=3 + i), shape.dtype) for i in range(4)]
+
+    def eager(hd, dd):
+        ws = B.alloc_workspace(cfg)
+        out = torch.empty_like(hd)
+        d_h = torch.empty_like(hd)
+        grads = B.alloc_weight_grads(cfg)
+        bws = torch.empty(B.slicemoe_backward_workspace_bytes(cfg), dtype=torch.uint8, device="cuda:0")
+        B.slicemoe_forward(cfg, hd, wd, out, ws)
+        B.slicemoe_backward(cfg, hd, wd, ws, dd, d_h, grads, bws)
+        torch.cuda.synchronize()
+        return out.float().cpu().numpy(), d_h.float().cpu().numpy(), {n: t.cpu().numpy() for n, t in grads.items()}
+
+    refs = [eager(hd, dd) for hd, dd in zip(hs, douts)]   # (also the warm-up calls)
+
+    h_in, d_in = torch.empty_like(hs[0]), torch.empty_like(douts[0])
+    out, d_h = torch.empty_like(h_in), torch.empty_like(h_in)
+    ws = B.alloc_workspace(cfg)
+    grads = B.alloc_weight_grads(cfg)
+    bws = torch.empty(B.slicemoe_backward_workspace_bytes(cfg), dtype=torch.uint8, device="cuda:0")
+    h_in.copy_(hs[0])
+    d_in.copy_(douts[0])
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.slicemoe_forward(cfg, h_in, wd, out, ws)
+        B.slicemoe_backward(cfg, h_in, wd, ws, d_in, d_h, grads, bws)
+    for i in (1, 2, 3, 0, 2):
+        h_in.copy_(hs[i])
+        d_in.copy_(douts[i])
+        out.fill_(3.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(out.float().cpu().numpy(), refs[i][0], err_msg=f"h' of replay with input {i}")
+        np.testing.assert_array_equal(d_h.float().cpu().numpy(), refs[i][1], err_msg=f"dL/dh of replay with input {i}")
+        for n, t in grads.items():
+            np.testing.assert_array_equal(t.cpu().numpy(), refs[i][2][n], err_msg=f"{n} of replay with input {i}")
+        _ = eager(hs[(i + 1) % 4], douts[i])   # eager work between the replays
