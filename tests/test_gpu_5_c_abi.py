@@ -9,7 +9,13 @@ EXE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "c_abi", "abi_con
 
 
 def run(*args):
-    assert os.path.exists(EXE), "tests/c_abi/abi_consumer is not built: run __graft_entry__.build()"
+    if not os.path.exists(EXE):   # built by __graft_entry__.build(); here only if nothing is built yet
+        import __graft_entry__
+        from paper_2510_04286_amd import binding
+        import oracle
+        binding.lib()
+        oracle.lib()
+        __graft_entry__.build_c_abi_consumer()
     r = subprocess.run([EXE, *args], capture_output=True, text=True, timeout=120)
     print(r.stdout, r.stderr)
     return r
