@@ -83,6 +83,8 @@ CASES = {
     "E40_cap": (wl.SliceMoEShape("E40", T=700, d=256, S=4, E=40, k=2, He=128), None, dict(tau=1.3, sigma=0.2, rate=0.2, alpha=600.0)),
     "k3_cap": (wl.SliceMoEShape("k3", T=150, d=256, S=4, E=8, k=3, He=96), None, dict(tau=0.7, sigma=0.0, rate=0.3, alpha=400.0)),
     "headline_generic_cap": (wl.CONFIGS["headline"], 130, dict(alpha=15.0), "generic"),
+    # at the full size: 524 288 probabilities into 32 exact integer sums (the term shrinks as 1 / slices, hence the weight)
+    "headline_full_cap": (wl.CONFIGS["headline"], None, dict(alpha=150.0), "ties"),
 }
 
 
@@ -108,7 +110,7 @@ def test_backward_matches_oracle(B, name):
     if alpha:   # the term is a visible part of what is compared
         ref0 = oracle.backward(h, shape.S, shape.k, w, dout, ref_f["idx"], ref_f["inv"], noise=noise, drop_u=drop_u, **okw)
         share = {n: rms(ref[n] - ref0[n]) / rms(ref[n]) for n in ("Wr1", "br1", "Wr2", "br2", "d_h")}
-        assert min(share[n] for n in ("Wr1", "br1", "Wr2", "br2")) > 0.05 and share["d_h"] > 0.005, share
+        assert min(share[n] for n in ("Wr1", "br1", "Wr2", "br2")) > 0.05 and share["d_h"] > 0.002, share
         print(f"\n[backward {name}] share of the capacity term in the gradients: " + " ".join(f"{n} {v:.2f}" for n, v in share.items()))
 
     wd = B.pack(cfg, B.weights_to_device(w, shape.dtype))
