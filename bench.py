@@ -24,12 +24,28 @@ METRIC = "SliceMoE layer fwd tokens/sec (bf16) + % of MFMA / HBM roofline per st
 PEAK_MFMA_BF16_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0           # MI355X HBM3E
 # HBM bytes per launch of the expert FFN kernel from rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, each scaled by what
-# the same counter reads for a copy kernel of known size), per workload, with the summary under profiles/ that holds
-# the run; a workload without a measurement of the current kernel reports null.
-FFN_TRAFFIC_BYTES = {
-    "headline": {"bytes": 114770875, "profile": "profiles/headline_forward_backward_hbm_traffic.md"},
-    "large": {"bytes": 2602585553, "profile": "profiles/large_forward_backward_hbm_traffic.md"},
+# the same counter reads for a copy kernel of known size): read from the committed summary of that run, so the figure
+# printed here is the profile's own; a workload without a summary reports null.
+FFN_TRAFFIC_PROFILE = {
+    "headline": "profiles/headline_forward_backward_hbm_traffic.md",
+    "large": "profiles/large_forward_backward_hbm_traffic.md",
 }
+
+
+def ffn_traffic_bytes(workload):
+    """(bytes per launch, summary it comes from) or (None, None)."""
+    import re
+    rel = FFN_TRAFFIC_PROFILE.get(workload)
+    if rel is None:
+        return None, None
+    try:
+        with open(os.path.join(ROOT, rel)) as f:
+            m = re.search(r"^Expert FFN[^:\n]*: (\d+) bytes per launch", f.read(), re.M)
+    except OSError:
+        return None, None
+    return (int(m.group(1)), rel) if m else (None, None)
+
+
 NEAR_TIE = 1e-6   # routing differences below this logit gap (fp32) are near-ties: counted, not errors
 
 
@@ -231,8 +247,8 @@ def main():
               else "ffn_resident_kernel" if resident else "ffn_streamed_kernel")
     roofline = {"kernel": kernel, "bound": "mfma", "achieved": round(achieved, 2),
                 "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_BF16_TFLOPS, 4),
-                "traffic": FFN_TRAFFIC_BYTES.get(args.workload, {}).get("bytes"),
-                "traffic_source": FFN_TRAFFIC_BYTES.get(args.workload, {}).get("profile"), "launch_us": round(t_ffn * 1e6, 2),
+                "traffic": ffn_traffic_bytes(args.workload)[0],
+                "traffic_source": ffn_traffic_bytes(args.workload)[1], "launch_us": round(t_ffn * 1e6, 2),
                 "flops_per_launch": flops["expert_ffn"], "hbm_bytes_algorithmic": bytes_["expert_ffn"]}
 
     backward = None
