@@ -8,7 +8,7 @@ whole-layer tokens/s, the per-stage breakdown, the roofline of the dominant kern
 grouped expert FFN, matrix-core bound) and the CPU oracle timed on this machine's host cores.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload headline|lm|skewed|large|paper [--slices S] [--topk k]]
-                  [--train-router TAU,SIGMA,RATE[,ALPHA]]
+                  [--train-router TAU,SIGMA,RATE[,ALPHA]] [--no-overlap]
 """
 import argparse
 import json
@@ -112,6 +112,9 @@ def main():
     ap.add_argument("--backward", action="store_true",
                     help="also time slicemoe_backward after the forward (reported under \"backward\"; the metric stays the forward)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="skip the extra measurement with independent batches on several streams (for kernel traces: "
+                         "kernels that run concurrently stretch each other's durations)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
@@ -183,23 +186,25 @@ def main():
     # memory-bound kernels then run under another's matrix-bound ones and the launch gaps are filled.  Reported
     # beside `value`, which stays the one-stream figure: inside a model consecutive layers depend on each other, and
     # only a caller with several micro-batches in flight gets this rate.
-    nstreams = 3 if nsets >= 3 else 2
-    among = nsets - nsets % nstreams
-    streams = [torch.cuda.Stream(device=dev) for _ in range(nstreams)]
-    for st in streams:
-        st.wait_stream(torch.cuda.current_stream())
-    ksteps = max(nstreams, min(args.steps, 300))
-    for i in range(2 * nstreams):
-        step(i, streams[i % nstreams], among)
-    torch.cuda.synchronize()
-    o0 = time.perf_counter()
-    for i in range(ksteps):
-        step(i, streams[i % nstreams], among)
-    torch.cuda.synchronize()
-    o1 = time.perf_counter()
-    overlapped = {"streams": nstreams, "steps": ksteps, "ms_per_step": round((o1 - o0) * 1e3 / ksteps, 5),
-                  "value": round(shape.T / ((o1 - o0) / ksteps), 1), "unit": "tokens/s",
-                  "note": "independent batches issued round-robin on the streams; value above is the one-stream figure"}
+    overlapped = None
+    if not args.no_overlap:
+        nstreams = 3 if nsets >= 3 else 2
+        among = nsets - nsets % nstreams
+        streams = [torch.cuda.Stream(device=dev) for _ in range(nstreams)]
+        for st in streams:
+            st.wait_stream(torch.cuda.current_stream())
+        ksteps = max(nstreams, min(args.steps, 300))
+        for i in range(2 * nstreams):
+            step(i, streams[i % nstreams], among)
+        torch.cuda.synchronize()
+        o0 = time.perf_counter()
+        for i in range(ksteps):
+            step(i, streams[i % nstreams], among)
+        torch.cuda.synchronize()
+        o1 = time.perf_counter()
+        overlapped = {"streams": nstreams, "steps": ksteps, "ms_per_step": round((o1 - o0) * 1e3 / ksteps, 5),
+                      "value": round(shape.T / ((o1 - o0) / ksteps), 1), "unit": "tokens/s",
+                      "note": "independent batches issued round-robin on the streams; value above is the one-stream figure"}
 
     # ---- per-stage durations: the same launches through the stage entry points, with events on
     # the launch stream (torch's current stream) between them
