@@ -12,8 +12,10 @@
  * Conventions common to every entry point
  *   - Every pointer is caller-allocated DEVICE memory unless it is the config / weights
  *     struct itself (HOST).  The library never allocates, frees or keeps a pointer.
- *   - Every call only enqueues kernels on `stream` and returns; there is no hidden
- *     synchronisation and no device->host copy.  Same inputs give bit-identical outputs.
+ *   - Every call only enqueues kernels on `stream` and returns (slicemoe_backward forks one of
+ *     its kernels onto a stream of the library's own and joins it back, see there); there is
+ *     no host-side synchronisation and no device->host copy.  Same inputs give bit-identical
+ *     outputs.
  *   - Slice id n = t*S + s; because slices are contiguous, h[T, d] row-major IS the slice
  *     matrix x[Ns = T*S, ds].  Assignment id a = n*k + j for the j-th selected expert.
  *   - Linear layers are y = x W + b with W stored [in, out] row-major; expert tensors carry
@@ -289,6 +291,15 @@ slicemoe_status slicemoe_forward_train(const slicemoe_config *cfg, const void *h
  *                        added in a fixed order: same inputs, bit-identical weight gradients and dL/dh, on every
  *                        path (no floating-point atomics anywhere in the backward).
  *   workspace            >= slicemoe_backward_workspace_bytes(cfg), 256-byte aligned
+ *   stream               the call's place in this stream orders it against the caller's other work, as for every entry
+ *                        point.  On the matrix-core path the expert weight gradients (one kernel and its reduction,
+ *                        which the rest of the backward neither feeds nor needs) run on a second stream that the library
+ *                        owns (one per device, default priority, created at the first backward on the device and kept
+ *                        until the process ends): it is forked from `stream` after the weights are repacked and joined
+ *                        back into `stream` before the call returns, so everything the call writes is complete when the
+ *                        work the caller enqueues next on `stream` runs.  The pattern is a plain fork and join with two
+ *                        events, which a HIP graph capture of `stream` takes along (after one eager call has created
+ *                        the stream).  Calls from several host threads on one device are enqueued one after the other.
  * For bf16 storage with d/S in {64, 96, 128} and He % 32 == 0 (slicemoe_backward_uses_mfma: 1, 0, or -1 for an
  * invalid config) the expert part (row gradients, dL/dp, expert weight gradients) runs on the matrix cores, and with
  * Hr = 256 the router part too: fp32 pre-activations and derivatives, two-term bf16 operands

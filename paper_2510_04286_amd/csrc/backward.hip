@@ -14,12 +14,15 @@
 //                      recomputes the router, goes back through the dropout's renormalisation and the softmax to
 //                      dL/dg, accumulates the router's weight gradients the same way, and writes dL/dh = router path
 //                      + the k expert-path rows of the slice (the gather that mirrors the combine).
-// Wide shapes are cut over the grid: hidden units in groups of 256 (grid.y of the expert kernel; partial dL/dx and
-// dL/dp are then added atomically) and slice features in chunks of kBwdCols (grid.z / grid.y; every chunk recomputes
-// the shared quantities and owns its slice of the weight gradients and of dL/dx).
+// Wide shapes: hidden units are taken in groups of 256 that a block of the expert kernel works through in turn (the
+// same thread adds each group's part of dL/dx and dL/dp to what it wrote before: no atomics), and slice features are
+// cut over the grid in chunks of kBwdCols (grid.z / grid.y; every chunk recomputes the shared quantities and owns its
+// slice of the weight gradients and of dL/dx).
 // Weight gradients: every block stores its partial sums in its own slot of a scratch buffer, and a second pair of
 // kernels adds the slots up in a fixed order (device-wide atomic adds from a thousand blocks cost more than the
 // arithmetic, and their order varies from run to run; this way the result is reproducible bit for bit).
+#include <mutex>
+
 #include "common.h"
 
 namespace slicemoe {
@@ -619,6 +622,52 @@ __global__ __launch_bounds__(256) void bwd_cap_coeff_kernel(const unsigned long 
     }
 }
 
+// ---- A stream of the library's own, beside the caller's.  The expert weight gradients (their kernel and the
+// reduction after it) depend on nothing that the rest of the backward produces, and nothing but the caller depends on
+// them, so they run on this stream while the row gradients and the router's kernels run on the caller's: the two
+// chains fill each other's launch gaps and tails.  One stream and two events per device, made at the first backward on
+// that device and kept until the process ends; default priority, no implicit synchronisation with the null stream.
+// The events are shared by all calls on a device, so the enqueueing of one call (fork .. join) holds a lock.
+static std::mutex g_side_mutex;
+
+static hipError_t side_stream(SideStream *out)
+{
+    static SideStream set[64];
+    static bool have[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (!have[dev]) {
+        SideStream n = {};
+        if ((e = hipStreamCreateWithFlags(&n.stream, hipStreamNonBlocking)) != hipSuccess) return e;
+        if ((e = hipEventCreateWithFlags(&n.fork, hipEventDisableTiming)) != hipSuccess) return e;
+        if ((e = hipEventCreateWithFlags(&n.join, hipEventDisableTiming)) != hipSuccess) return e;
+        set[dev] = n;
+        have[dev] = true;
+    }
+    *out = set[dev];
+    return hipSuccess;
+}
+
+// Joins the side stream back into the caller's stream when the scope ends, on every path out of it.
+struct SideJoin {
+    const SideStream *side = nullptr;
+    hipStream_t s = nullptr;
+    hipError_t result = hipSuccess;
+    ~SideJoin() { (void)join(); }
+    hipError_t join()
+    {
+        if (side != nullptr) {
+            hipError_t e = hipEventRecord(side->join, side->stream);
+            if (e == hipSuccess) e = hipStreamWaitEvent(s, side->join, 0);
+            if (e != hipSuccess) result = e;
+            side = nullptr;
+        }
+        return result;
+    }
+};
+
 template <typename T>
 static hipError_t run_backward(const slicemoe_config &c, const void *h, const slicemoe_weights &w, const RouteVariant &v_in,
                                const float *drop_u, float rate, const int32_t *idx, const float *pk,
@@ -661,9 +710,18 @@ static hipError_t run_backward(const slicemoe_config &c, const void *h, const sl
     const int hidden_groups = (c.He + kBwdThreads - 1) / kBwdThreads;
     const int col_chunks = (ds + kBwdCols - 1) / kBwdCols;
     const size_t eslot = expert_slot_floats(ds, c.He);
+    std::unique_lock<std::mutex> side_lock(g_side_mutex, std::defer_lock);
+    SideStream side = {};
+    SideJoin joiner;
+    hipStream_t se = s;   // stream of the expert weight gradients and their reduction
     if (backward_mfma_shape(c)) {
+        side_lock.lock();
+        if ((e = side_stream(&side)) != hipSuccess) return e;
         e = launch_backward_expert_mfma(c, h, w, d_out, pk, offsets, perm, ws + P.packed, P.rows_per_chunk, P.chunks, eslot,
-                                        dxrow, dpk, epart, s);
+                                        dxrow, dpk, epart, s, &side);
+        joiner.side = &side;   // from here on the side stream holds work of this call: joined on every way out
+        joiner.s = s;
+        se = side.stream;
         if (e != hipSuccess) return e;
     } else {
     const size_t dsp = (size_t)(ds + kBwdCols - 1) / kBwdCols * kBwdCols;
@@ -687,10 +745,10 @@ static hipError_t run_backward(const slicemoe_config &c, const void *h, const sl
     const bool vec4 = ds % 4 == 0 && c.He % 4 == 0 &&
                       (((uintptr_t)g.W1 | (uintptr_t)g.b1 | (uintptr_t)g.W2 | (uintptr_t)g.b2 | (uintptr_t)epart) & 15) == 0;
     if (vec4)
-        bwd_reduce_expert_kernel<4><<<dim3((unsigned)c.E, (unsigned)((eslot / 4 + kRedElems - 1) / kRedElems)), kRedElems * kRedSeqs, 0, s>>>(
+        bwd_reduce_expert_kernel<4><<<dim3((unsigned)c.E, (unsigned)((eslot / 4 + kRedElems - 1) / kRedElems)), kRedElems * kRedSeqs, 0, se>>>(
             epart, offsets, ds, c.He, c.E, P.rows_per_chunk, g.W1, g.b1, g.W2, g.b2);
     else
-        bwd_reduce_expert_kernel<1><<<dim3((unsigned)c.E, (unsigned)((eslot + kRedElems - 1) / kRedElems)), kRedElems * kRedSeqs, 0, s>>>(
+        bwd_reduce_expert_kernel<1><<<dim3((unsigned)c.E, (unsigned)((eslot + kRedElems - 1) / kRedElems)), kRedElems * kRedSeqs, 0, se>>>(
             epart, offsets, ds, c.He, c.E, P.rows_per_chunk, g.W1, g.b1, g.W2, g.b2);
     if ((e = hipGetLastError()) != hipSuccess) return e;
 
@@ -720,7 +778,8 @@ static hipError_t run_backward(const slicemoe_config &c, const void *h, const sl
     }
     bwd_reduce_router_kernel<<<(unsigned)((rslot + kRedElems - 1) / kRedElems), kRedElems * kRedSeqs, 0, s>>>(rpart, (int)P.slice_blocks, ds, c.Hr, c.E, g.Wr1,
                                                                            g.br1, g.Wr2, g.br2);
-    return hipGetLastError();
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    return joiner.join();
 }
 
 hipError_t launch_backward(const slicemoe_config &c, const void *h, const slicemoe_weights &w, const RouteVariant &v,

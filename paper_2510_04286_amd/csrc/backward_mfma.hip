@@ -799,7 +799,7 @@ template <int DS>
 static hipError_t run_expert_mfma(const slicemoe_config &c, const BwdPacked &L, const void *h, const void *d_out,
                                   const float *pk, const int32_t *offsets, const int32_t *perm, const char *packed,
                                   int rows_per_chunk, long long chunks, size_t slot_floats, float *dxrow, float *dpk,
-                                  float *part, hipStream_t s)
+                                  float *part, hipStream_t s, hipStream_t sw /* stream of the weight-gradient kernel */)
 {
     const long long Na = (long long)c.T * c.S * c.k;
     const bf16_t *x = (const bf16_t *)h, *g = (const bf16_t *)d_out;
@@ -830,14 +830,14 @@ static hipError_t run_expert_mfma(const slicemoe_config &c, const BwdPacked &L, 
         const size_t lds_p = (size_t)2 * (DS / 16) * 1024 + 2 * 2 * 2 * 1024 + 2 * 2 * 8 * 64 * sizeof(float) + 64 * sizeof(float);
         auto pk2 = bwd_weights_pair_mfma_kernel<DS>;
         if ((e = grant_dynamic_lds((const void *)pk2, lds_p)) != hipSuccess) return e;
-        pk2<<<(unsigned)((chunks + 7) / 8 * 8 * HT), 128, lds_p, s>>>(x, g, pk, offsets, perm, packed, L.stride, L.w2r, L.b1, c.He, c.E, c.k,
+        pk2<<<(unsigned)((chunks + 7) / 8 * 8 * HT), 128, lds_p, sw>>>(x, g, pk, offsets, perm, packed, L.stride, L.w2r, L.b1, c.He, c.E, c.k,
                                                                    rows_per_chunk, slot_floats, part);
         return hipGetLastError();
     } else {
     const size_t lds_w = (size_t)2 * kBmWgWaves * (DS / 16) * 1024 + kBmWgWaves * 32 * sizeof(float);
     auto wk = bwd_weights_mfma_kernel<DS>;
     if ((e = grant_dynamic_lds((const void *)wk, lds_w)) != hipSuccess) return e;
-    wk<<<(unsigned)((chunks + 7) / 8 * 8 * ((HT + kBmWgWaves - 1) / kBmWgWaves)), kBmWgWaves * 64, lds_w, s>>>(
+    wk<<<(unsigned)((chunks + 7) / 8 * 8 * ((HT + kBmWgWaves - 1) / kBmWgWaves)), kBmWgWaves * 64, lds_w, sw>>>(
         x, g, pk, offsets, perm, packed, L.stride, L.w2r, L.b1, c.He, c.E, c.k, rows_per_chunk, slot_floats, part);
     return hipGetLastError();
     }
@@ -848,7 +848,7 @@ static hipError_t run_expert_mfma(const slicemoe_config &c, const BwdPacked &L, 
 hipError_t launch_backward_expert_mfma(const slicemoe_config &c, const void *h, const slicemoe_weights &w, const void *d_out,
                                        const float *pk, const int32_t *offsets, const int32_t *perm, void *packed,
                                        int rows_per_chunk, long long chunks, size_t slot_floats, float *dxrow, float *dpk,
-                                       float *part, hipStream_t s)
+                                       float *part, hipStream_t s, const SideStream *side)
 {
     if (!backward_mfma_shape(c) || rows_per_chunk % 32 != 0) return hipErrorInvalidValue;
     const int He = c.He, E = c.E, ds = c.d / c.S;
@@ -863,11 +863,17 @@ hipError_t launch_backward_expert_mfma(const slicemoe_config &c, const void *h, 
     // w1c: the [He, ds] matrix M[hidden][c] = W1[c][hidden], contraction over the hidden units in accumulator order
     jobs.job[2] = bwd_pack_job(kPackChain, w.W1, He, He, ds, ds, 1, (size_t)He, wstride, pb + L.w1c, L.stride, E);
     jobs.job[3] = bwd_pack_job(kPackBias, w.b1, He, He, He, He, 0, 0, (size_t)He, pb + L.b1, L.stride, E);
-    const hipError_t e = bwd_pack_launch(jobs, s);
+    hipError_t e = bwd_pack_launch(jobs, s);
     if (e != hipSuccess) return e;
-    if (ds == 64) return run_expert_mfma<64>(c, L, h, d_out, pk, offsets, perm, pb, rows_per_chunk, chunks, slot_floats, dxrow, dpk, part, s);
-    if (ds == 96) return run_expert_mfma<96>(c, L, h, d_out, pk, offsets, perm, pb, rows_per_chunk, chunks, slot_floats, dxrow, dpk, part, s);
-    return run_expert_mfma<128>(c, L, h, d_out, pk, offsets, perm, pb, rows_per_chunk, chunks, slot_floats, dxrow, dpk, part, s);
+    hipStream_t sw = s;
+    if (side != nullptr) {   // the weight-gradient kernel starts when the repacked weights are there
+        if ((e = hipEventRecord(side->fork, s)) != hipSuccess) return e;
+        if ((e = hipStreamWaitEvent(side->stream, side->fork, 0)) != hipSuccess) return e;
+        sw = side->stream;
+    }
+    if (ds == 64) return run_expert_mfma<64>(c, L, h, d_out, pk, offsets, perm, pb, rows_per_chunk, chunks, slot_floats, dxrow, dpk, part, s, sw);
+    if (ds == 96) return run_expert_mfma<96>(c, L, h, d_out, pk, offsets, perm, pb, rows_per_chunk, chunks, slot_floats, dxrow, dpk, part, s, sw);
+    return run_expert_mfma<128>(c, L, h, d_out, pk, offsets, perm, pb, rows_per_chunk, chunks, slot_floats, dxrow, dpk, part, s, sw);
 }
 
 }  // namespace slicemoe

@@ -145,10 +145,16 @@ hipError_t launch_backward_router_mfma(const slicemoe_config &c, const void *h, 
                                        const int32_t *inv, const float *dpk, const float *dxrow, void *d_h, void *scratch,
                                        int slices_per_block, long long slice_blocks, size_t slot_floats, float *part,
                                        hipStream_t s);
+// side (optional): a second stream with a fork event.  The weight-gradient kernel is then launched on side->stream, ordered
+// after the repacking on s by the event; the caller joins the stream back before anything reads `part`.
+struct SideStream {
+    hipStream_t stream;
+    hipEvent_t fork, join;
+};
 hipError_t launch_backward_expert_mfma(const slicemoe_config &c, const void *h, const slicemoe_weights &w, const void *d_out,
                                        const float *pk, const int32_t *offsets, const int32_t *perm, void *packed,
                                        int rows_per_chunk, long long chunks, size_t slot_floats, float *dxrow, float *dpk,
-                                       float *part, hipStream_t s);
+                                       float *part, hipStream_t s, const SideStream *side = nullptr);
 size_t backward_lds_bytes(const slicemoe_config &c);
 hipError_t launch_backward(const slicemoe_config &c, const void *h, const slicemoe_weights &w, const RouteVariant &v,
                            const float *drop_u, float rate, const int32_t *idx, const float *pk, const int32_t *offsets,

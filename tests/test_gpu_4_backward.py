@@ -367,3 +367,59 @@ def test_backward_argument_checks_on_device(B):
         with pytest.raises(B.SliceMoEError) as ei:
             B.slicemoe_backward(cfg, args[0], wd, ws, args[1], args[2], grads, bws)
         assert ei.value.status == B.SLICEMOE_ERR_INVALID_ARG
+
+
+def test_backward_from_two_host_threads_on_two_streams(B):
+    """The matrix-core backward forks part of its work onto a stream the library owns and shares between calls: two host
+    threads enqueueing on their own streams at the same time still get the bits of a call made alone."""
+    import threading
+    import torch
+    shape, h, w = make_inputs(wl.CONFIGS["headline"], 2048)
+    cfg = B.config_of(shape)
+    assert B.slicemoe_backward_uses_mfma(cfg) == 1
+    wd = B.pack(cfg, B.weights_to_device(w, shape.dtype))
+    douts = [B.to_device(wl.make_dout(shape, seed=3 + i), shape.dtype) for i in range(2)]
+    hs = [B.to_device(wl.make_h(shape, seed=1 + 4 * i), shape.dtype) for i in range(2)]
+
+    def buffers(hd):
+        return dict(ws=B.alloc_workspace(cfg), out=torch.empty_like(hd), d_h=torch.empty_like(hd), grads=B.alloc_weight_grads(cfg),
+                    bws=torch.empty(B.slicemoe_backward_workspace_bytes(cfg), dtype=torch.uint8, device="cuda:0"))
+
+    def result(b):
+        return b["d_h"].float().cpu().numpy(), {n: t.cpu().numpy() for n, t in b["grads"].items()}
+
+    alone = []
+    for hd, dd in zip(hs, douts):
+        b = buffers(hd)
+        B.slicemoe_forward(cfg, hd, wd, b["out"], b["ws"])
+        B.slicemoe_backward(cfg, hd, wd, b["ws"], dd, b["d_h"], b["grads"], b["bws"])
+        torch.cuda.synchronize()
+        alone.append(result(b))
+
+    bufs = [buffers(hd) for hd in hs]
+    streams = [torch.cuda.Stream() for _ in range(2)]
+    for st in streams:
+        st.wait_stream(torch.cuda.current_stream())
+    errors = []
+
+    def worker(i):
+        try:
+            for _ in range(8):
+                B.slicemoe_forward(cfg, hs[i], wd, bufs[i]["out"], bufs[i]["ws"], stream=streams[i])
+                B.slicemoe_backward(cfg, hs[i], wd, bufs[i]["ws"], douts[i], bufs[i]["d_h"], bufs[i]["grads"], bufs[i]["bws"],
+                                    stream=streams[i])
+        except Exception as exc:   # reported by the main thread
+            errors.append(exc)
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for i in range(2):
+        got_dh, got = result(bufs[i])
+        np.testing.assert_array_equal(got_dh, alone[i][0])
+        for n in NAMES:
+            np.testing.assert_array_equal(got[n], alone[i][1][n], err_msg=n)
