@@ -113,8 +113,8 @@ def main():
                     help="also time slicemoe_backward after the forward (reported under \"backward\"; the metric stays the forward)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true",
-                    help="skip the extra measurement with independent batches on several streams (for kernel traces: "
-                         "kernels that run concurrently stretch each other's durations)")
+                    help="skip the extra measurement with independent batches on several streams and keep the backward "
+                         "on one stream (for kernel traces: kernels that run concurrently stretch each other's durations)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
@@ -137,7 +137,8 @@ def main():
                 if l.split("#")[0].strip()]
         w["br2"] = np.array(vals, dtype=np.float32)
     h = wl.make_h(shape)
-    cfg = B.config_of(shape)
+    # profiling runs keep the backward's kernels on one stream too: concurrent kernels stretch each other's durations
+    cfg = B.config_of(shape, flags=B.SLICEMOE_FLAG_SINGLE_STREAM if args.no_overlap else 0)
     # every benchmark workload runs on the matrix-core kernels; of the paper's slice-count sweep, S = 4 and 8 do
     assert args.workload == "paper" or B.slicemoe_uses_mfma(cfg) == 1
     dev = "cuda:0"

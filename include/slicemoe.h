@@ -66,6 +66,7 @@ typedef enum { SLICEMOE_F32 = 0, SLICEMOE_BF16 = 1 } slicemoe_dtype;
 /* flags */
 #define SLICEMOE_FLAG_FORCE_GENERIC 1u /* never use the MFMA kernels (debug / cross-check)      */
 #define SLICEMOE_FLAG_REQUIRE_MFMA 2u  /* return UNSUPPORTED instead of using generic kernels   */
+#define SLICEMOE_FLAG_SINGLE_STREAM 4u /* slicemoe_backward keeps every kernel on `stream`      */
 
 /* Same handle type as hipStream_t, spelled out so this header needs no HIP include. */
 struct ihipStream_t;
@@ -300,6 +301,7 @@ slicemoe_status slicemoe_forward_train(const slicemoe_config *cfg, const void *h
  *                        work the caller enqueues next on `stream` runs.  The pattern is a plain fork and join with two
  *                        events, which a HIP graph capture of `stream` takes along (after one eager call has created
  *                        the stream).  Calls from several host threads on one device are enqueued one after the other.
+ *                        SLICEMOE_FLAG_SINGLE_STREAM keeps every kernel on `stream` (same results, a few percent slower).
  * For bf16 storage with d/S in {64, 96, 128} and He % 32 == 0 (slicemoe_backward_uses_mfma: 1, 0, or -1 for an
  * invalid config) the expert part (row gradients, dL/dp, expert weight gradients) runs on the matrix cores, and with
  * Hr = 256 the router part too: fp32 pre-activations and derivatives, two-term bf16 operands

@@ -23,6 +23,7 @@ SLICEMOE_F32 = 0
 SLICEMOE_BF16 = 1
 SLICEMOE_FLAG_FORCE_GENERIC = 1
 SLICEMOE_FLAG_REQUIRE_MFMA = 2
+SLICEMOE_FLAG_SINGLE_STREAM = 4
 
 EXPORTS = [
     "slicemoe_status_string", "slicemoe_uses_mfma", "slicemoe_capacity", "slicemoe_workspace_bytes",

@@ -714,7 +714,11 @@ static hipError_t run_backward(const slicemoe_config &c, const void *h, const sl
     SideStream side = {};
     SideJoin joiner;
     hipStream_t se = s;   // stream of the expert weight gradients and their reduction
-    if (backward_mfma_shape(c)) {
+    if (backward_mfma_shape(c) && (c.flags & SLICEMOE_FLAG_SINGLE_STREAM)) {
+        e = launch_backward_expert_mfma(c, h, w, d_out, pk, offsets, perm, ws + P.packed, P.rows_per_chunk, P.chunks, eslot,
+                                        dxrow, dpk, epart, s);
+        if (e != hipSuccess) return e;
+    } else if (backward_mfma_shape(c)) {
         side_lock.lock();
         if ((e = side_stream(&side)) != hipSuccess) return e;
         e = launch_backward_expert_mfma(c, h, w, d_out, pk, offsets, perm, ws + P.packed, P.rows_per_chunk, P.chunks, eslot,

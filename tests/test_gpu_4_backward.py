@@ -395,6 +395,16 @@ def test_backward_from_two_host_threads_on_two_streams(B):
         B.slicemoe_backward(cfg, hd, wd, b["ws"], dd, b["d_h"], b["grads"], b["bws"])
         torch.cuda.synchronize()
         alone.append(result(b))
+    # and with every kernel kept on the caller's stream: the same bits
+    cfg1 = B.config_of(shape, flags=B.SLICEMOE_FLAG_SINGLE_STREAM)
+    b = buffers(hs[0])
+    B.slicemoe_forward(cfg1, hs[0], wd, b["out"], b["ws"])
+    B.slicemoe_backward(cfg1, hs[0], wd, b["ws"], douts[0], b["d_h"], b["grads"], b["bws"])
+    torch.cuda.synchronize()
+    one_dh, one = result(b)
+    np.testing.assert_array_equal(one_dh, alone[0][0])
+    for n in NAMES:
+        np.testing.assert_array_equal(one[n], alone[0][1][n], err_msg=n)
 
     bufs = [buffers(hd) for hd in hs]
     streams = [torch.cuda.Stream() for _ in range(2)]
